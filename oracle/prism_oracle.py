@@ -1,0 +1,334 @@
+"""CPU oracle for the Prism hot path — TEST INFRASTRUCTURE, not a product path.
+
+Only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg may import
+this module.  It shares no code with the HIP library or its Python binding and
+imports neither; it is a plain, slow, fp64 NumPy statement of what the paper
+defines, written to be checked against the paper by eye.
+
+Two parts of different kinds:
+
+* Block selection (heuristic; the algorithm is its own definition): follows the
+  steps and notation of the paper's Sec. 3.4 "Prism: Spectral-Aware Block
+  Selection" (Fig. "PyTorch-style implementation of Prism") and App. C
+  "Top-P Block Selection":
+    pool -> band slices -> RMS -> temperatures -> dual-band logits ->
+    row softmax -> top-p -> union.
+* Block-masked causal attention (exact; has a plain definition): softmax over the
+  keys that are both causally visible and inside a selected block
+  (Sec. 2 "Block-Sparse Attention", Sec. 3.1 "Coarse-grained Attention" for the
+  1/sqrt(d) scale), and dense causal attention as the all-ones special case,
+  written as a separate function.
+
+Readings taken where the paper is silent (all listed in the design notes):
+  - bands are contiguous slices [0, d_h) and [d - d_l, d) of the adjacent-pair
+    RoPE layout; rms() is one scalar per head over all N blocks and the band's
+    dims; for grouped-query attention the key statistics are per kv head and
+    q-head hq uses kv-head hq // (h / h_kv);
+  - estimation is block-causal: logits of key blocks v > u are -inf before the
+    softmax; nothing (diagonal, sink) is forced;
+  - top-p ties: stable descending order (lower block index first);
+  - a band with d_z = 0 is skipped; zero band energy gives zero logits;
+  - p >= 1 selects every causal block.
+
+Pins (tests/test_oracle_*.py): Dirichlet-kernel closed form for pooled RoPE
+content (Eq. "attenuation"), printed cutoff dimensions, 1/sqrt(B) residual,
+tau = 1 when a band is the full head, brute-force top-p on tiny rows, naive
+triple-loop attention, all-ones mask == dense, torch SDPA in fp64.
+Exact mask values on random data are pinned by no printed example in the paper
+("parity unpinned" for the selection on random data beyond those invariants).
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Dict, List, Optional, Sequence, Tuple
+
+import numpy as np
+
+
+# --------------------------------------------------------------------------- #
+# input decoding
+# --------------------------------------------------------------------------- #
+def bf16_to_f64(bits: np.ndarray) -> np.ndarray:
+    """Exact value of bf16 bit patterns (uint16) as fp64."""
+    b = np.ascontiguousarray(bits)
+    if b.dtype != np.uint16:
+        raise TypeError("expected uint16 bf16 bit patterns")
+    return (b.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+
+
+# --------------------------------------------------------------------------- #
+# Part 1 — block selection, step by step (Sec. 3.4, App. C)
+# --------------------------------------------------------------------------- #
+def pool(X: np.ndarray, B: int) -> np.ndarray:
+    """Mean pooling, Eq. "mean-pooling": x_bar_u = (1/|I_u|) sum_{i in I_u} x_i.
+
+    X: [H, L, d] fp64 -> [H, N, d], N = ceil(L / B).  A ragged last block is
+    averaged over the tokens it actually holds."""
+    H, L, d = X.shape
+    N = -(-L // B)
+    out = np.empty((H, N, d), dtype=np.float64)
+    for u in range(N):
+        out[:, u, :] = X[:, u * B:min(L, (u + 1) * B), :].mean(axis=1)
+    return out
+
+
+def rms(Xb: np.ndarray) -> np.ndarray:
+    """RMS(X_bar) = sqrt( (1/N) sum_u ||x_bar_u||^2 / width ), one scalar per head
+    (Sec. 3.4 "Energy-Based Temperature Calibration").  Xb: [H, N, width]."""
+    H, N, width = Xb.shape
+    return np.sqrt((Xb ** 2).sum(axis=(1, 2)) / (N * width))
+
+
+def temperature(d_z: int, d: int, rq_z: np.ndarray, rq: np.ndarray,
+                rk_z: np.ndarray, rk: np.ndarray) -> np.ndarray:
+    """tau_z = sqrt(d_z/d) * (RMS(Qbar_z)/RMS(Qbar)) * (RMS(Kbar_z)/RMS(Kbar))."""
+    with np.errstate(divide="ignore", invalid="ignore"):
+        t = np.sqrt(d_z / d) * (rq_z / rq) * (rk_z / rk)
+    return t
+
+
+def softmax_rows(logits: np.ndarray) -> np.ndarray:
+    """Row softmax over the last axis; -inf entries get probability 0."""
+    m = logits.max(axis=-1, keepdims=True)
+    e = np.exp(logits - m)
+    return e / e.sum(axis=-1, keepdims=True)
+
+
+def top_p(probs: np.ndarray, p: float) -> np.ndarray:
+    """App. C: sort descending, cumulative sum, keep rank k while the mass
+    strictly before it is < p, scatter back.  probs: [..., N] -> bool [..., N].
+    Ties are ordered by a stable sort (lower index first)."""
+    order = np.argsort(-probs, axis=-1, kind="stable")
+    sorted_probs = np.take_along_axis(probs, order, axis=-1)
+    cumulative = np.cumsum(sorted_probs, axis=-1)
+    sorted_mask = (cumulative - sorted_probs) < p
+    mask = np.zeros(probs.shape, dtype=bool)
+    np.put_along_axis(mask, order, sorted_mask, axis=-1)
+    return mask
+
+
+@dataclass
+class Selection:
+    """Everything the selection produces for one call (all q-heads)."""
+    mask: np.ndarray                 # [h, N, N] bool, union of the bands
+    band_masks: Dict[str, np.ndarray]   # "high"/"low" -> [h, N, N] bool
+    logits: Dict[str, np.ndarray]    # "high"/"low" -> [h, N, N] fp64 (-inf above diagonal)
+    probs: Dict[str, np.ndarray]
+    tau: Dict[str, np.ndarray]       # [h]
+    scale: Dict[str, np.ndarray]     # sqrt(d_z) * tau_z, [h]
+    q_pooled: np.ndarray             # [h, N, d]
+    k_pooled: np.ndarray             # [h_kv, N, d]
+    rms_q: Dict[str, np.ndarray]     # "full"/"high"/"low" -> [h]
+    rms_k: Dict[str, np.ndarray]     # -> [h_kv]
+
+
+def prism_select(Q: np.ndarray, K: np.ndarray, d_h: int, d_l: int, B: int, p: float,
+                 causal: bool = True, calibrate: bool = True) -> Selection:
+    """Block mask of Sec. 3.4.  Q: [h, L, d] fp64, K: [h_kv, L, d] fp64."""
+    h, L, d = Q.shape
+    h_kv = K.shape[0]
+    if h % h_kv:
+        raise ValueError("n_q_heads must be a multiple of n_kv_heads")
+    g = h // h_kv
+    kv_of = np.arange(h) // g
+
+    # 1. pooling & slicing
+    Qb, Kb = pool(Q, B), pool(K, B)
+    N = Qb.shape[1]
+    bands = {"high": slice(0, d_h), "low": slice(d - d_l, d)}
+    width = {"high": d_h, "low": d_l}
+
+    # 2. RMS energies
+    rms_q = {"full": rms(Qb)}
+    rms_k = {"full": rms(Kb)}
+    for z, sl in bands.items():
+        if width[z] > 0:
+            rms_q[z] = rms(Qb[:, :, sl])
+            rms_k[z] = rms(Kb[:, :, sl])
+        else:
+            rms_q[z] = np.zeros(h)
+            rms_k[z] = np.zeros(h_kv)
+
+    tri = np.tril(np.ones((N, N), dtype=bool))
+    tau: Dict[str, np.ndarray] = {}
+    scale: Dict[str, np.ndarray] = {}
+    logits: Dict[str, np.ndarray] = {}
+    probs: Dict[str, np.ndarray] = {}
+    band_masks: Dict[str, np.ndarray] = {}
+    for z, sl in bands.items():
+        d_z = width[z]
+        if d_z == 0:                               # band disabled
+            tau[z] = np.full(h, np.nan)
+            scale[z] = np.full(h, np.nan)
+            logits[z] = np.full((h, N, N), -np.inf)
+            probs[z] = np.zeros((h, N, N))
+            band_masks[z] = np.zeros((h, N, N), dtype=bool)
+            continue
+        # 3. calibration
+        if calibrate:
+            tau[z] = temperature(d_z, d, rms_q[z], rms_q["full"],
+                                 rms_k[z][kv_of], rms_k["full"][kv_of])
+        else:
+            tau[z] = np.ones(h)
+        # 4. dual-band scoring
+        scale[z] = np.sqrt(d_z) * tau[z]
+        raw = np.einsum("hud,hvd->huv", Qb[:, :, sl], Kb[kv_of][:, :, sl])
+        lz = np.empty_like(raw)
+        for hq in range(h):
+            s = scale[z][hq]
+            if np.isfinite(s) and s > 0.0:
+                lz[hq] = raw[hq] / s
+            else:                                   # zero band energy -> flat logits
+                lz[hq] = 0.0
+        if causal:
+            lz = np.where(tri[None], lz, -np.inf)
+        logits[z] = lz
+        # 5. selection
+        probs[z] = softmax_rows(lz)
+        if p >= 1.0:
+            mz = np.ones((h, N, N), dtype=bool)
+        else:
+            mz = top_p(probs[z], p)
+        if causal:
+            mz &= tri[None]
+        band_masks[z] = mz
+
+    mask = band_masks["high"] | band_masks["low"]
+    return Selection(mask, band_masks, logits, probs, tau, scale, Qb, Kb, rms_q, rms_k)
+
+
+def mask_to_csr(mask: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+    """[h, N, N] bool -> (row_ptr int32 [h*N+1], col_idx int32 [nnz]); one row per
+    (head, q-block), columns ascending."""
+    h, N, _ = mask.shape
+    flat = mask.reshape(h * N, N)
+    counts = flat.sum(axis=1)
+    row_ptr = np.zeros(h * N + 1, dtype=np.int64)
+    np.cumsum(counts, out=row_ptr[1:])
+    col_idx = np.nonzero(flat)[1].astype(np.int32)
+    return row_ptr.astype(np.int32), col_idx
+
+
+@dataclass
+class Tolerance:
+    """Per-block verdict classes for comparing another implementation's mask."""
+    must: np.ndarray        # [h, N, N] bool — has to be selected
+    must_not: np.ndarray    # [h, N, N] bool — has to be unselected
+    # everything else is "don't care"
+
+    @property
+    def dont_care_fraction(self) -> float:
+        h, N, _ = self.must.shape
+        causal = h * N * (N + 1) // 2
+        tri = np.tril(np.ones((N, N), dtype=bool))[None]
+        dc = (~self.must) & (~self.must_not) & tri
+        return float(dc.sum()) / float(causal)
+
+
+def selection_tolerance(sel: Selection, p: float, logit_margin: float = 1e-3,
+                        p_margin: float = 1e-3) -> Tolerance:
+    """Blocks whose selection may legitimately differ in another implementation.
+
+    Per band and row the selected set is the top-k* blocks by score, the cutoff lying
+    between the lowest selected score l_in and the highest unselected score l_out.  A
+    block is "don't care" when
+      - it is selected and its score is within `logit_margin` of l_out, or it is
+        unselected and within `logit_margin` of l_in (a score error of that size could
+        swap it across the cutoff; exact ties fall here too), or
+      - it enters the set somewhere between p - p_margin and p + p_margin (the
+        cumulative mass at the cutoff is that close to p).
+    must = union over bands of (selected minus don't-care); must_not = complement of the
+    union over bands of (selected or don't-care)."""
+    h, N, _ = sel.mask.shape
+    tri = np.tril(np.ones((N, N), dtype=bool))[None]
+    keep = np.zeros((h, N, N), dtype=bool)       # union_z (M_z \ D_z)
+    cover = np.zeros((h, N, N), dtype=bool)      # union_z (M_z | D_z)
+    for z in ("high", "low"):
+        mz, lz, pz = sel.band_masks[z], sel.logits[z], sel.probs[z]
+        if not mz.any():
+            continue
+        l_in = np.where(mz, lz, np.inf).min(axis=-1, keepdims=True)
+        l_out = np.where((~mz) & tri, lz, -np.inf).max(axis=-1, keepdims=True)
+        with np.errstate(invalid="ignore"):
+            swap_out = mz & ((lz - l_out) <= logit_margin)
+            swap_in = (~mz) & tri & ((l_in - lz) <= logit_margin)
+        if p >= 1.0:
+            shell = np.zeros_like(mz)
+        else:
+            hi = top_p(pz, p + p_margin) if p + p_margin < 1.0 else np.broadcast_to(tri, mz.shape)
+            lo = top_p(pz, max(p - p_margin, 1e-12))
+            shell = hi & ~lo
+        dz = (swap_out | swap_in | shell) & tri
+        keep |= mz & ~dz
+        cover |= (mz | dz)
+    return Tolerance(must=keep, must_not=(~cover) | (~tri))
+
+
+# --------------------------------------------------------------------------- #
+# Part 2 — attention by its plain definition
+# --------------------------------------------------------------------------- #
+def block_sparse_attention_row(Qh: np.ndarray, Kh: np.ndarray, Vh: np.ndarray,
+                               u: int, blocks: Sequence[int], B: int
+                               ) -> Tuple[np.ndarray, np.ndarray]:
+    """One q-block of one head.  For token i in block u the visible set is
+    J(i) = { j <= i : block(j) in `blocks` }; o_i = sum_J softmax_J(q_i.k_j/sqrt(d)) v_j.
+    Qh/Kh/Vh: [L, d] fp64.  Returns (O [rows, d], lse [rows]); a token with an empty
+    visible set gets a zero output row and lse = -inf."""
+    L, d = Qh.shape
+    r0, r1 = u * B, min(L, (u + 1) * B)
+    rows = np.arange(r0, r1)
+    if len(blocks) == 0:
+        return np.zeros((r1 - r0, d)), np.full(r1 - r0, -np.inf)
+    cols = np.concatenate([np.arange(v * B, min(L, (v + 1) * B)) for v in blocks])
+    s = (Qh[r0:r1] @ Kh[cols].T) / np.sqrt(d)
+    s = np.where(cols[None, :] <= rows[:, None], s, -np.inf)
+    m = s.max(axis=1, keepdims=True)
+    out = np.zeros((r1 - r0, d))
+    lse = np.full(r1 - r0, -np.inf)
+    ok = np.isfinite(m[:, 0])
+    e = np.exp(s[ok] - m[ok])
+    den = e.sum(axis=1, keepdims=True)
+    out[ok] = (e / den) @ Vh[cols]
+    lse[ok] = m[ok, 0] + np.log(den[:, 0])
+    return out, lse
+
+
+def block_sparse_attention(Q: np.ndarray, K: np.ndarray, V: np.ndarray, mask: np.ndarray,
+                           B: int, rows: Optional[Sequence[Tuple[int, int]]] = None
+                           ) -> Dict[Tuple[int, int], Tuple[np.ndarray, np.ndarray]]:
+    """Block-masked causal attention for the listed (head, q-block) rows (all rows
+    when `rows` is None).  Q: [h, L, d]; K, V: [h_kv, L, d]; mask: [h, N, N] bool."""
+    h, L, d = Q.shape
+    g = h // K.shape[0]
+    N = mask.shape[1]
+    if rows is None:
+        rows = [(hq, u) for hq in range(h) for u in range(N)]
+    out = {}
+    for hq, u in rows:
+        blocks = np.nonzero(mask[hq, u, :u + 1])[0]
+        out[(hq, u)] = block_sparse_attention_row(Q[hq], K[hq // g], V[hq // g], u, blocks, B)
+    return out
+
+
+def dense_causal_attention(Q: np.ndarray, K: np.ndarray, V: np.ndarray,
+                           q_chunk: int = 1024) -> Tuple[np.ndarray, np.ndarray]:
+    """softmax(Q K^T / sqrt(d) + causal) V over whole heads.  Returns
+    (O [h, L, d], lse [h, L]).  Query rows are processed in chunks only to bound
+    memory; each chunk sees all keys."""
+    h, L, d = Q.shape
+    g = h // K.shape[0]
+    O = np.empty((h, L, d))
+    lse = np.empty((h, L))
+    j = np.arange(L)
+    for hq in range(h):
+        Kh, Vh = K[hq // g], V[hq // g]
+        for r0 in range(0, L, q_chunk):
+            r1 = min(L, r0 + q_chunk)
+            s = (Q[hq, r0:r1] @ Kh[:r1].T) / np.sqrt(d)
+            s = np.where(j[None, :r1] <= np.arange(r0, r1)[:, None], s, -np.inf)
+            m = s.max(axis=1, keepdims=True)
+            e = np.exp(s - m)
+            den = e.sum(axis=1, keepdims=True)
+            O[hq, r0:r1] = (e / den) @ Vh[:r1]
+            lse[hq, r0:r1] = m[:, 0] + np.log(den[:, 0])
+    return O, lse
