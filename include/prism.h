@@ -1,0 +1,153 @@
+/*
+ * prism.h — C ABI of libprism: Prism block-importance estimation and block-sparse
+ * causal prefill attention for AMD MI355X (gfx950).
+ *
+ * Section / equation names refer to "Prism: Spectral-Aware Block-Sparse Attention"
+ * (arXiv 2602.08426).
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers (HBM) owned by the caller, unless a
+ *     parameter is explicitly marked "host".  The library never frees or keeps them.
+ *   - Tensors are dense and contiguous:
+ *        Q, O      : [n_q_heads , seq_len, head_dim]  bf16
+ *        K, V      : [n_kv_heads, seq_len, head_dim]  bf16
+ *     A batch is expressed by folding it into the head counts
+ *     (n_q_heads = batch*h, n_kv_heads = batch*h_kv); q-head i reads kv-head
+ *     i / (n_q_heads / n_kv_heads), which keeps the grouping inside each batch item.
+ *   - RoPE has already been applied to Q and K; feature pair j is dims (2j, 2j+1)
+ *     (Sec. 3.1 "Spectral Structure of RoPE"), so the high-frequency band is the
+ *     FIRST d_high dims and the low-frequency band the LAST d_low dims (Sec. 3.4).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls only
+ *     enqueue work; they return before it has run.  Outputs are valid after the
+ *     stream has been synchronised.
+ *   - Return value: PRISM_OK or a negative prism_status.  Arguments are validated on
+ *     the host before anything is launched; on error nothing has been enqueued.
+ *   - No entry point allocates device memory; scratch comes in through `workspace`
+ *     (256-byte aligned) whose size the *_workspace_bytes calls report.
+ */
+#ifndef PRISM_H_
+#define PRISM_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum prism_status {
+  PRISM_OK = 0,
+  PRISM_ERR_INVALID_ARG = -1,     /* null pointer, inconsistent sizes, p outside (0,1], ... */
+  PRISM_ERR_UNSUPPORTED = -2,     /* head_dim != 128, block not in {64,128}, seq_len % block != 0, ... */
+  PRISM_ERR_WORKSPACE = -3,       /* workspace missing, misaligned or too small */
+  PRISM_ERR_HIP = -4              /* a HIP runtime call failed (launch error) */
+} prism_status;
+
+/* flags */
+#define PRISM_FLAG_NO_CALIBRATION 1u   /* tau_high = tau_low = 1 (ablation of Sec. 4.4) */
+
+/* Problem description shared by all calls (plain data, host memory). */
+typedef struct prism_params {
+  int32_t n_q_heads;    /* h   (batch folded in)                                   */
+  int32_t n_kv_heads;   /* h_kv, must divide n_q_heads                             */
+  int32_t seq_len;      /* L, multiple of `block`                                   */
+  int32_t head_dim;     /* d, must be 128                                           */
+  int32_t block;        /* B, 64 or 128; N = L / B blocks, N <= 2048                */
+  int32_t d_high;       /* width of the high-frequency band, multiple of 32, 0..d   */
+  int32_t d_low;        /* width of the low-frequency band,  multiple of 32, 0..d   */
+  float   top_p;        /* p in (0,1]; p >= 1 selects every causal block            */
+  uint32_t flags;       /* PRISM_FLAG_*                                              */
+} prism_params;
+
+/* Library version as major*10000 + minor*100 + patch. */
+int prism_version(void);
+
+/* Static, human-readable text for a status code (host pointer, never NULL). */
+const char* prism_status_string(int status);
+
+/* ------------------------------------------------------------------------------------
+ * Block importance estimation — Sec. 3.4 "Prism: Spectral-Aware Block Selection" and
+ * App. C "Top-P Block Selection".
+ *
+ * Computes, per q-head:  mean-pooled Qbar, Kbar (Eq. "mean-pooling");  RMS energies of
+ * the full / high / low slices;  tau_z = sqrt(d_z/d) (RMS(Qbar_z)/RMS(Qbar))
+ * (RMS(Kbar_z)/RMS(Kbar));  logits_z = Qbar_z Kbar_z^T / (tau_z sqrt(d_z)) for key
+ * blocks v <= u (block-causal);  row softmax;  top-p (smallest set of highest-probability
+ * blocks whose mass reaches p; equal probabilities are taken in ascending block order);
+ * M = M_high | M_low;  and the compacted per-(head, q-block) index lists of M.
+ * A band with d_z == 0 is skipped.  Zero band energy gives flat logits.
+ *
+ * Outputs
+ *   mask_bits : [n_q_heads, N, W] uint64, W = ceil(N/64); bit (v % 64) of word v / 64 of
+ *               row (head, u) is M[u, v].  Fully overwritten.
+ *   row_ptr   : [n_q_heads*N + 1] int32, CSR row offsets, row index = head*N + u.
+ *   col_idx   : [col_capacity] int32, selected key blocks of each row in ascending order.
+ *               n_q_heads*N*(N+1)/2 entries always suffice.
+ *   info      : [4] int32: info[0] = number of selected (head,u,v) triples,
+ *               info[1] = 1 if that number exceeds col_capacity (col_idx then holds only
+ *               the entries that fit and must not be used), info[2..3] reserved (0).
+ * workspace: prism_estimate_workspace_bytes() bytes.
+ * ---------------------------------------------------------------------------------- */
+int prism_estimate_workspace_bytes(const prism_params* params, size_t* bytes /* host, out */);
+
+int prism_estimate(const prism_params* params,
+                   const void* q_bf16, const void* k_bf16,
+                   uint64_t* mask_bits, int32_t* row_ptr,
+                   int32_t* col_idx, int64_t col_capacity,
+                   int32_t* info,
+                   void* workspace, size_t workspace_bytes, void* stream);
+
+/* Same computation as prism_estimate up to the block scores, for inspection at small
+ * sizes: writes the pooled vectors, the two scales sqrt(d_z)*tau_z and the dual-band
+ * logits (Sec. 3.4, step "Dual-Band Scoring").  Any output pointer may be NULL.
+ *   pooled_q : [n_q_heads , N, d] float      pooled_k : [n_kv_heads, N, d] float
+ *   scales   : [n_q_heads, 2] float (high, low); 0 when the band is disabled
+ *   logits_high, logits_low : [n_q_heads, N, N] float; entries with v > u are not written
+ * Uses the same workspace size as prism_estimate. */
+int prism_block_scores(const prism_params* params,
+                       const void* q_bf16, const void* k_bf16,
+                       float* pooled_q, float* pooled_k, float* scales,
+                       float* logits_high, float* logits_low,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+/* Compaction of a caller-supplied block mask (same layouts and `info` semantics as
+ * prism_estimate; the mask -> index-list step that block-sparse kernels need,
+ * Sec. 3.1 "Coarse-grained Attention": the mask decides which pairs (u,v) are computed).
+ * Bits with v >= N must be 0.  Needs no workspace. */
+int prism_mask_to_csr(const prism_params* params, const uint64_t* mask_bits,
+                      int32_t* row_ptr, int32_t* col_idx, int64_t col_capacity,
+                      int32_t* info, void* stream);
+
+/* Index lists of the all-ones causal mask (dense attention as the special case M = 1):
+ * row (head,u) = {0..u}.  col_capacity must be >= n_q_heads*N*(N+1)/2. */
+int prism_causal_csr(const prism_params* params, int32_t* row_ptr, int32_t* col_idx,
+                     int64_t col_capacity, void* stream);
+
+/* ------------------------------------------------------------------------------------
+ * Block-sparse causal attention — Sec. 2 "Block-Sparse Attention": the dense
+ * computation and online accumulation restricted to the selected block pairs.
+ *
+ * For token i of q-block u = i / B of head hq:
+ *    J(i) = { j <= i : block j / B is listed in row (hq,u) },
+ *    o_i  = sum_{j in J} softmax_J( q_i . k_j / sqrt(d) )_j  v_j       (bf16 in, fp32 accumulate)
+ * Listed blocks v > u are ignored; a row with an empty list gives o = 0, lse = -inf.
+ *
+ *   row_ptr, col_idx : CSR as produced above; col_count = number of valid entries in
+ *                      col_idx (row_ptr values are clamped to it).
+ *   out_bf16         : [n_q_heads, L, d] bf16, fully overwritten.
+ *   lse              : [n_q_heads, L] float natural-log sum-exp of the scaled scores, or NULL.
+ * workspace: prism_sparse_attn_workspace_bytes() bytes (holds a transposed copy of V).
+ * top_p, d_high, d_low and flags of `params` are ignored here.
+ * ---------------------------------------------------------------------------------- */
+int prism_sparse_attn_workspace_bytes(const prism_params* params, size_t* bytes /* host, out */);
+
+int prism_sparse_attn(const prism_params* params,
+                      const void* q_bf16, const void* k_bf16, const void* v_bf16,
+                      const int32_t* row_ptr, const int32_t* col_idx, int64_t col_count,
+                      void* out_bf16, float* lse,
+                      void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PRISM_H_ */

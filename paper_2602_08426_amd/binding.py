@@ -1,0 +1,191 @@
+"""ctypes binding of libprism.so — argument marshalling only.
+
+Every function has the name of the C entry point it calls (include/prism.h).  PyTorch is
+used for device memory (`torch.empty`) and the current HIP stream; all computation happens
+inside the library's kernels.  There is no fallback: if the library is missing or a call
+returns an error status, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import torch
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libprism.so")
+_lib: Optional[ctypes.CDLL] = None
+
+PRISM_FLAG_NO_CALIBRATION = 1
+
+
+class PrismError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = _load().prism_status_string(status).decode()
+        super().__init__(f"{where} failed with status {status}: {msg}")
+
+
+class prism_params(ctypes.Structure):
+    _fields_ = [("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
+                ("seq_len", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+                ("block", ctypes.c_int32), ("d_high", ctypes.c_int32), ("d_low", ctypes.c_int32),
+                ("top_p", ctypes.c_float), ("flags", ctypes.c_uint32)]
+
+    @property
+    def n_blocks(self) -> int:
+        return self.seq_len // self.block
+
+    @property
+    def words_per_row(self) -> int:
+        return (self.n_blocks + 63) // 64
+
+
+EXPORTS = ("prism_version", "prism_status_string", "prism_estimate_workspace_bytes",
+           "prism_estimate", "prism_block_scores", "prism_mask_to_csr", "prism_causal_csr",
+           "prism_sparse_attn_workspace_bytes", "prism_sparse_attn")
+
+
+def _load() -> ctypes.CDLL:
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise FileNotFoundError(
+            f"{_LIB_PATH} not found: build it first (python -m paper_2602_08426_amd.build "
+            "or __graft_entry__.build())")
+    lib = ctypes.CDLL(_LIB_PATH)
+    P, vp, i64, sz = ctypes.POINTER(prism_params), ctypes.c_void_p, ctypes.c_int64, ctypes.c_size_t
+    lib.prism_version.restype = ctypes.c_int
+    lib.prism_version.argtypes = []
+    lib.prism_status_string.restype = ctypes.c_char_p
+    lib.prism_status_string.argtypes = [ctypes.c_int]
+    lib.prism_estimate_workspace_bytes.argtypes = [P, ctypes.POINTER(sz)]
+    lib.prism_estimate.argtypes = [P, vp, vp, vp, vp, vp, i64, vp, vp, sz, vp]
+    lib.prism_block_scores.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.prism_mask_to_csr.argtypes = [P, vp, vp, vp, i64, vp, vp]
+    lib.prism_causal_csr.argtypes = [P, vp, vp, i64, vp]
+    lib.prism_sparse_attn_workspace_bytes.argtypes = [P, ctypes.POINTER(sz)]
+    lib.prism_sparse_attn.argtypes = [P, vp, vp, vp, vp, vp, i64, vp, vp, vp, sz, vp]
+    for name in EXPORTS[2:]:
+        getattr(lib, name).restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def make_params(n_q_heads: int, n_kv_heads: int, seq_len: int, block: int, d_high: int = 64,
+                d_low: int = 96, top_p: float = 0.95, flags: int = 0, head_dim: int = 128) -> prism_params:
+    return prism_params(n_q_heads, n_kv_heads, seq_len, head_dim, block, d_high, d_low, top_p, flags)
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("expected a contiguous device tensor")
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _check(status: int, where: str) -> None:
+    if status != 0:
+        raise PrismError(status, where)
+
+
+def prism_version() -> int:
+    return _load().prism_version()
+
+
+def prism_status_string(status: int) -> str:
+    return _load().prism_status_string(status).decode()
+
+
+def prism_estimate_workspace_bytes(params: prism_params) -> int:
+    n = ctypes.c_size_t(0)
+    _check(_load().prism_estimate_workspace_bytes(ctypes.byref(params), ctypes.byref(n)),
+           "prism_estimate_workspace_bytes")
+    return n.value
+
+
+def prism_sparse_attn_workspace_bytes(params: prism_params) -> int:
+    n = ctypes.c_size_t(0)
+    _check(_load().prism_sparse_attn_workspace_bytes(ctypes.byref(params), ctypes.byref(n)),
+           "prism_sparse_attn_workspace_bytes")
+    return n.value
+
+
+def alloc_workspace(nbytes: int, device="cuda") -> torch.Tensor:
+    """256-byte aligned scratch (torch's caching allocator aligns to 512 B)."""
+    return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+
+
+def alloc_estimate_outputs(params: prism_params, col_capacity: Optional[int] = None, device="cuda"):
+    N, W, h = params.n_blocks, params.words_per_row, params.n_q_heads
+    if col_capacity is None:
+        col_capacity = h * N * (N + 1) // 2
+    mask_bits = torch.empty((h, N, W), dtype=torch.int64, device=device)
+    row_ptr = torch.empty(h * N + 1, dtype=torch.int32, device=device)
+    col_idx = torch.empty(max(col_capacity, 1), dtype=torch.int32, device=device)
+    info = torch.empty(4, dtype=torch.int32, device=device)
+    return mask_bits, row_ptr, col_idx, info
+
+
+def prism_estimate(params: prism_params, q: torch.Tensor, k: torch.Tensor, mask_bits: torch.Tensor,
+                   row_ptr: torch.Tensor, col_idx: torch.Tensor, col_capacity: int,
+                   info: torch.Tensor, workspace: torch.Tensor) -> None:
+    _check(_load().prism_estimate(ctypes.byref(params), _ptr(q), _ptr(k), _ptr(mask_bits),
+                                  _ptr(row_ptr), _ptr(col_idx), col_capacity, _ptr(info),
+                                  _ptr(workspace), workspace.numel(), _stream()), "prism_estimate")
+
+
+def prism_block_scores(params: prism_params, q: torch.Tensor, k: torch.Tensor,
+                       pooled_q: Optional[torch.Tensor], pooled_k: Optional[torch.Tensor],
+                       scales: Optional[torch.Tensor], logits_high: Optional[torch.Tensor],
+                       logits_low: Optional[torch.Tensor], workspace: torch.Tensor) -> None:
+    _check(_load().prism_block_scores(ctypes.byref(params), _ptr(q), _ptr(k), _ptr(pooled_q),
+                                      _ptr(pooled_k), _ptr(scales), _ptr(logits_high),
+                                      _ptr(logits_low), _ptr(workspace), workspace.numel(),
+                                      _stream()), "prism_block_scores")
+
+
+def prism_mask_to_csr(params: prism_params, mask_bits: torch.Tensor, row_ptr: torch.Tensor,
+                      col_idx: torch.Tensor, col_capacity: int, info: torch.Tensor) -> None:
+    _check(_load().prism_mask_to_csr(ctypes.byref(params), _ptr(mask_bits), _ptr(row_ptr),
+                                     _ptr(col_idx), col_capacity, _ptr(info), _stream()),
+           "prism_mask_to_csr")
+
+
+def prism_causal_csr(params: prism_params, row_ptr: torch.Tensor, col_idx: torch.Tensor,
+                     col_capacity: int) -> None:
+    _check(_load().prism_causal_csr(ctypes.byref(params), _ptr(row_ptr), _ptr(col_idx),
+                                    col_capacity, _stream()), "prism_causal_csr")
+
+
+def prism_sparse_attn(params: prism_params, q: torch.Tensor, k: torch.Tensor, v: torch.Tensor,
+                      row_ptr: torch.Tensor, col_idx: torch.Tensor, col_count: int,
+                      out: torch.Tensor, lse: Optional[torch.Tensor], workspace: torch.Tensor) -> None:
+    _check(_load().prism_sparse_attn(ctypes.byref(params), _ptr(q), _ptr(k), _ptr(v), _ptr(row_ptr),
+                                     _ptr(col_idx), col_count, _ptr(out), _ptr(lse),
+                                     _ptr(workspace), workspace.numel(), _stream()),
+           "prism_sparse_attn")
+
+
+# ---- conveniences for callers holding numpy bf16 bit patterns --------------------------
+def bf16_bits_to_device(bits, device="cuda") -> torch.Tensor:
+    """numpy uint16 bf16 bit patterns -> device bf16 tensor (a copy, no arithmetic)."""
+    import numpy as np
+    t = torch.from_numpy(np.ascontiguousarray(bits).view(np.int16))
+    return t.to(device).view(torch.bfloat16)
+
+
+def device_bf16_to_bits(t: torch.Tensor):
+    """device bf16 tensor -> numpy uint16 bit patterns."""
+    import numpy as np
+    return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)

@@ -1,0 +1,325 @@
+// Block-sparse causal flash attention of libprism (gfx950, bf16 MFMA, fp32 online softmax).
+//
+// Sec. 2 "Block-Sparse Attention": dense QK^T / softmax / PV with online accumulation,
+// restricted to the (q-block, kv-block) pairs listed in a CSR index list.
+//
+// Formulation.  Each wave owns 32 query rows and works on the TRANSPOSED problem so that
+// every per-query quantity (running max, running sum, output scale) lives in one lane:
+//     S^T = K Q^T      (v_mfma_f32_32x32x16_bf16: A = K tile rows, B = Q rows)
+//     O^T += V^T P^T   (A = V^T rows, B = P^T, which is exactly the accumulator layout of S^T
+//                       after bf16 conversion, so P never leaves registers)
+// In the 32x32 accumulator layout lane l holds query column l%32 and, per 32-key tile,
+// keys 8*(r/4) + 4*(l/32) + r%4 for r = 0..15.  One MFMA K-step of PV therefore consumes
+// keys {16s + 8g + 4*(l/32) + i}; the V^T operand must present the same keys in the same
+// slots, which is achieved by a one-off re-layout of V in HBM (vt_image_kernel): per kv
+// block a [d][B] image whose key positions inside every group of 16 are permuted to
+// pos = 8*hf + 4*g + i  for key = 8*g + 4*hf + i.  A 16-byte LDS read then yields one
+// A operand.
+#include "prism_common.h"
+
+namespace prism {
+
+// =====================================================================================
+// V re-layout: V [h_kv, L, d]  ->  image [h_kv, N, d, B] with permuted key positions.
+// =====================================================================================
+template <int BLK>
+__global__ __launch_bounds__(256) void vt_image_kernel(const uint16_t* __restrict__ v,
+                                                       uint16_t* __restrict__ vt, int L, int N) {
+  __shared__ uint16_t tile[BLK][kHeadDim + 2];
+  const int blk = blockIdx.x, kvh = blockIdx.y, t = threadIdx.x;
+  const uint16_t* src = v + ((size_t)kvh * L + (size_t)blk * BLK) * kHeadDim;
+  for (int idx = t; idx < BLK * 16; idx += 256) {
+    const int row = idx >> 4, c = idx & 15;
+    const uint4 x = *reinterpret_cast<const uint4*>(src + (size_t)row * kHeadDim + c * 8);
+    uint32_t* dst = reinterpret_cast<uint32_t*>(&tile[row][c * 8]);   // 4-byte aligned: row stride 260 B
+    dst[0] = x.x; dst[1] = x.y; dst[2] = x.z; dst[3] = x.w;
+  }
+  __syncthreads();
+  constexpr int CPR = BLK / 8;                       // 16-byte chunks per image row
+  uint16_t* dstb = vt + ((size_t)kvh * N + blk) * (size_t)kHeadDim * BLK;
+  for (int idx = t; idx < kHeadDim * CPR; idx += 256) {
+    const int d = idx / CPR, c = idx % CPR;
+    uint32_t w[4];
+#pragma unroll
+    for (int e = 0; e < 8; e += 2) {
+      // position p = c*8 + e inside the row; group a = p/16, hf = (p/8)&1, g = (p/4)&1, i = p&3
+      const int p0 = c * 8 + e, p1 = p0 + 1;
+      const int k0 = (p0 & ~15) + 8 * ((p0 >> 2) & 1) + 4 * ((p0 >> 3) & 1) + (p0 & 3);
+      const int k1 = (p1 & ~15) + 8 * ((p1 >> 2) & 1) + 4 * ((p1 >> 3) & 1) + (p1 & 3);
+      w[e >> 1] = (uint32_t)tile[k0][d] | ((uint32_t)tile[k1][d] << 16);
+    }
+    *reinterpret_cast<uint4*>(dstb + (size_t)d * BLK + c * 8) = make_uint4(w[0], w[1], w[2], w[3]);
+  }
+}
+
+// =====================================================================================
+// Sparse attention kernel.  One workgroup per (q-head, q-block); BLK/32 waves of 32 queries.
+// LDS: K tile [BLK][128] bf16 and V^T tile [128][BLK] bf16, 16-byte chunks XOR-swizzled by
+// row so that both the row-major writes and the 16-lane column reads are conflict-free.
+// Loop per listed kv block (V and the next K are fetched while the MFMAs of the other
+// operand run):
+//     K(j) in LDS | issue V(j) loads | S^T = K Q^T | online softmax | V(j) -> LDS | barrier
+//     issue K(j+1) loads | O^T += V^T P^T | K(j+1) -> LDS | barrier
+// =====================================================================================
+template <int BLK>
+struct AttnCfg {
+  static constexpr int kWaves = BLK / 32;
+  static constexpr int kThreads = kWaves * 64;
+  static constexpr int kTileBytes = BLK * kHeadDim * 2;
+  static constexpr int kChunks = kTileBytes / 16;          // 16-byte pieces per tile
+  static constexpr int kPerThread = kChunks / kThreads;    // = 8
+  static constexpr int kVtCpr = BLK / 8;                   // chunks per V^T row
+};
+
+template <int BLK>
+__device__ __forceinline__ void load_tile_regs(const uint16_t* __restrict__ src, uint4 (&r)[8], int t) {
+  using C = AttnCfg<BLK>;
+#pragma unroll
+  for (int i = 0; i < C::kPerThread; ++i)
+    r[i] = *reinterpret_cast<const uint4*>(src + (size_t)(i * C::kThreads + t) * 8);
+}
+
+// K tile: rows of 16 chunks (256 B).
+template <int BLK>
+__device__ __forceinline__ void store_k_tile(char* lds, const uint4 (&r)[8], int t) {
+  using C = AttnCfg<BLK>;
+#pragma unroll
+  for (int i = 0; i < C::kPerThread; ++i) {
+    const int idx = i * C::kThreads + t;
+    const int row = idx >> 4, c = idx & 15;
+    *reinterpret_cast<uint4*>(lds + row * 256 + ((c ^ (row & 15)) << 4)) = r[i];
+  }
+}
+
+// V^T tile: 128 rows of kVtCpr chunks.
+template <int BLK>
+__device__ __forceinline__ void store_vt_tile(char* lds, const uint4 (&r)[8], int t) {
+  using C = AttnCfg<BLK>;
+#pragma unroll
+  for (int i = 0; i < C::kPerThread; ++i) {
+    const int idx = i * C::kThreads + t;
+    const int row = idx / C::kVtCpr, c = idx % C::kVtCpr;
+    *reinterpret_cast<uint4*>(lds + row * (BLK * 2) + ((c ^ (row & (C::kVtCpr - 1))) << 4)) = r[i];
+  }
+}
+
+template <int BLK>
+__global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
+    const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ vt,
+    const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx, int64_t col_count,
+    uint16_t* __restrict__ out, float* __restrict__ lse, int h, int h_kv, int L, int N) {
+  using C = AttnCfg<BLK>;
+  constexpr int KT = BLK / 32;                       // 32-key tiles per kv block
+  __shared__ __attribute__((aligned(16))) char lds_k[C::kTileBytes];
+  __shared__ __attribute__((aligned(16))) char lds_v[C::kTileBytes];
+
+  // work item: longest rows (large u) first; consecutive workgroups share a kv head
+  const int bid = blockIdx.x;
+  const int u = N - 1 - bid / h;
+  const int rr = bid % h;
+  const int g = h / h_kv;
+  const int kvh = rr % h_kv;
+  const int hq = kvh * g + rr / h_kv;
+
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int l32 = lane & 31, hf = lane >> 5;
+
+  const size_t row = (size_t)hq * N + u;
+  int64_t beg = row_ptr[row], end = row_ptr[row + 1];
+  beg = beg < 0 ? 0 : (beg > col_count ? col_count : beg);
+  end = end < beg ? beg : (end > col_count ? col_count : end);
+
+  const uint16_t* kbase = k + (size_t)kvh * L * kHeadDim;
+  const uint16_t* vbase = vt + (size_t)kvh * N * (size_t)kHeadDim * BLK;
+
+  // Q fragments (B operand of S^T = K Q^T): query row 32*wave + l32, dims 16*ks + 8*hf ..+7
+  const int qrow = u * BLK + wave * 32 + l32;
+  bf16x8 qf[8];
+  {
+    const uint16_t* qp = q + ((size_t)hq * L + qrow) * kHeadDim + hf * 8;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16);
+  }
+
+  f32x16 oacc[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) oacc[i][r] = 0.f;
+  float m_run = -INFINITY;          // running max, in units of log2: s * sm_scale
+  float l_run = 0.f;                // this lane's share of the running sum
+  const float sm_scale = 1.4426950408889634f * 0.08838834764831845f;   // log2(e) / sqrt(128)
+
+  uint4 stage[8];
+  // find the first valid entry (v <= u) and stage its K tile
+  int64_t it = beg;
+  while (it < end && (col_idx[it] < 0 || col_idx[it] > u)) ++it;
+  if (it < end) {
+    load_tile_regs<BLK>(kbase + (size_t)col_idx[it] * BLK * kHeadDim, stage, t);
+    store_k_tile<BLK>(lds_k, stage, t);
+  }
+  __syncthreads();
+
+  while (it < end) {
+    const int v = col_idx[it];
+    int64_t nx = it + 1;
+    while (nx < end && (col_idx[nx] < 0 || col_idx[nx] > u)) ++nx;
+
+    // ---- V(j) loads in flight during S^T ----
+    load_tile_regs<BLK>(vbase + (size_t)v * kHeadDim * BLK, stage, t);
+
+    // ---- S^T = K Q^T ----
+    f32x16 sacc[KT];
+#pragma unroll
+    for (int kt = 0; kt < KT; ++kt) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sacc[kt][r] = 0.f;
+      const int krow = kt * 32 + l32;
+      const char* kp = lds_k + krow * 256;
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+        const bf16x8 a = *reinterpret_cast<const bf16x8*>(kp + (((2 * ks + hf) ^ (krow & 15)) << 4));
+        sacc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], sacc[kt], 0, 0, 0);
+      }
+    }
+
+    // ---- causal mask inside the diagonal block ----
+    if (v == u) {
+      const int qloc = wave * 32 + l32;
+#pragma unroll
+      for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int kloc = kt * 32 + 8 * (r >> 2) + 4 * hf + (r & 3);
+          if (kloc > qloc) sacc[kt][r] = -INFINITY;
+        }
+    }
+
+    // ---- online softmax (per query = per lane pair l, l^32) ----
+    float mx = -INFINITY;
+#pragma unroll
+    for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[kt][r]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(m_run, mx * sm_scale);       // finite: every query sees a key
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+    m_run = m_new;
+    float psum = 0.f;
+    bf16x8 pf[KT][2];
+#pragma unroll
+    for (int kt = 0; kt < KT; ++kt) {
+#pragma unroll
+      for (int s = 0; s < 2; ++s) {
+#pragma unroll
+        for (int j = 0; j < 8; j += 2) {
+          const float p0 = __builtin_amdgcn_exp2f(fmaf(sacc[kt][8 * s + j], sm_scale, -m_new));
+          const float p1 = __builtin_amdgcn_exp2f(fmaf(sacc[kt][8 * s + j + 1], sm_scale, -m_new));
+          psum += p0 + p1;
+          const f32x2 pp = {p0, p1};
+          const bf16x2 pb = __builtin_convertvector(pp, bf16x2);
+          pf[kt][s][j] = pb[0];
+          pf[kt][s][j + 1] = pb[1];
+        }
+      }
+    }
+    l_run = l_run * alpha + psum;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) oacc[i][r] *= alpha;
+
+    // ---- V(j) -> LDS ----
+    store_vt_tile<BLK>(lds_v, stage, t);
+    __syncthreads();                 // V visible; everyone is done reading K(j)
+
+    // ---- K(j+1) loads in flight during PV ----
+    if (nx < end) load_tile_regs<BLK>(kbase + (size_t)col_idx[nx] * BLK * kHeadDim, stage, t);
+
+    // ---- O^T += V^T P^T ----
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) {
+      const int vrow = dt * 32 + l32;
+      const char* vp = lds_v + vrow * (BLK * 2);
+#pragma unroll
+      for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+          const int c = 2 * (2 * kt + s) + hf;
+          const bf16x8 a =
+              *reinterpret_cast<const bf16x8*>(vp + ((c ^ (vrow & (C::kVtCpr - 1))) << 4));
+          oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[kt][s], oacc[dt], 0, 0, 0);
+        }
+    }
+
+    if (nx < end) store_k_tile<BLK>(lds_k, stage, t);
+    __syncthreads();                 // K(j+1) visible; everyone is done reading V(j)
+    it = nx;
+  }
+
+  // ---- epilogue: O = O^T / l, bf16, [q][d] ----
+  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  const float inv_l = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+  uint16_t* op = out + ((size_t)hq * L + qrow) * kHeadDim;
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+    for (int gq = 0; gq < 4; ++gq) {
+      const int d0 = dt * 32 + gq * 8 + hf * 4;
+      const f32x2 a = {oacc[dt][gq * 4 + 0] * inv_l, oacc[dt][gq * 4 + 1] * inv_l};
+      const f32x2 b = {oacc[dt][gq * 4 + 2] * inv_l, oacc[dt][gq * 4 + 3] * inv_l};
+      const bf16x2 ab = __builtin_convertvector(a, bf16x2);
+      const bf16x2 bb = __builtin_convertvector(b, bf16x2);
+      uint2 w;
+      w.x = *reinterpret_cast<const uint32_t*>(&ab);
+      w.y = *reinterpret_cast<const uint32_t*>(&bb);
+      *reinterpret_cast<uint2*>(op + d0) = w;
+    }
+  if (lse != nullptr && hf == 0)
+    lse[(size_t)hq * L + qrow] =
+        l_tot > 0.f ? (m_run + log2f(l_tot)) * 0.6931471805599453f : -INFINITY;
+}
+
+}  // namespace prism
+
+using namespace prism;
+
+extern "C" int prism_sparse_attn_workspace_bytes(const prism_params* params, size_t* bytes) {
+  if (bytes == nullptr) return PRISM_ERR_INVALID_ARG;
+  int rc = check_params(params);
+  if (rc != PRISM_OK) return rc;
+  *bytes = align_up((size_t)params->n_kv_heads * params->seq_len * kHeadDim * 2, 256);
+  return PRISM_OK;
+}
+
+extern "C" int prism_sparse_attn(const prism_params* params, const void* q_bf16, const void* k_bf16,
+                                 const void* v_bf16, const int32_t* row_ptr, const int32_t* col_idx,
+                                 int64_t col_count, void* out_bf16, float* lse, void* workspace,
+                                 size_t workspace_bytes, void* stream) {
+  int rc = check_params(params);
+  if (rc != PRISM_OK) return rc;
+  if (!q_bf16 || !k_bf16 || !v_bf16 || !row_ptr || !col_idx || !out_bf16 || col_count < 0)
+    return PRISM_ERR_INVALID_ARG;
+  const size_t need = (size_t)params->n_kv_heads * params->seq_len * kHeadDim * 2;
+  if (workspace == nullptr || (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0 ||
+      workspace_bytes < need)
+    return PRISM_ERR_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int N = params->seq_len / params->block;
+  const int h = params->n_q_heads, h_kv = params->n_kv_heads, L = params->seq_len;
+  uint16_t* vt = static_cast<uint16_t*>(workspace);
+  if (params->block == 128) {
+    hipLaunchKernelGGL(vt_image_kernel<128>, dim3(N, h_kv), dim3(256), 0, st,
+                       (const uint16_t*)v_bf16, vt, L, N);
+    hipLaunchKernelGGL(sparse_attn_kernel<128>, dim3(h * N), dim3(AttnCfg<128>::kThreads), 0, st,
+                       (const uint16_t*)q_bf16, (const uint16_t*)k_bf16, vt, row_ptr, col_idx,
+                       col_count, (uint16_t*)out_bf16, lse, h, h_kv, L, N);
+  } else {
+    hipLaunchKernelGGL(vt_image_kernel<64>, dim3(N, h_kv), dim3(256), 0, st,
+                       (const uint16_t*)v_bf16, vt, L, N);
+    hipLaunchKernelGGL(sparse_attn_kernel<64>, dim3(h * N), dim3(AttnCfg<64>::kThreads), 0, st,
+                       (const uint16_t*)q_bf16, (const uint16_t*)k_bf16, vt, row_ptr, col_idx,
+                       col_count, (uint16_t*)out_bf16, lse, h, h_kv, L, N);
+  }
+  return launch_status();
+}

@@ -1,0 +1,85 @@
+// Internal helpers shared by the libprism translation units (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "prism.h"
+
+namespace prism {
+
+constexpr int kHeadDim = 128;
+constexpr int kMaxBlocks = 2048;       // N <= 2048  (128K tokens at B = 64)
+constexpr int kWave = 64;
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+// Validation shared by every entry point.  Returns PRISM_OK or an error code.
+inline int check_params(const prism_params* p) {
+  if (p == nullptr) return PRISM_ERR_INVALID_ARG;
+  if (p->n_q_heads <= 0 || p->n_kv_heads <= 0 || p->seq_len <= 0) return PRISM_ERR_INVALID_ARG;
+  if (p->n_q_heads % p->n_kv_heads != 0) return PRISM_ERR_INVALID_ARG;
+  if (p->head_dim != kHeadDim) return PRISM_ERR_UNSUPPORTED;
+  if (p->block != 64 && p->block != 128) return PRISM_ERR_UNSUPPORTED;
+  if (p->seq_len % p->block != 0) return PRISM_ERR_UNSUPPORTED;
+  const int64_t n = p->seq_len / p->block;
+  if (n > kMaxBlocks) return PRISM_ERR_UNSUPPORTED;
+  // CSR offsets are int32
+  const int64_t pairs = (int64_t)p->n_q_heads * n * (n + 1) / 2;
+  if (pairs >= (int64_t)1 << 31) return PRISM_ERR_UNSUPPORTED;
+  if ((int64_t)p->n_q_heads * n + 1 >= (int64_t)1 << 31) return PRISM_ERR_UNSUPPORTED;
+  return PRISM_OK;
+}
+
+inline int check_bands(const prism_params* p) {
+  if (p->d_high < 0 || p->d_low < 0 || p->d_high > p->head_dim || p->d_low > p->head_dim)
+    return PRISM_ERR_INVALID_ARG;
+  if (p->d_high % 32 != 0 || p->d_low % 32 != 0) return PRISM_ERR_INVALID_ARG;
+  if (p->d_high == 0 && p->d_low == 0) return PRISM_ERR_INVALID_ARG;
+  if (!(p->top_p > 0.0f) || !(p->top_p <= 1.0f)) return PRISM_ERR_INVALID_ARG;   // also rejects NaN
+  return PRISM_OK;
+}
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+inline int launch_status() {
+  return hipGetLastError() == hipSuccess ? PRISM_OK : PRISM_ERR_HIP;
+}
+
+// ---- device helpers -------------------------------------------------------------
+__device__ __forceinline__ float wave_sum(float x) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off, 64);
+  return x;
+}
+__device__ __forceinline__ double wave_sum(double x) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off, 64);
+  return x;
+}
+__device__ __forceinline__ float wave_max(float x) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) x = fmaxf(x, __shfl_xor(x, off, 64));
+  return x;
+}
+__device__ __forceinline__ int wave_sum(int x) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off, 64);
+  return x;
+}
+
+__device__ __forceinline__ float bf16_bits_to_float(uint32_t b) { return __uint_as_float(b << 16); }
+
+// fp32 -> bf16 bits, round to nearest even (finite inputs).
+__device__ __forceinline__ uint32_t float_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+
+}  // namespace prism

@@ -1,0 +1,563 @@
+// Block-importance estimation kernels of libprism (gfx950).
+//
+// Pipeline (Sec. 3.4 "Prism: Spectral-Aware Block Selection", App. C "Top-P Block Selection"):
+//   pool_energy_kernel : mean pooling of Q and K blocks + per-block band energies   (HBM-bound)
+//   scale_kernel       : RMS energies -> tau_z -> 1 / (sqrt(d_z) tau_z) per q-head
+//   select_kernel      : dual-band block logits on bf16 MFMA (pooled vectors split into a
+//                        bf16 high and low part), row softmax, top-p, union, bit rows
+//   scan/fill kernels  : bit rows -> CSR index lists
+#include "prism_common.h"
+
+namespace prism {
+
+// =====================================================================================
+// Mean pooling (Eq. "mean-pooling") and band energies (Sec. 3.4, RMS definition).
+// One workgroup per (block, head); 256 threads read B x 128 bf16 = B*256 contiguous bytes
+// as 16-byte pieces: thread t owns dims 8*(t%16)..+7 of rows t/16, t/16+16, ...
+// Outputs per (head, block): pooled vector as bf16 hi + bf16 lo (hi + lo carries 16
+// significant bits), optional fp32 copy, and the three sums of squares
+// (full, first d_high dims, last d_low dims) in energy[(head*N + block)*4 + {0,1,2}].
+// Heads 0..h-1 are Q heads, h..h+h_kv-1 are K heads.
+// =====================================================================================
+template <int BLK>
+__global__ __launch_bounds__(256) void pool_energy_kernel(
+    const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, int h, int L, int N,
+    int d_high, int low_start, uint16_t* __restrict__ pooled_hi, uint16_t* __restrict__ pooled_lo,
+    float* __restrict__ energy, float* __restrict__ pooled_q_f32, float* __restrict__ pooled_k_f32) {
+  __shared__ float part[16][kHeadDim + 4];
+  __shared__ float esum[2][4];
+  const int blk = blockIdx.x, head = blockIdx.y, t = threadIdx.x;
+  const uint16_t* src = (head < h) ? q + (size_t)head * L * kHeadDim
+                                   : k + (size_t)(head - h) * L * kHeadDim;
+  src += (size_t)blk * BLK * kHeadDim;
+  const int c = t & 15, rg = t >> 4;
+
+  uint4 v[BLK / 16];
+#pragma unroll
+  for (int it = 0; it < BLK / 16; ++it)
+    v[it] = *reinterpret_cast<const uint4*>(src + (size_t)(rg + it * 16) * kHeadDim + c * 8);
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int it = 0; it < BLK / 16; ++it) {
+    acc[0] += __uint_as_float(v[it].x << 16);
+    acc[1] += __uint_as_float(v[it].x & 0xFFFF0000u);
+    acc[2] += __uint_as_float(v[it].y << 16);
+    acc[3] += __uint_as_float(v[it].y & 0xFFFF0000u);
+    acc[4] += __uint_as_float(v[it].z << 16);
+    acc[5] += __uint_as_float(v[it].z & 0xFFFF0000u);
+    acc[6] += __uint_as_float(v[it].w << 16);
+    acc[7] += __uint_as_float(v[it].w & 0xFFFF0000u);
+  }
+  *reinterpret_cast<float4*>(&part[rg][c * 8]) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+  *reinterpret_cast<float4*>(&part[rg][c * 8 + 4]) = make_float4(acc[4], acc[5], acc[6], acc[7]);
+  __syncthreads();
+
+  if (t < kHeadDim) {
+    float s = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s += part[r][t];
+    const float mean = s * (1.0f / BLK);
+    const uint32_t hi = float_to_bf16_bits(mean);
+    const float rem = mean - bf16_bits_to_float(hi);
+    const uint32_t lo = float_to_bf16_bits(rem);
+    const size_t o = ((size_t)head * N + blk) * kHeadDim + t;
+    pooled_hi[o] = (uint16_t)hi;
+    pooled_lo[o] = (uint16_t)lo;
+    if (head < h) {
+      if (pooled_q_f32) pooled_q_f32[o] = mean;
+    } else if (pooled_k_f32) {
+      pooled_k_f32[((size_t)(head - h) * N + blk) * kHeadDim + t] = mean;
+    }
+    const float sq = mean * mean;
+    const float e_full = wave_sum(sq);
+    const float e_high = wave_sum(t < d_high ? sq : 0.f);
+    const float e_low = wave_sum(t >= low_start ? sq : 0.f);
+    if ((t & 63) == 0) {
+      esum[t >> 6][0] = e_full;
+      esum[t >> 6][1] = e_high;
+      esum[t >> 6][2] = e_low;
+    }
+  }
+  __syncthreads();
+  if (t < 3) energy[((size_t)head * N + blk) * 4 + t] = esum[0][t] + esum[1][t];
+}
+
+// =====================================================================================
+// Energy-based temperature calibration (Sec. 3.4): per q-head
+//   tau_z = sqrt(d_z/d) * RMS(Qbar_z)/RMS(Qbar) * RMS(Kbar_z)/RMS(Kbar),  scale_z = sqrt(d_z) tau_z.
+// One wave per q-head sums the per-block energies in a fixed order (fp64).
+// inv_scale[hq*2 + z] = 1/scale_z, or 0 when the band is disabled or has no energy.
+// =====================================================================================
+__global__ __launch_bounds__(64) void scale_kernel(const float* __restrict__ energy, int h, int h_kv,
+                                                   int N, int d_high, int d_low, int calibrate,
+                                                   float* __restrict__ inv_scale,
+                                                   float* __restrict__ scales_out) {
+  const int hq = blockIdx.x, lane = threadIdx.x;
+  const int kvh = h + hq / (h / h_kv);
+  double eq[3] = {0, 0, 0}, ek[3] = {0, 0, 0};
+  for (int i = lane; i < N; i += 64) {
+#pragma unroll
+    for (int z = 0; z < 3; ++z) {
+      eq[z] += (double)energy[((size_t)hq * N + i) * 4 + z];
+      ek[z] += (double)energy[((size_t)kvh * N + i) * 4 + z];
+    }
+  }
+#pragma unroll
+  for (int z = 0; z < 3; ++z) {
+    eq[z] = wave_sum(eq[z]);
+    ek[z] = wave_sum(ek[z]);
+  }
+  if (lane == 0) {
+    const double d = kHeadDim;
+    const double rq = sqrt(eq[0] / (N * d)), rk = sqrt(ek[0] / (N * d));
+    for (int z = 0; z < 2; ++z) {
+      const int dz = z == 0 ? d_high : d_low;
+      double scale = 0.0;
+      if (dz > 0) {
+        if (calibrate) {
+          const double rqz = sqrt(eq[z + 1] / (N * (double)dz));
+          const double rkz = sqrt(ek[z + 1] / (N * (double)dz));
+          const double tau = sqrt(dz / d) * (rqz / rq) * (rkz / rk);
+          scale = sqrt((double)dz) * tau;
+        } else {
+          scale = sqrt((double)dz);
+        }
+      }
+      const bool ok = isfinite(scale) && scale > 0.0;
+      inv_scale[hq * 2 + z] = ok ? (float)(1.0 / scale) : 0.f;
+      if (scales_out) scales_out[hq * 2 + z] = ok ? (float)scale : 0.f;
+    }
+  }
+}
+
+// =====================================================================================
+// Dual-band scoring, softmax, top-p, union (Sec. 3.4 steps 4-5, App. C).
+//
+// One workgroup (4 waves) per (strip of 16 q-blocks, q-head).  Per band:
+//   phase A: logits[16][v <= u_max] = Qbar_z Kbar_z^T * inv_scale on
+//            v_mfma_f32_16x16x32_bf16, with x = hi + lo and the three products
+//            hi*hi + hi*lo + lo*hi (fp32 accumulate), written to LDS;
+//   phase B: one wave per row: lanes hold the row (column i*64 + lane in register i),
+//            softmax numerators e = exp(l - max), then the selection threshold is found
+//            by bisection on the bit pattern of e: the smallest key T* whose strictly
+//            larger elements carry mass < p * sum(e).  Elements above T* are selected;
+//            elements equal to T* are taken in ascending block order while the mass before
+//            them stays < p * sum(e)  (== minimal descending prefix with exclusive
+//            cumulative mass < p, stable order).
+// Bits of both bands are OR-ed in registers (lane i keeps word i of the row).
+// DUMP = true writes the logits to global memory instead of selecting.
+// =====================================================================================
+constexpr int kStripRows = 16;
+
+template <int MAXCH, bool DUMP>
+__global__ __launch_bounds__(256) void select_kernel(
+    const uint16_t* __restrict__ pooled_hi, const uint16_t* __restrict__ pooled_lo,
+    const float* __restrict__ inv_scale, int h, int h_kv, int N, int d_high, int d_low, float top_p,
+    uint64_t* __restrict__ mask_bits, int32_t* __restrict__ row_ptr,
+    float* __restrict__ logits_high, float* __restrict__ logits_low) {
+  extern __shared__ float lds_logits[];
+  const int strip = blockIdx.x, hq = blockIdx.y;
+  const int kvh = h + hq / (h / h_kv);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int u0 = strip * kStripRows;
+  const int ncols = min(N, u0 + kStripRows);
+  const int ntiles = (ncols + 15) >> 4;
+  const int ld = ntiles * 16 + 4;
+  const int W = (N + 63) >> 6;
+
+  uint64_t myword[4] = {0, 0, 0, 0};
+
+  for (int z = 0; z < 2; ++z) {
+    const int dz = z == 0 ? d_high : d_low;
+    if (dz == 0) continue;                         // uniform: same for the whole grid
+    const int band_off = z == 0 ? 0 : kHeadDim - d_low;
+    const int ksteps = dz >> 5;
+    const float inv = inv_scale[hq * 2 + z];
+
+    // ---------------- phase A ----------------
+    {
+      const int arow = min(u0 + (lane & 15), N - 1);
+      const size_t aoff = ((size_t)hq * N + arow) * kHeadDim + band_off + (lane >> 4) * 8;
+      bf16x8 ah[4], al[4];
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        if (ks < ksteps) {
+          ah[ks] = *reinterpret_cast<const bf16x8*>(pooled_hi + aoff + ks * 32);
+          al[ks] = *reinterpret_cast<const bf16x8*>(pooled_lo + aoff + ks * 32);
+        }
+      }
+      for (int ct = wave; ct < ntiles; ct += 4) {
+        const int brow = min(ct * 16 + (lane & 15), N - 1);
+        const size_t boff = ((size_t)kvh * N + brow) * kHeadDim + band_off + (lane >> 4) * 8;
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+          if (ks < ksteps) {
+            const bf16x8 bh = *reinterpret_cast<const bf16x8*>(pooled_hi + boff + ks * 32);
+            const bf16x8 bl = *reinterpret_cast<const bf16x8*>(pooled_lo + boff + ks * 32);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al[ks], bh, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah[ks], bl, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah[ks], bh, acc, 0, 0, 0);
+          }
+        }
+        const int col = ct * 16 + (lane & 15);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int row = (lane >> 4) * 4 + r;
+          const float lg = acc[r] * inv;
+          lds_logits[row * ld + col] = lg;
+          if (DUMP) {
+            const int u = u0 + row;
+            float* dst = z == 0 ? logits_high : logits_low;
+            if (dst != nullptr && u < N && col <= u) dst[((size_t)hq * N + u) * N + col] = lg;
+          }
+        }
+      }
+    }
+    __syncthreads();
+
+    // ---------------- phase B ----------------
+    if (!DUMP) {
+#pragma unroll
+      for (int rr = 0; rr < 4; ++rr) {
+        const int r = wave * 4 + rr;
+        const int u = u0 + r;
+        if (u >= N) continue;                      // uniform per wave
+        const int n = u + 1;
+        const int nch = (n + 63) >> 6;
+        float e[MAXCH];
+        float mx = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < MAXCH; ++i) {
+          const int idx = i * 64 + lane;
+          e[i] = (i < nch && idx < n) ? lds_logits[r * ld + idx] : -INFINITY;
+          mx = fmaxf(mx, e[i]);
+        }
+        mx = wave_max(mx);
+        float part = 0.f;
+#pragma unroll
+        for (int i = 0; i < MAXCH; ++i) {
+          if (i < nch) {
+            e[i] = (e[i] == -INFINITY) ? 0.f : __expf(e[i] - mx);
+            part += e[i];
+          } else {
+            e[i] = 0.f;
+          }
+        }
+        const float total = wave_sum(part);
+        const float target = top_p * total;
+
+        uint32_t tstar = 0;       // selected: key > tstar_minus ... see below
+        float gstar = 0.f;
+        const bool all = top_p >= 1.0f;
+        if (!all) {
+          // largest key T with mass{key > T} >= target; T* = T + 1 is then the smallest
+          // key whose strictly-larger mass is < target (and T* is some element's key).
+          uint32_t T = 0;
+          for (int bit = 30; bit >= 0; --bit) {
+            const uint32_t cand = T | (1u << bit);
+            float gp = 0.f;
+#pragma unroll
+            for (int i = 0; i < MAXCH; ++i)
+              if (i < nch) gp += (__float_as_uint(e[i]) > cand) ? e[i] : 0.f;
+            const float G = wave_sum(gp);
+            if (!(G < target)) T = cand;
+          }
+          tstar = T + 1;
+          float gp = 0.f;
+#pragma unroll
+          for (int i = 0; i < MAXCH; ++i)
+            if (i < nch) gp += (__float_as_uint(e[i]) > tstar) ? e[i] : 0.f;
+          gstar = wave_sum(gp);
+        }
+        const float tie_val = __uint_as_float(tstar);
+        int tie_base = 0;
+#pragma unroll
+        for (int i = 0; i < MAXCH; ++i) {
+          if (i < nch) {
+            const int idx = i * 64 + lane;
+            bool sel;
+            if (all) {
+              sel = idx < n;
+            } else {
+              const uint32_t key = __float_as_uint(e[i]);
+              const bool tie = key == tstar;
+              const uint64_t tb = __ballot(tie);
+              const int rank = tie_base + __popcll(tb & ((1ull << lane) - 1ull));
+              sel = (key > tstar) || (tie && (gstar + (float)rank * tie_val < target));
+              tie_base += __popcll(tb);
+            }
+            const uint64_t bal = __ballot(sel);
+            if (lane == i) myword[rr] |= bal;
+          }
+        }
+      }
+      __syncthreads();                             // LDS is reused by the next band
+    }
+  }
+
+  if (!DUMP) {
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr) {
+      const int u = u0 + wave * 4 + rr;
+      if (u >= N) continue;
+      const size_t row = (size_t)hq * N + u;
+      const int cnt = wave_sum((int)(lane < W ? __popcll(myword[rr]) : 0));
+      if (lane < W) mask_bits[row * W + lane] = myword[rr];
+      if (lane == 0) row_ptr[row + 1] = cnt;
+    }
+  }
+}
+
+// =====================================================================================
+// Bit rows -> CSR
+// =====================================================================================
+__global__ __launch_bounds__(256) void row_count_kernel(const uint64_t* __restrict__ mask_bits,
+                                                        int R, int W, int32_t* __restrict__ row_ptr) {
+  const int r = blockIdx.x * 256 + threadIdx.x;
+  if (r >= R) return;
+  int c = 0;
+  for (int i = 0; i < W; ++i) c += __popcll(mask_bits[(size_t)r * W + i]);
+  row_ptr[r + 1] = c;
+}
+
+// In-place: row_ptr[r+1] holds the count of row r on entry, the inclusive prefix sum on
+// exit; row_ptr[0] = 0.  Single workgroup of 1024 threads, each owning a contiguous span.
+__global__ __launch_bounds__(1024) void scan_kernel(int32_t* __restrict__ row_ptr, int R,
+                                                    int64_t capacity, int32_t* __restrict__ info) {
+  __shared__ int wave_tot[16];
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int per = (R + 1023) / 1024;
+  const int lo = min(R, t * per), hi = min(R, lo + per);
+  int s = 0;
+  for (int i = lo; i < hi; ++i) s += row_ptr[i + 1];
+  // inclusive scan of s across the workgroup
+  int inc = s;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const int y = __shfl_up(inc, off, 64);
+    if (lane >= off) inc += y;
+  }
+  if (lane == 63) wave_tot[wave] = inc;
+  __syncthreads();
+  int base = 0;
+  for (int w = 0; w < wave; ++w) base += wave_tot[w];
+  int run = base + inc - s;                        // exclusive prefix of this thread's span
+  for (int i = lo; i < hi; ++i) {
+    run += row_ptr[i + 1];
+    row_ptr[i + 1] = run;
+  }
+  if (t == 0) row_ptr[0] = 0;
+  if (t == 1023) {
+    info[0] = run;
+    info[1] = ((int64_t)run > capacity) ? 1 : 0;
+    info[2] = 0;
+    info[3] = 0;
+  }
+}
+
+// One wave per row: ascending columns of the set bits.
+__global__ __launch_bounds__(256) void fill_kernel(const uint64_t* __restrict__ mask_bits, int R,
+                                                   int W, const int32_t* __restrict__ row_ptr,
+                                                   int32_t* __restrict__ col_idx, int64_t capacity) {
+  const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (r >= R) return;
+  int64_t base = row_ptr[r];
+  for (int i = 0; i < W; ++i) {
+    const uint64_t word = mask_bits[(size_t)r * W + i];
+    const int rank = __popcll(word & ((1ull << lane) - 1ull));
+    if (((word >> lane) & 1ull) && base + rank < capacity) col_idx[base + rank] = i * 64 + lane;
+    base += __popcll(word);
+  }
+}
+
+__global__ __launch_bounds__(256) void causal_csr_kernel(int h, int N, int32_t* __restrict__ row_ptr,
+                                                         int32_t* __restrict__ col_idx) {
+  const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  const int R = h * N;
+  if (r > R) return;
+  if (r == R) {
+    if (lane == 0) row_ptr[R] = (int32_t)((int64_t)h * N * (N + 1) / 2);
+    return;
+  }
+  const int hq = r / N, u = r % N;
+  const int64_t base = (int64_t)hq * N * (N + 1) / 2 + (int64_t)u * (u + 1) / 2;
+  if (lane == 0) row_ptr[r] = (int32_t)base;
+  for (int v = lane; v <= u; v += 64) col_idx[base + v] = v;
+}
+
+// ---- workspace layout ------------------------------------------------------------
+struct EstimateWs {
+  size_t pooled_hi, pooled_lo, energy, inv_scale, total;
+};
+static EstimateWs estimate_ws(const prism_params* p) {
+  const size_t N = p->seq_len / p->block;
+  const size_t heads = (size_t)p->n_q_heads + p->n_kv_heads;
+  EstimateWs w;
+  size_t off = 0;
+  w.pooled_hi = off; off = align_up(off + heads * N * kHeadDim * 2, 256);
+  w.pooled_lo = off; off = align_up(off + heads * N * kHeadDim * 2, 256);
+  w.energy = off;    off = align_up(off + heads * N * 4 * sizeof(float), 256);
+  w.inv_scale = off; off = align_up(off + (size_t)p->n_q_heads * 2 * sizeof(float), 256);
+  w.total = off;
+  return w;
+}
+
+static int run_pool_and_scale(const prism_params* p, const void* q, const void* k, char* ws,
+                              const EstimateWs& L, float* pooled_q, float* pooled_k, float* scales,
+                              hipStream_t st) {
+  const int N = p->seq_len / p->block;
+  const dim3 grid(N, p->n_q_heads + p->n_kv_heads);
+  uint16_t* hi = reinterpret_cast<uint16_t*>(ws + L.pooled_hi);
+  uint16_t* lo = reinterpret_cast<uint16_t*>(ws + L.pooled_lo);
+  float* energy = reinterpret_cast<float*>(ws + L.energy);
+  float* inv = reinterpret_cast<float*>(ws + L.inv_scale);
+  const int low_start = p->head_dim - p->d_low;
+  if (p->block == 128)
+    hipLaunchKernelGGL(pool_energy_kernel<128>, grid, dim3(256), 0, st, (const uint16_t*)q,
+                       (const uint16_t*)k, p->n_q_heads, p->seq_len, N, p->d_high, low_start, hi, lo,
+                       energy, pooled_q, pooled_k);
+  else
+    hipLaunchKernelGGL(pool_energy_kernel<64>, grid, dim3(256), 0, st, (const uint16_t*)q,
+                       (const uint16_t*)k, p->n_q_heads, p->seq_len, N, p->d_high, low_start, hi, lo,
+                       energy, pooled_q, pooled_k);
+  hipLaunchKernelGGL(scale_kernel, dim3(p->n_q_heads), dim3(64), 0, st, energy, p->n_q_heads,
+                     p->n_kv_heads, N, p->d_high, p->d_low,
+                     (p->flags & PRISM_FLAG_NO_CALIBRATION) ? 0 : 1, inv, scales);
+  return launch_status();
+}
+
+template <int MAXCH, bool DUMP>
+static int launch_select(const prism_params* p, char* ws, const EstimateWs& L, uint64_t* mask_bits,
+                         int32_t* row_ptr, float* lh, float* ll, hipStream_t st) {
+  const int N = p->seq_len / p->block;
+  const int strips = (N + kStripRows - 1) / kStripRows;
+  const size_t lds = (size_t)kStripRows * (((N + 15) / 16) * 16 + 4) * sizeof(float);
+  auto kern = select_kernel<MAXCH, DUMP>;
+  if (lds > 64 * 1024) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+      return PRISM_ERR_HIP;
+  }
+  hipLaunchKernelGGL(kern, dim3(strips, p->n_q_heads), dim3(256), lds, st,
+                     reinterpret_cast<const uint16_t*>(ws + L.pooled_hi),
+                     reinterpret_cast<const uint16_t*>(ws + L.pooled_lo),
+                     reinterpret_cast<const float*>(ws + L.inv_scale), p->n_q_heads, p->n_kv_heads, N,
+                     p->d_high, p->d_low, p->top_p, mask_bits, row_ptr, lh, ll);
+  return launch_status();
+}
+
+static int run_compaction(const prism_params* p, const uint64_t* mask_bits, int32_t* row_ptr,
+                          int32_t* col_idx, int64_t capacity, int32_t* info, bool count_rows,
+                          hipStream_t st) {
+  const int N = p->seq_len / p->block;
+  const int R = p->n_q_heads * N;
+  const int W = (N + 63) / 64;
+  if (count_rows)
+    hipLaunchKernelGGL(row_count_kernel, dim3((R + 255) / 256), dim3(256), 0, st, mask_bits, R, W,
+                       row_ptr);
+  hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(1024), 0, st, row_ptr, R, capacity, info);
+  hipLaunchKernelGGL(fill_kernel, dim3((R + 3) / 4), dim3(256), 0, st, mask_bits, R, W, row_ptr,
+                     col_idx, capacity);
+  return launch_status();
+}
+
+static int check_ws(const void* ws, size_t have, size_t need) {
+  if (ws == nullptr || (reinterpret_cast<uintptr_t>(ws) & 255u) != 0 || have < need)
+    return PRISM_ERR_WORKSPACE;
+  return PRISM_OK;
+}
+
+}  // namespace prism
+
+using namespace prism;
+
+extern "C" int prism_version(void) { return 100; }
+
+extern "C" const char* prism_status_string(int status) {
+  switch (status) {
+    case PRISM_OK: return "ok";
+    case PRISM_ERR_INVALID_ARG: return "invalid argument";
+    case PRISM_ERR_UNSUPPORTED: return "unsupported configuration";
+    case PRISM_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case PRISM_ERR_HIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+extern "C" int prism_estimate_workspace_bytes(const prism_params* params, size_t* bytes) {
+  if (bytes == nullptr) return PRISM_ERR_INVALID_ARG;
+  int rc = check_params(params);
+  if (rc != PRISM_OK) return rc;
+  *bytes = estimate_ws(params).total;
+  return PRISM_OK;
+}
+
+extern "C" int prism_estimate(const prism_params* params, const void* q_bf16, const void* k_bf16,
+                              uint64_t* mask_bits, int32_t* row_ptr, int32_t* col_idx,
+                              int64_t col_capacity, int32_t* info, void* workspace,
+                              size_t workspace_bytes, void* stream) {
+  int rc = check_params(params);
+  if (rc != PRISM_OK) return rc;
+  rc = check_bands(params);
+  if (rc != PRISM_OK) return rc;
+  if (!q_bf16 || !k_bf16 || !mask_bits || !row_ptr || !col_idx || !info || col_capacity < 0)
+    return PRISM_ERR_INVALID_ARG;
+  const EstimateWs L = estimate_ws(params);
+  rc = check_ws(workspace, workspace_bytes, L.total);
+  if (rc != PRISM_OK) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  char* ws = static_cast<char*>(workspace);
+  rc = run_pool_and_scale(params, q_bf16, k_bf16, ws, L, nullptr, nullptr, nullptr, st);
+  if (rc != PRISM_OK) return rc;
+  const int N = params->seq_len / params->block;
+  rc = (N <= 1024) ? launch_select<16, false>(params, ws, L, mask_bits, row_ptr, nullptr, nullptr, st)
+                   : launch_select<32, false>(params, ws, L, mask_bits, row_ptr, nullptr, nullptr, st);
+  if (rc != PRISM_OK) return rc;
+  return run_compaction(params, mask_bits, row_ptr, col_idx, col_capacity, info, false, st);
+}
+
+extern "C" int prism_block_scores(const prism_params* params, const void* q_bf16,
+                                  const void* k_bf16, float* pooled_q, float* pooled_k, float* scales,
+                                  float* logits_high, float* logits_low, void* workspace,
+                                  size_t workspace_bytes, void* stream) {
+  int rc = check_params(params);
+  if (rc != PRISM_OK) return rc;
+  rc = check_bands(params);
+  if (rc != PRISM_OK) return rc;
+  if (!q_bf16 || !k_bf16) return PRISM_ERR_INVALID_ARG;
+  const EstimateWs L = estimate_ws(params);
+  rc = check_ws(workspace, workspace_bytes, L.total);
+  if (rc != PRISM_OK) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  char* ws = static_cast<char*>(workspace);
+  rc = run_pool_and_scale(params, q_bf16, k_bf16, ws, L, pooled_q, pooled_k, scales, st);
+  if (rc != PRISM_OK) return rc;
+  if (logits_high == nullptr && logits_low == nullptr) return PRISM_OK;
+  return launch_select<16, true>(params, ws, L, nullptr, nullptr, logits_high, logits_low, st);
+}
+
+extern "C" int prism_mask_to_csr(const prism_params* params, const uint64_t* mask_bits,
+                                 int32_t* row_ptr, int32_t* col_idx, int64_t col_capacity,
+                                 int32_t* info, void* stream) {
+  int rc = check_params(params);
+  if (rc != PRISM_OK) return rc;
+  if (!mask_bits || !row_ptr || !col_idx || !info || col_capacity < 0) return PRISM_ERR_INVALID_ARG;
+  return run_compaction(params, mask_bits, row_ptr, col_idx, col_capacity, info, true,
+                        static_cast<hipStream_t>(stream));
+}
+
+extern "C" int prism_causal_csr(const prism_params* params, int32_t* row_ptr, int32_t* col_idx,
+                                int64_t col_capacity, void* stream) {
+  int rc = check_params(params);
+  if (rc != PRISM_OK) return rc;
+  if (!row_ptr || !col_idx) return PRISM_ERR_INVALID_ARG;
+  const int64_t N = params->seq_len / params->block;
+  if (col_capacity < (int64_t)params->n_q_heads * N * (N + 1) / 2) return PRISM_ERR_INVALID_ARG;
+  const int R = params->n_q_heads * (int)N;
+  hipLaunchKernelGGL(causal_csr_kernel, dim3((R + 1 + 3) / 4), dim3(256), 0,
+                     static_cast<hipStream_t>(stream), params->n_q_heads, (int)N, row_ptr, col_idx);
+  return launch_status();
+}

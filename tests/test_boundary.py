@@ -1,0 +1,104 @@
+"""Host-side checks of the C ABI (no GPU): the library loads, exports every symbol that
+include/prism.h declares, and rejects bad arguments before launching anything."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2602_08426_amd import binding as pb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "prism.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(pb.library_path()):
+        from paper_2602_08426_amd.build import build_library
+        build_library()
+    return pb._load()
+
+
+def _declared():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(prism_[a-z_]+)\s*\(", src)))
+
+
+def test_exports_every_declared_symbol(lib):
+    names = _declared()
+    assert set(names) == set(pb.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_version_and_status_strings(lib):
+    assert pb.prism_version() >= 100
+    assert pb.prism_status_string(0) == "ok"
+    for s in (-1, -2, -3, -4, -99):
+        assert isinstance(pb.prism_status_string(s), str) and pb.prism_status_string(s)
+
+
+def test_workspace_queries(lib):
+    p = pb.make_params(32, 8, 131072, 128)
+    n = pb.prism_estimate_workspace_bytes(p)
+    heads, N = 40, 1024
+    assert n >= heads * N * 128 * 2 * 2 + heads * N * 16
+    assert n < 64 << 20
+    assert pb.prism_sparse_attn_workspace_bytes(p) == 8 * 131072 * 128 * 2
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(n_q_heads=6, n_kv_heads=4), -1),          # h % h_kv
+    (dict(n_q_heads=0), -1),
+    (dict(head_dim=64), -2),
+    (dict(block=32), -2),
+    (dict(seq_len=1000), -2),                        # L % B
+    (dict(seq_len=128 * 4096), -2),                  # N > 2048
+])
+def test_bad_geometry_is_rejected(lib, kw, status):
+    base = dict(n_q_heads=4, n_kv_heads=2, seq_len=1024, block=128)
+    base.update(kw)
+    p = pb.make_params(**base)
+    n = ctypes.c_size_t(0)
+    assert lib.prism_estimate_workspace_bytes(ctypes.byref(p), ctypes.byref(n)) == status
+    assert lib.prism_sparse_attn_workspace_bytes(ctypes.byref(p), ctypes.byref(n)) == status
+
+
+@pytest.mark.parametrize("kw", [dict(d_high=48), dict(d_low=160), dict(d_high=0, d_low=0),
+                                dict(top_p=0.0), dict(top_p=1.5), dict(top_p=float("nan"))])
+def test_bad_bands_are_rejected_before_launch(lib, kw):
+    base = dict(n_q_heads=4, n_kv_heads=2, seq_len=1024, block=128)
+    base.update(kw)
+    p = pb.make_params(**base)
+    fake = ctypes.c_void_p(256)     # never dereferenced: validation fails first
+    rc = lib.prism_estimate(ctypes.byref(p), fake, fake, fake, fake, fake, 10, fake, fake, 1 << 30, None)
+    assert rc == -1
+
+
+def test_null_pointers_and_workspace_are_rejected(lib):
+    p = pb.make_params(4, 2, 1024, 128)
+    fake = ctypes.c_void_p(256)
+    assert lib.prism_estimate(ctypes.byref(p), None, fake, fake, fake, fake, 10, fake, fake, 1 << 30, None) == -1
+    assert lib.prism_estimate(ctypes.byref(p), fake, fake, fake, fake, fake, 10, fake, None, 1 << 30, None) == -3
+    assert lib.prism_estimate(ctypes.byref(p), fake, fake, fake, fake, fake, 10, fake, fake, 16, None) == -3
+    assert lib.prism_estimate(ctypes.byref(p), fake, fake, fake, fake, fake, 10, fake,
+                              ctypes.c_void_p(264), 1 << 30, None) == -3           # misaligned
+    assert lib.prism_sparse_attn(ctypes.byref(p), fake, fake, None, fake, fake, 0, fake, None, fake, 1 << 30, None) == -1
+    assert lib.prism_sparse_attn(ctypes.byref(p), fake, fake, fake, fake, fake, 0, fake, None, fake, 16, None) == -3
+    assert lib.prism_causal_csr(ctypes.byref(p), fake, fake, 3, None) == -1        # capacity too small
+    assert lib.prism_mask_to_csr(ctypes.byref(p), None, fake, fake, 3, fake, None) == -1
+    assert lib.prism_estimate(None, fake, fake, fake, fake, fake, 10, fake, fake, 1 << 30, None) == -1
+
+
+def test_mask_pack_roundtrip():
+    import numpy as np
+    from tests.gpu_util import pack_mask, unpack_mask
+    rng = np.random.default_rng(0)
+    for N in (1, 5, 64, 65, 130):
+        m = rng.random((3, N, N)) < 0.3
+        w = pack_mask(m)
+        assert w.shape == (3, N, (N + 63) // 64)
+        np.testing.assert_array_equal(unpack_mask(w, N), m)
+        assert ((w[0, 0, 0] >> np.uint64(0)) & np.uint64(1)) == m[0, 0, 0]

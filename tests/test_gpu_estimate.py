@@ -1,0 +1,187 @@
+"""GPU parity: prism_estimate / prism_block_scores / CSR entry points vs the CPU oracle.
+
+Bar: integer outputs (CSR vs the bit mask, caller-mask compaction, causal lists) bit-exact;
+block masks exact outside the oracle's don't-care set (scores within 1e-3 of the selection
+cutoff, or cumulative mass within 1e-3 of p); pooled vectors / scales / logits within
+fp32-accumulation tolerances far below that margin.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import prism_oracle as orc
+from paper_2602_08426_amd import binding as pb
+from paper_2602_08426_amd import workloads as wl
+from tests import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+
+def _inputs(w):
+    Qb, Kb, Vb = wl.generate(w)
+    return Qb, Kb, Vb, pb.bf16_bits_to_device(Qb), pb.bf16_bits_to_device(Kb)
+
+
+def _check_mask(w, gpu_mask, sel, p, max_dont_care=0.02):
+    tol = orc.selection_tolerance(sel, p)
+    missing = tol.must & ~gpu_mask
+    extra = tol.must_not & gpu_mask
+    assert not missing.any(), f"{w.name}: {missing.sum()} must-select blocks missing, first {np.argwhere(missing)[:5]}"
+    assert not extra.any(), f"{w.name}: {extra.sum()} forbidden blocks selected, first {np.argwhere(extra)[:5]}"
+    assert tol.dont_care_fraction < max_dont_care
+    return float((gpu_mask != sel.mask).sum()) / gpu_mask[0].size
+
+
+def _check_csr(res, h, N):
+    mask, row_ptr, col = res["mask"], res["row_ptr"], res["col_idx"]
+    rp_ref, col_ref = orc.mask_to_csr(mask)
+    np.testing.assert_array_equal(row_ptr, rp_ref)
+    np.testing.assert_array_equal(col[:len(col_ref)], col_ref)
+    assert res["info"][0] == len(col_ref) and res["info"][1] == 0
+    assert not np.triu(mask, 1).any()
+
+
+CASES = [
+    ("c1_2k_slash", None, None, None, None),
+    ("c2_llama_8k", 128 * 37, 8, 2, None),       # ragged strip (N = 37), GQA 4
+    ("c2_llama_8k", 8192, 8, 4, 64),             # block 64, N = 128
+    ("c5_qwen_64k", 128 * 100, 7, 1, None),      # group of 7, lognormal keys, p = 0.93
+    ("c2_llama_8k", 128, 4, 4, None),            # a single block
+]
+
+
+@pytest.mark.parametrize("name,L,h,hkv,B", CASES)
+def test_scores_and_mask_match_oracle(name, L, h, hkv, B):
+    w = wl.WORKLOADS[name]
+    if L is not None:
+        w = wl.small_variant(w, L, h, hkv, B)
+    print(f"case {w.name} h={w.n_q_heads}/{w.n_kv_heads} L={w.seq_len} B={w.block}", flush=True)
+    Qb, Kb, _, qd, kd = _inputs(w)
+    sel = orc.prism_select(orc.bf16_to_f64(Qb), orc.bf16_to_f64(Kb), w.d_high, w.d_low, w.block, w.top_p)
+    params = gu.params_for(w)
+    N = w.n_blocks
+
+    sc = gu.gpu_block_scores(params, qd, kd)
+    np.testing.assert_allclose(sc["pooled_q"], sel.q_pooled, rtol=2e-6, atol=2e-6)
+    np.testing.assert_allclose(sc["pooled_k"], sel.k_pooled, rtol=2e-6, atol=2e-6)
+    np.testing.assert_allclose(sc["scales"][:, 0], sel.scale["high"], rtol=2e-5)
+    np.testing.assert_allclose(sc["scales"][:, 1], sel.scale["low"], rtol=2e-5)
+    tri = np.tril(np.ones((N, N), bool))
+    for z in ("high", "low"):
+        got, ref = sc[f"logits_{z}"][:, tri], sel.logits[z][:, tri]
+        err = np.abs(got - ref)
+        assert (err <= 1e-4 + 2e-5 * np.abs(ref)).all(), (z, err.max(), np.abs(ref).max())
+        assert np.isnan(sc[f"logits_{z}"][:, ~tri]).all()        # v > u never written
+
+    res = gu.gpu_estimate(params, qd, kd)
+    _check_mask(w, res["mask"], sel, w.top_p)
+    _check_csr(res, w.n_q_heads, N)
+    # determinism: a second run gives the same bits
+    res2 = gu.gpu_estimate(params, qd, kd)
+    np.testing.assert_array_equal(res["words"], res2["words"])
+    np.testing.assert_array_equal(res["col_idx"][:res["info"][0]], res2["col_idx"][:res2["info"][0]])
+
+
+@pytest.mark.parametrize("over,okw", [
+    (dict(top_p=1.0), dict(p=1.0)),
+    (dict(top_p=0.5), dict(p=0.5)),
+    (dict(d_high=0), dict(d_h=0)),
+    (dict(d_low=0, d_high=64), dict(d_l=0)),
+    (dict(d_high=128, d_low=128), dict(d_h=128, d_l=128)),
+    (dict(d_high=32, d_low=64), dict(d_h=32, d_l=64)),
+    (dict(flags=pb.PRISM_FLAG_NO_CALIBRATION), dict(calibrate=False)),
+])
+def test_parameter_variants(over, okw):
+    w = wl.small_variant(wl.WORKLOADS["c3_llama_32k"], 128 * 50, 4, 2)
+    Qb, Kb, _, qd, kd = _inputs(w)
+    kw = dict(d_h=w.d_high, d_l=w.d_low, p=w.top_p, calibrate=True)
+    kw.update(okw)
+    sel = orc.prism_select(orc.bf16_to_f64(Qb), orc.bf16_to_f64(Kb), kw["d_h"], kw["d_l"], w.block,
+                           kw["p"], calibrate=kw["calibrate"])
+    params = gu.params_for(w, **over)
+    res = gu.gpu_estimate(params, qd, kd)
+    _check_mask(w, res["mask"], sel, kw["p"], max_dont_care=0.05)
+    _check_csr(res, w.n_q_heads, w.n_blocks)
+    if kw["p"] >= 1.0:
+        np.testing.assert_array_equal(res["mask"], np.tril(np.ones((50, 50), bool))[None].repeat(4, 0))
+
+
+def test_many_blocks_path_n_2048():
+    """N = 2048 (128K tokens at B = 64): the 32-registers-per-lane selection variant."""
+    w = wl.small_variant(wl.WORKLOADS["c4_llama_128k"], 131072, 1, 1, 64)
+    Qb, Kb, _, qd, kd = _inputs(w)
+    sel = orc.prism_select(orc.bf16_to_f64(Qb), orc.bf16_to_f64(Kb), w.d_high, w.d_low, w.block, w.top_p)
+    res = gu.gpu_estimate(gu.params_for(w), qd, kd)
+    _check_mask(w, res["mask"], sel, w.top_p)
+    _check_csr(res, 1, w.n_blocks)
+
+
+def test_degenerate_inputs_zero_and_constant():
+    """All-zero inputs: zero energy -> flat logits -> exact ties, taken in ascending block
+    order until the mass reaches p (same rule as the oracle's stable sort)."""
+    h, L, B, N = 2, 128 * 20, 128, 20
+    z = np.zeros((h, L, 128), np.uint16)
+    qd, kd = pb.bf16_bits_to_device(z), pb.bf16_bits_to_device(z)
+    sel = orc.prism_select(orc.bf16_to_f64(z), orc.bf16_to_f64(z), 64, 96, B, 0.8)
+    res = gu.gpu_estimate(pb.make_params(h, h, L, B, top_p=0.8), qd, kd)
+    # ties at the cutoff are "don't care" for parity, but the count per row must be the
+    # minimal one up to one block of rounding
+    cnt_g, cnt_o = res["mask"].sum(-1), sel.mask.sum(-1)
+    assert (np.abs(cnt_g - cnt_o) <= 1).all()
+    assert (res["mask"].sum(-1) >= 1).all() and not np.triu(res["mask"], 1).any()
+    for u in range(N):                                   # lowest indices first
+        k = cnt_g[0, u]
+        assert res["mask"][0, u, :k].all()
+    _check_csr(res, h, N)
+
+
+def test_capacity_overflow_is_flagged_not_written():
+    w = wl.small_variant(wl.WORKLOADS["c2_llama_8k"], 2048, 4, 2)
+    _, _, _, qd, kd = _inputs(w)
+    params = gu.params_for(w)
+    full = gu.gpu_estimate(params, qd, kd)
+    nnz = int(full["info"][0])
+    cap = nnz // 2
+    mask_bits, row_ptr, _, info = pb.alloc_estimate_outputs(params)
+    col = torch.full((nnz + 8,), -7, dtype=torch.int32, device="cuda")
+    ws = pb.alloc_workspace(pb.prism_estimate_workspace_bytes(params))
+    pb.prism_estimate(params, qd, kd, mask_bits, row_ptr, col, cap, info, ws)
+    torch.cuda.synchronize()
+    inf = info.cpu().numpy()
+    assert inf[0] == nnz and inf[1] == 1
+    c = col.cpu().numpy()
+    np.testing.assert_array_equal(c[:cap], full["col_idx"][:cap])
+    assert (c[cap:] == -7).all()                         # nothing written past the capacity
+
+
+@pytest.mark.parametrize("h,N,B", [(3, 37, 128), (2, 130, 64), (1, 1, 128), (5, 64, 128)])
+def test_mask_to_csr_and_causal_csr_exact(h, N, B):
+    rng = np.random.default_rng(N)
+    mask = np.tril(rng.random((h, N, N)) < 0.3)
+    mask[:, N // 2, :] = False                          # an empty row
+    params = pb.make_params(h, h, N * B, B)
+    words = torch.from_numpy(gu.pack_mask(mask).view(np.int64)).cuda()
+    _, row_ptr, col_idx, info = pb.alloc_estimate_outputs(params)
+    pb.prism_mask_to_csr(params, words, row_ptr, col_idx, col_idx.numel(), info)
+    torch.cuda.synchronize()
+    rp_ref, col_ref = orc.mask_to_csr(mask)
+    np.testing.assert_array_equal(row_ptr.cpu().numpy(), rp_ref)
+    np.testing.assert_array_equal(col_idx.cpu().numpy()[:len(col_ref)], col_ref)
+    assert info.cpu().numpy()[0] == len(col_ref)
+
+    pb.prism_causal_csr(params, row_ptr, col_idx, col_idx.numel())
+    torch.cuda.synchronize()
+    rp_ref, col_ref = orc.mask_to_csr(np.tril(np.ones((h, N, N), bool)))
+    np.testing.assert_array_equal(row_ptr.cpu().numpy(), rp_ref)
+    np.testing.assert_array_equal(col_idx.cpu().numpy()[:len(col_ref)], col_ref)
+
+
+def test_device_call_errors_raise():
+    p = pb.make_params(4, 2, 1024, 128)
+    q = torch.zeros((4, 1024, 128), dtype=torch.bfloat16, device="cuda")
+    k = torch.zeros((2, 1024, 128), dtype=torch.bfloat16, device="cuda")
+    mask_bits, row_ptr, col_idx, info = pb.alloc_estimate_outputs(p)
+    with pytest.raises(pb.PrismError) as e:
+        pb.prism_estimate(p, q, k, mask_bits, row_ptr, col_idx, col_idx.numel(), info,
+                          pb.alloc_workspace(256))
+    assert e.value.status == -3
