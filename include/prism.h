@@ -147,6 +147,22 @@ int prism_sparse_attn(const prism_params* params,
                       void* out_bf16, float* lse,
                       void* workspace, size_t workspace_bytes, void* stream);
 
+/* The two halves of prism_sparse_attn, for callers that reuse one V image for several
+ * attention calls (or time the attention kernel alone):
+ *   prism_v_image          : writes the transposed, block-tiled copy of V that the attention
+ *                            kernel reads into `v_image` (prism_sparse_attn_workspace_bytes()
+ *                            bytes, 256-byte aligned).
+ *   prism_sparse_attn_pre  : same computation and arguments as prism_sparse_attn, with the
+ *                            image in place of V.
+ * prism_sparse_attn(...) == prism_v_image(..., workspace) ; prism_sparse_attn_pre(..., workspace). */
+int prism_v_image(const prism_params* params, const void* v_bf16, void* v_image,
+                  size_t v_image_bytes, void* stream);
+
+int prism_sparse_attn_pre(const prism_params* params,
+                          const void* q_bf16, const void* k_bf16, const void* v_image,
+                          const int32_t* row_ptr, const int32_t* col_idx, int64_t col_count,
+                          void* out_bf16, float* lse, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

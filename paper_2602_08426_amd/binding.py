@@ -43,7 +43,8 @@ class prism_params(ctypes.Structure):
 
 EXPORTS = ("prism_version", "prism_status_string", "prism_estimate_workspace_bytes",
            "prism_estimate", "prism_block_scores", "prism_mask_to_csr", "prism_causal_csr",
-           "prism_sparse_attn_workspace_bytes", "prism_sparse_attn")
+           "prism_sparse_attn_workspace_bytes", "prism_sparse_attn", "prism_v_image",
+           "prism_sparse_attn_pre")
 
 
 def _load() -> ctypes.CDLL:
@@ -67,6 +68,8 @@ def _load() -> ctypes.CDLL:
     lib.prism_causal_csr.argtypes = [P, vp, vp, i64, vp]
     lib.prism_sparse_attn_workspace_bytes.argtypes = [P, ctypes.POINTER(sz)]
     lib.prism_sparse_attn.argtypes = [P, vp, vp, vp, vp, vp, i64, vp, vp, vp, sz, vp]
+    lib.prism_v_image.argtypes = [P, vp, vp, sz, vp]
+    lib.prism_sparse_attn_pre.argtypes = [P, vp, vp, vp, vp, vp, i64, vp, vp, vp]
     for name in EXPORTS[2:]:
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
@@ -175,6 +178,19 @@ def prism_sparse_attn(params: prism_params, q: torch.Tensor, k: torch.Tensor, v:
                                      _ptr(col_idx), col_count, _ptr(out), _ptr(lse),
                                      _ptr(workspace), workspace.numel(), _stream()),
            "prism_sparse_attn")
+
+
+def prism_v_image(params: prism_params, v: torch.Tensor, v_image: torch.Tensor) -> None:
+    _check(_load().prism_v_image(ctypes.byref(params), _ptr(v), _ptr(v_image), v_image.numel(),
+                                 _stream()), "prism_v_image")
+
+
+def prism_sparse_attn_pre(params: prism_params, q: torch.Tensor, k: torch.Tensor,
+                          v_image: torch.Tensor, row_ptr: torch.Tensor, col_idx: torch.Tensor,
+                          col_count: int, out: torch.Tensor, lse: Optional[torch.Tensor]) -> None:
+    _check(_load().prism_sparse_attn_pre(ctypes.byref(params), _ptr(q), _ptr(k), _ptr(v_image),
+                                         _ptr(row_ptr), _ptr(col_idx), col_count, _ptr(out),
+                                         _ptr(lse), _stream()), "prism_sparse_attn_pre")
 
 
 # ---- conveniences for callers holding numpy bf16 bit patterns --------------------------

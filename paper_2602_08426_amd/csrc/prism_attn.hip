@@ -55,11 +55,12 @@ __global__ __launch_bounds__(256) void vt_image_kernel(const uint16_t* __restric
 // =====================================================================================
 // Sparse attention kernel.  One workgroup per (q-head, q-block); BLK/32 waves of 32 queries.
 // LDS: K tile [BLK][128] bf16 and V^T tile [128][BLK] bf16, 16-byte chunks XOR-swizzled by
-// row so that both the row-major writes and the 16-lane column reads are conflict-free.
+// row so that the 16-lane column reads are conflict-free.  Tiles are copied global -> LDS
+// asynchronously, without passing through registers.
 // Loop per listed kv block (V and the next K are fetched while the MFMAs of the other
 // operand run):
-//     K(j) in LDS | issue V(j) loads | S^T = K Q^T | online softmax | V(j) -> LDS | barrier
-//     issue K(j+1) loads | O^T += V^T P^T | K(j+1) -> LDS | barrier
+//     K(j) in LDS | start V(j) copy | S^T = K Q^T | online softmax | wait V(j) | barrier
+//     start K(j+1) copy | O^T += V^T P^T | wait K(j+1) | barrier
 // =====================================================================================
 template <int BLK>
 struct AttnCfg {
@@ -71,37 +72,41 @@ struct AttnCfg {
   static constexpr int kVtCpr = BLK / 8;                   // chunks per V^T row
 };
 
-template <int BLK>
-__device__ __forceinline__ void load_tile_regs(const uint16_t* __restrict__ src, uint4 (&r)[8], int t) {
-  using C = AttnCfg<BLK>;
-#pragma unroll
-  for (int i = 0; i < C::kPerThread; ++i)
-    r[i] = *reinterpret_cast<const uint4*>(src + (size_t)(i * C::kThreads + t) * 8);
-}
+// Asynchronous global -> LDS tile copies (global_load_lds_dwordx4: every lane fetches 16
+// bytes from its own global address and the wave's 64 pieces land contiguously in LDS at
+// M0-base + 16*lane).  LDS slot p (16-byte units) of a tile belongs to (row, c') with
+// c' the swizzled chunk position; the lane that fills it reads global chunk
+// c = c' ^ (row mod chunks-per-row), i.e. the swizzle is applied on the global side.
+typedef const __attribute__((address_space(1))) void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
 
-// K tile: rows of 16 chunks (256 B).
 template <int BLK>
-__device__ __forceinline__ void store_k_tile(char* lds, const uint4 (&r)[8], int t) {
+__device__ __forceinline__ void async_load_k_tile(const uint16_t* __restrict__ src, char* lds, int t) {
   using C = AttnCfg<BLK>;
+  const int wave_base = (t & ~63);
 #pragma unroll
   for (int i = 0; i < C::kPerThread; ++i) {
-    const int idx = i * C::kThreads + t;
-    const int row = idx >> 4, c = idx & 15;
-    *reinterpret_cast<uint4*>(lds + row * 256 + ((c ^ (row & 15)) << 4)) = r[i];
+    const int p = i * C::kThreads + t;
+    const int row = p >> 4, c = (p & 15) ^ (row & 15);
+    __builtin_amdgcn_global_load_lds((gptr_t)(src + row * kHeadDim + c * 8),
+                                     (lptr_t)(lds + (i * C::kThreads + wave_base) * 16), 16, 0, 0);
   }
 }
 
-// V^T tile: 128 rows of kVtCpr chunks.
 template <int BLK>
-__device__ __forceinline__ void store_vt_tile(char* lds, const uint4 (&r)[8], int t) {
+__device__ __forceinline__ void async_load_vt_tile(const uint16_t* __restrict__ src, char* lds, int t) {
   using C = AttnCfg<BLK>;
+  const int wave_base = (t & ~63);
 #pragma unroll
   for (int i = 0; i < C::kPerThread; ++i) {
-    const int idx = i * C::kThreads + t;
-    const int row = idx / C::kVtCpr, c = idx % C::kVtCpr;
-    *reinterpret_cast<uint4*>(lds + row * (BLK * 2) + ((c ^ (row & (C::kVtCpr - 1))) << 4)) = r[i];
+    const int p = i * C::kThreads + t;
+    const int row = p / C::kVtCpr, c = (p % C::kVtCpr) ^ (row & (C::kVtCpr - 1));
+    __builtin_amdgcn_global_load_lds((gptr_t)(src + row * BLK + c * 8),
+                                     (lptr_t)(lds + (i * C::kThreads + wave_base) * 16), 16, 0, 0);
   }
 }
+
+__device__ __forceinline__ void wait_async_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 template <int BLK>
 __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
@@ -150,14 +155,22 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
   float l_run = 0.f;                // this lane's share of the running sum
   const float sm_scale = 1.4426950408889634f * 0.08838834764831845f;   // log2(e) / sqrt(128)
 
-  uint4 stage[8];
-  // find the first valid entry (v <= u) and stage its K tile
+  // LDS read offsets of this lane inside a 32-row slab: row l32, swizzled chunk
+  // (2*step + hf) ^ (row mod chunks-per-row).  The K tile has 16 chunks per row; the V^T
+  // tile has BLK/8 (for BLK = 128 the two tables coincide).
+  constexpr int kDepth = 4;                                // LDS reads kept in flight
+  int koff[8], voff[KT * 2];
+#pragma unroll
+  for (int st = 0; st < 8; ++st) koff[st] = l32 * 256 + (((2 * st + hf) ^ (l32 & 15)) << 4);
+#pragma unroll
+  for (int st = 0; st < KT * 2; ++st)
+    voff[st] = l32 * (BLK * 2) + (((2 * st + hf) ^ (l32 & (C::kVtCpr - 1))) << 4);
+
+  // find the first valid entry (v <= u) and start its K tile
   int64_t it = beg;
   while (it < end && (col_idx[it] < 0 || col_idx[it] > u)) ++it;
-  if (it < end) {
-    load_tile_regs<BLK>(kbase + (size_t)col_idx[it] * BLK * kHeadDim, stage, t);
-    store_k_tile<BLK>(lds_k, stage, t);
-  }
+  if (it < end) async_load_k_tile<BLK>(kbase + (size_t)col_idx[it] * BLK * kHeadDim, lds_k, t);
+  wait_async_loads();
   __syncthreads();
 
   while (it < end) {
@@ -165,21 +178,34 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
     int64_t nx = it + 1;
     while (nx < end && (col_idx[nx] < 0 || col_idx[nx] > u)) ++nx;
 
-    // ---- V(j) loads in flight during S^T ----
-    load_tile_regs<BLK>(vbase + (size_t)v * kHeadDim * BLK, stage, t);
+    // ---- V(j) -> LDS, in flight during S^T and the softmax ----
+    async_load_vt_tile<BLK>(vbase + (size_t)v * kHeadDim * BLK, lds_v, t);
 
     // ---- S^T = K Q^T ----
+    // Flat software pipeline over the KT*8 (tile, k-step) pairs: the LDS read of step
+    // i + kDepth is issued right after the MFMA of step i, in source order.
     f32x16 sacc[KT];
 #pragma unroll
     for (int kt = 0; kt < KT; ++kt) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) sacc[kt][r] = 0.f;
-      const int krow = kt * 32 + l32;
-      const char* kp = lds_k + krow * 256;
+    }
+    {
+      constexpr int kSteps = KT * 8;
+      bf16x8 fr[kDepth];
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(kp + (((2 * ks + hf) ^ (krow & 15)) << 4));
-        sacc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], sacc[kt], 0, 0, 0);
+      for (int i = 0; i < kDepth; ++i)
+        fr[i] = *reinterpret_cast<const bf16x8*>(lds_k + (i >> 3) * 8192 + koff[i & 7]);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int i = 0; i < kSteps; ++i) {
+        const int kt = i >> 3, ks = i & 7;
+        sacc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i % kDepth], qf[ks], sacc[kt], 0, 0, 0);
+        if (i + kDepth < kSteps) {
+          const int j = i + kDepth;
+          fr[i % kDepth] = *reinterpret_cast<const bf16x8*>(lds_k + (j >> 3) * 8192 + koff[j & 7]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
 
@@ -203,8 +229,15 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
       for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[kt][r]);
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
     const float m_new = fmaxf(m_run, mx * sm_scale);       // finite: every query sees a key
-    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-    m_run = m_new;
+    if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) { // some query's max moved: rescale
+      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+      l_run *= alpha;
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[i][r] *= alpha;
+      m_run = m_new;
+    }
     float psum = 0.f;
     bf16x8 pf[KT][2];
 #pragma unroll
@@ -223,37 +256,37 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
         }
       }
     }
-    l_run = l_run * alpha + psum;
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) oacc[i][r] *= alpha;
+    l_run += psum;
 
-    // ---- V(j) -> LDS ----
-    store_vt_tile<BLK>(lds_v, stage, t);
-    __syncthreads();                 // V visible; everyone is done reading K(j)
+    wait_async_loads();              // this wave's share of V(j) has landed
+    __syncthreads();                 // V(j) complete; everyone is done reading K(j)
 
-    // ---- K(j+1) loads in flight during PV ----
-    if (nx < end) load_tile_regs<BLK>(kbase + (size_t)col_idx[nx] * BLK * kHeadDim, stage, t);
+    // ---- K(j+1) -> LDS, in flight during PV ----
+    if (nx < end) async_load_k_tile<BLK>(kbase + (size_t)col_idx[nx] * BLK * kHeadDim, lds_k, t);
 
-    // ---- O^T += V^T P^T ----
+    // ---- O^T += V^T P^T ----  (same flat pipeline over the 4*KT*2 (d-tile, k-step) pairs)
+    {
+      constexpr int kPer = KT * 2;                   // k-steps per d-tile
+      constexpr int kSteps = 4 * kPer;
+      bf16x8 fr[kDepth];
 #pragma unroll
-    for (int dt = 0; dt < 4; ++dt) {
-      const int vrow = dt * 32 + l32;
-      const char* vp = lds_v + vrow * (BLK * 2);
+      for (int i = 0; i < kDepth; ++i)
+        fr[i] = *reinterpret_cast<const bf16x8*>(lds_v + (i / kPer) * (32 * BLK * 2) + voff[i % kPer]);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int kt = 0; kt < KT; ++kt)
-#pragma unroll
-        for (int s = 0; s < 2; ++s) {
-          const int c = 2 * (2 * kt + s) + hf;
-          const bf16x8 a =
-              *reinterpret_cast<const bf16x8*>(vp + ((c ^ (vrow & (C::kVtCpr - 1))) << 4));
-          oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[kt][s], oacc[dt], 0, 0, 0);
+      for (int i = 0; i < kSteps; ++i) {
+        const int dt = i / kPer, st = i % kPer;
+        oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i % kDepth], pf[st >> 1][st & 1], oacc[dt], 0, 0, 0);
+        if (i + kDepth < kSteps) {
+          const int j = i + kDepth;
+          fr[i % kDepth] = *reinterpret_cast<const bf16x8*>(lds_v + (j / kPer) * (32 * BLK * 2) + voff[j % kPer]);
         }
+        __builtin_amdgcn_sched_barrier(0);
+      }
     }
 
-    if (nx < end) store_k_tile<BLK>(lds_k, stage, t);
-    __syncthreads();                 // K(j+1) visible; everyone is done reading V(j)
+    wait_async_loads();              // this wave's share of K(j+1) has landed
+    __syncthreads();                 // K(j+1) complete; everyone is done reading V(j)
     it = nx;
   }
 
@@ -292,6 +325,55 @@ extern "C" int prism_sparse_attn_workspace_bytes(const prism_params* params, siz
   return PRISM_OK;
 }
 
+static int check_image(const prism_params* params, const void* img, size_t bytes) {
+  const size_t need = (size_t)params->n_kv_heads * params->seq_len * kHeadDim * 2;
+  if (img == nullptr || (reinterpret_cast<uintptr_t>(img) & 255u) != 0 || bytes < need)
+    return PRISM_ERR_WORKSPACE;
+  return PRISM_OK;
+}
+
+extern "C" int prism_v_image(const prism_params* params, const void* v_bf16, void* v_image,
+                             size_t v_image_bytes, void* stream) {
+  int rc = check_params(params);
+  if (rc != PRISM_OK) return rc;
+  if (!v_bf16) return PRISM_ERR_INVALID_ARG;
+  rc = check_image(params, v_image, v_image_bytes);
+  if (rc != PRISM_OK) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int N = params->seq_len / params->block;
+  if (params->block == 128)
+    hipLaunchKernelGGL(vt_image_kernel<128>, dim3(N, params->n_kv_heads), dim3(256), 0, st,
+                       (const uint16_t*)v_bf16, (uint16_t*)v_image, params->seq_len, N);
+  else
+    hipLaunchKernelGGL(vt_image_kernel<64>, dim3(N, params->n_kv_heads), dim3(256), 0, st,
+                       (const uint16_t*)v_bf16, (uint16_t*)v_image, params->seq_len, N);
+  return launch_status();
+}
+
+extern "C" int prism_sparse_attn_pre(const prism_params* params, const void* q_bf16,
+                                     const void* k_bf16, const void* v_image, const int32_t* row_ptr,
+                                     const int32_t* col_idx, int64_t col_count, void* out_bf16,
+                                     float* lse, void* stream) {
+  int rc = check_params(params);
+  if (rc != PRISM_OK) return rc;
+  if (!q_bf16 || !k_bf16 || !row_ptr || !col_idx || !out_bf16 || col_count < 0)
+    return PRISM_ERR_INVALID_ARG;
+  if (v_image == nullptr || (reinterpret_cast<uintptr_t>(v_image) & 255u) != 0)
+    return PRISM_ERR_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int N = params->seq_len / params->block;
+  const int h = params->n_q_heads, h_kv = params->n_kv_heads, L = params->seq_len;
+  if (params->block == 128)
+    hipLaunchKernelGGL(sparse_attn_kernel<128>, dim3(h * N), dim3(AttnCfg<128>::kThreads), 0, st,
+                       (const uint16_t*)q_bf16, (const uint16_t*)k_bf16, (const uint16_t*)v_image,
+                       row_ptr, col_idx, col_count, (uint16_t*)out_bf16, lse, h, h_kv, L, N);
+  else
+    hipLaunchKernelGGL(sparse_attn_kernel<64>, dim3(h * N), dim3(AttnCfg<64>::kThreads), 0, st,
+                       (const uint16_t*)q_bf16, (const uint16_t*)k_bf16, (const uint16_t*)v_image,
+                       row_ptr, col_idx, col_count, (uint16_t*)out_bf16, lse, h, h_kv, L, N);
+  return launch_status();
+}
+
 extern "C" int prism_sparse_attn(const prism_params* params, const void* q_bf16, const void* k_bf16,
                                  const void* v_bf16, const int32_t* row_ptr, const int32_t* col_idx,
                                  int64_t col_count, void* out_bf16, float* lse, void* workspace,
@@ -300,26 +382,10 @@ extern "C" int prism_sparse_attn(const prism_params* params, const void* q_bf16,
   if (rc != PRISM_OK) return rc;
   if (!q_bf16 || !k_bf16 || !v_bf16 || !row_ptr || !col_idx || !out_bf16 || col_count < 0)
     return PRISM_ERR_INVALID_ARG;
-  const size_t need = (size_t)params->n_kv_heads * params->seq_len * kHeadDim * 2;
-  if (workspace == nullptr || (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0 ||
-      workspace_bytes < need)
-    return PRISM_ERR_WORKSPACE;
-  hipStream_t st = static_cast<hipStream_t>(stream);
-  const int N = params->seq_len / params->block;
-  const int h = params->n_q_heads, h_kv = params->n_kv_heads, L = params->seq_len;
-  uint16_t* vt = static_cast<uint16_t*>(workspace);
-  if (params->block == 128) {
-    hipLaunchKernelGGL(vt_image_kernel<128>, dim3(N, h_kv), dim3(256), 0, st,
-                       (const uint16_t*)v_bf16, vt, L, N);
-    hipLaunchKernelGGL(sparse_attn_kernel<128>, dim3(h * N), dim3(AttnCfg<128>::kThreads), 0, st,
-                       (const uint16_t*)q_bf16, (const uint16_t*)k_bf16, vt, row_ptr, col_idx,
-                       col_count, (uint16_t*)out_bf16, lse, h, h_kv, L, N);
-  } else {
-    hipLaunchKernelGGL(vt_image_kernel<64>, dim3(N, h_kv), dim3(256), 0, st,
-                       (const uint16_t*)v_bf16, vt, L, N);
-    hipLaunchKernelGGL(sparse_attn_kernel<64>, dim3(h * N), dim3(AttnCfg<64>::kThreads), 0, st,
-                       (const uint16_t*)q_bf16, (const uint16_t*)k_bf16, vt, row_ptr, col_idx,
-                       col_count, (uint16_t*)out_bf16, lse, h, h_kv, L, N);
-  }
-  return launch_status();
+  rc = check_image(params, workspace, workspace_bytes);
+  if (rc != PRISM_OK) return rc;
+  rc = prism_v_image(params, v_bf16, workspace, workspace_bytes, stream);
+  if (rc != PRISM_OK) return rc;
+  return prism_sparse_attn_pre(params, q_bf16, k_bf16, workspace, row_ptr, col_idx, col_count,
+                               out_bf16, lse, stream);
 }

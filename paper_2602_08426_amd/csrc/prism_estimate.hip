@@ -3,8 +3,8 @@
 // Pipeline (Sec. 3.4 "Prism: Spectral-Aware Block Selection", App. C "Top-P Block Selection"):
 //   pool_energy_kernel : mean pooling of Q and K blocks + per-block band energies   (HBM-bound)
 //   scale_kernel       : RMS energies -> tau_z -> 1 / (sqrt(d_z) tau_z) per q-head
-//   select_kernel      : dual-band block logits on bf16 MFMA (pooled vectors split into a
-//                        bf16 high and low part), row softmax, top-p, union, bit rows
+//   select_kernel      : dual-band block logits on bf16 MFMA (pooled vectors split into
+//                        three bf16 terms), row softmax, top-p, union, bit rows
 //   scan/fill kernels  : bit rows -> CSR index lists
 #include "prism_common.h"
 
@@ -14,16 +14,16 @@ namespace prism {
 // Mean pooling (Eq. "mean-pooling") and band energies (Sec. 3.4, RMS definition).
 // One workgroup per (block, head); 256 threads read B x 128 bf16 = B*256 contiguous bytes
 // as 16-byte pieces: thread t owns dims 8*(t%16)..+7 of rows t/16, t/16+16, ...
-// Outputs per (head, block): pooled vector as bf16 hi + bf16 lo (hi + lo carries 16
-// significant bits), optional fp32 copy, and the three sums of squares
+// Outputs per (head, block): pooled vector as three bf16 terms hi + mid + lo (together
+// they carry the full fp32 mantissa), optional fp32 copy, and the three sums of squares
 // (full, first d_high dims, last d_low dims) in energy[(head*N + block)*4 + {0,1,2}].
 // Heads 0..h-1 are Q heads, h..h+h_kv-1 are K heads.
 // =====================================================================================
 template <int BLK>
 __global__ __launch_bounds__(256) void pool_energy_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, int h, int L, int N,
-    int d_high, int low_start, uint16_t* __restrict__ pooled_hi, uint16_t* __restrict__ pooled_lo,
-    float* __restrict__ energy, float* __restrict__ pooled_q_f32, float* __restrict__ pooled_k_f32) {
+    int d_high, int low_start, uint16_t* __restrict__ pooled_hi, uint16_t* __restrict__ pooled_mid,
+    uint16_t* __restrict__ pooled_lo, float* __restrict__ energy, float* __restrict__ pooled_q_f32, float* __restrict__ pooled_k_f32) {
   __shared__ float part[16][kHeadDim + 4];
   __shared__ float esum[2][4];
   const int blk = blockIdx.x, head = blockIdx.y, t = threadIdx.x;
@@ -57,11 +57,15 @@ __global__ __launch_bounds__(256) void pool_energy_kernel(
 #pragma unroll
     for (int r = 0; r < 16; ++r) s += part[r][t];
     const float mean = s * (1.0f / BLK);
+    // mean = hi + mid + lo exactly up to 2^-26 relative (three bf16 terms of 8 bits each)
     const uint32_t hi = float_to_bf16_bits(mean);
-    const float rem = mean - bf16_bits_to_float(hi);
-    const uint32_t lo = float_to_bf16_bits(rem);
+    const float rem1 = mean - bf16_bits_to_float(hi);
+    const uint32_t mid = float_to_bf16_bits(rem1);
+    const float rem2 = rem1 - bf16_bits_to_float(mid);
+    const uint32_t lo = float_to_bf16_bits(rem2);
     const size_t o = ((size_t)head * N + blk) * kHeadDim + t;
     pooled_hi[o] = (uint16_t)hi;
+    pooled_mid[o] = (uint16_t)mid;
     pooled_lo[o] = (uint16_t)lo;
     if (head < h) {
       if (pooled_q_f32) pooled_q_f32[o] = mean;
@@ -135,8 +139,8 @@ __global__ __launch_bounds__(64) void scale_kernel(const float* __restrict__ ene
 //
 // One workgroup (4 waves) per (strip of 16 q-blocks, q-head).  Per band:
 //   phase A: logits[16][v <= u_max] = Qbar_z Kbar_z^T * inv_scale on
-//            v_mfma_f32_16x16x32_bf16, with x = hi + lo and the three products
-//            hi*hi + hi*lo + lo*hi (fp32 accumulate), written to LDS;
+//            v_mfma_f32_16x16x32_bf16, with x = hi + mid + lo (three bf16 terms) and the
+//            six products of weight >= 2^-16 (fp32 accumulate), written to LDS;
 //   phase B: one wave per row: lanes hold the row (column i*64 + lane in register i),
 //            softmax numerators e = exp(l - max), then the selection threshold is found
 //            by bisection on the bit pattern of e: the smallest key T* whose strictly
@@ -151,8 +155,9 @@ constexpr int kStripRows = 16;
 
 template <int MAXCH, bool DUMP>
 __global__ __launch_bounds__(256) void select_kernel(
-    const uint16_t* __restrict__ pooled_hi, const uint16_t* __restrict__ pooled_lo,
-    const float* __restrict__ inv_scale, int h, int h_kv, int N, int d_high, int d_low, float top_p,
+    const uint16_t* __restrict__ pooled_hi, const uint16_t* __restrict__ pooled_mid,
+    const uint16_t* __restrict__ pooled_lo, const float* __restrict__ inv_scale, int h, int h_kv,
+    int N, int d_high, int d_low, float top_p,
     uint64_t* __restrict__ mask_bits, int32_t* __restrict__ row_ptr,
     float* __restrict__ logits_high, float* __restrict__ logits_low) {
   extern __shared__ float lds_logits[];
@@ -178,11 +183,12 @@ __global__ __launch_bounds__(256) void select_kernel(
     {
       const int arow = min(u0 + (lane & 15), N - 1);
       const size_t aoff = ((size_t)hq * N + arow) * kHeadDim + band_off + (lane >> 4) * 8;
-      bf16x8 ah[4], al[4];
+      bf16x8 ah[4], am[4], al[4];
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks) {
         if (ks < ksteps) {
           ah[ks] = *reinterpret_cast<const bf16x8*>(pooled_hi + aoff + ks * 32);
+          am[ks] = *reinterpret_cast<const bf16x8*>(pooled_mid + aoff + ks * 32);
           al[ks] = *reinterpret_cast<const bf16x8*>(pooled_lo + aoff + ks * 32);
         }
       }
@@ -194,9 +200,14 @@ __global__ __launch_bounds__(256) void select_kernel(
         for (int ks = 0; ks < 4; ++ks) {
           if (ks < ksteps) {
             const bf16x8 bh = *reinterpret_cast<const bf16x8*>(pooled_hi + boff + ks * 32);
+            const bf16x8 bm = *reinterpret_cast<const bf16x8*>(pooled_mid + boff + ks * 32);
             const bf16x8 bl = *reinterpret_cast<const bf16x8*>(pooled_lo + boff + ks * 32);
+            // all cross terms down to 2^-24 relative, smallest first
             acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al[ks], bh, acc, 0, 0, 0);
             acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah[ks], bl, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(am[ks], bm, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(am[ks], bh, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah[ks], bm, acc, 0, 0, 0);
             acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah[ks], bh, acc, 0, 0, 0);
           }
         }
@@ -390,7 +401,7 @@ __global__ __launch_bounds__(256) void causal_csr_kernel(int h, int N, int32_t* 
 
 // ---- workspace layout ------------------------------------------------------------
 struct EstimateWs {
-  size_t pooled_hi, pooled_lo, energy, inv_scale, total;
+  size_t pooled_hi, pooled_mid, pooled_lo, energy, inv_scale, total;
 };
 static EstimateWs estimate_ws(const prism_params* p) {
   const size_t N = p->seq_len / p->block;
@@ -398,6 +409,7 @@ static EstimateWs estimate_ws(const prism_params* p) {
   EstimateWs w;
   size_t off = 0;
   w.pooled_hi = off; off = align_up(off + heads * N * kHeadDim * 2, 256);
+  w.pooled_mid = off; off = align_up(off + heads * N * kHeadDim * 2, 256);
   w.pooled_lo = off; off = align_up(off + heads * N * kHeadDim * 2, 256);
   w.energy = off;    off = align_up(off + heads * N * 4 * sizeof(float), 256);
   w.inv_scale = off; off = align_up(off + (size_t)p->n_q_heads * 2 * sizeof(float), 256);
@@ -411,18 +423,19 @@ static int run_pool_and_scale(const prism_params* p, const void* q, const void* 
   const int N = p->seq_len / p->block;
   const dim3 grid(N, p->n_q_heads + p->n_kv_heads);
   uint16_t* hi = reinterpret_cast<uint16_t*>(ws + L.pooled_hi);
+  uint16_t* mid = reinterpret_cast<uint16_t*>(ws + L.pooled_mid);
   uint16_t* lo = reinterpret_cast<uint16_t*>(ws + L.pooled_lo);
   float* energy = reinterpret_cast<float*>(ws + L.energy);
   float* inv = reinterpret_cast<float*>(ws + L.inv_scale);
   const int low_start = p->head_dim - p->d_low;
   if (p->block == 128)
     hipLaunchKernelGGL(pool_energy_kernel<128>, grid, dim3(256), 0, st, (const uint16_t*)q,
-                       (const uint16_t*)k, p->n_q_heads, p->seq_len, N, p->d_high, low_start, hi, lo,
-                       energy, pooled_q, pooled_k);
+                       (const uint16_t*)k, p->n_q_heads, p->seq_len, N, p->d_high, low_start, hi, mid,
+                       lo, energy, pooled_q, pooled_k);
   else
     hipLaunchKernelGGL(pool_energy_kernel<64>, grid, dim3(256), 0, st, (const uint16_t*)q,
-                       (const uint16_t*)k, p->n_q_heads, p->seq_len, N, p->d_high, low_start, hi, lo,
-                       energy, pooled_q, pooled_k);
+                       (const uint16_t*)k, p->n_q_heads, p->seq_len, N, p->d_high, low_start, hi, mid,
+                       lo, energy, pooled_q, pooled_k);
   hipLaunchKernelGGL(scale_kernel, dim3(p->n_q_heads), dim3(64), 0, st, energy, p->n_q_heads,
                      p->n_kv_heads, N, p->d_high, p->d_low,
                      (p->flags & PRISM_FLAG_NO_CALIBRATION) ? 0 : 1, inv, scales);
@@ -443,6 +456,7 @@ static int launch_select(const prism_params* p, char* ws, const EstimateWs& L, u
   }
   hipLaunchKernelGGL(kern, dim3(strips, p->n_q_heads), dim3(256), lds, st,
                      reinterpret_cast<const uint16_t*>(ws + L.pooled_hi),
+                     reinterpret_cast<const uint16_t*>(ws + L.pooled_mid),
                      reinterpret_cast<const uint16_t*>(ws + L.pooled_lo),
                      reinterpret_cast<const float*>(ws + L.inv_scale), p->n_q_heads, p->n_kv_heads, N,
                      p->d_high, p->d_low, p->top_p, mask_bits, row_ptr, lh, ll);

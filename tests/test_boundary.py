@@ -44,7 +44,7 @@ def test_workspace_queries(lib):
     p = pb.make_params(32, 8, 131072, 128)
     n = pb.prism_estimate_workspace_bytes(p)
     heads, N = 40, 1024
-    assert n >= heads * N * 128 * 2 * 2 + heads * N * 16
+    assert n >= heads * N * 128 * 2 * 3 + heads * N * 16
     assert n < 64 << 20
     assert pb.prism_sparse_attn_workspace_bytes(p) == 8 * 131072 * 128 * 2
 

@@ -70,7 +70,9 @@ def test_scores_and_mask_match_oracle(name, L, h, hkv, B):
     for z in ("high", "low"):
         got, ref = sc[f"logits_{z}"][:, tri], sel.logits[z][:, tri]
         err = np.abs(got - ref)
-        assert (err <= 1e-4 + 2e-5 * np.abs(ref)).all(), (z, err.max(), np.abs(ref).max())
+        bad = int((err > 2e-5 + 4e-6 * np.abs(ref)).sum())
+        print(f"  logits_{z}: max abs err {err.max():.3g} at |ref| up to {np.abs(ref).max():.3g}", flush=True)
+        assert bad == 0, f"{z}: {bad} logits off, max err {err.max():.3g}, max |ref| {np.abs(ref).max():.3g}"
         assert np.isnan(sc[f"logits_{z}"][:, ~tri]).all()        # v > u never written
 
     res = gu.gpu_estimate(params, qd, kd)
