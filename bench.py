@@ -77,6 +77,8 @@ def main() -> int:
     ap.add_argument("--dense-reps", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--gen-threads", type=int, default=16)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (known HBM traffic) for counter calibration")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding or collectives); "
@@ -158,6 +160,14 @@ def main() -> int:
         ms_dense = float(np.mean([a.elapsed_time(b) for a, b in evd])) + ms_vimg
         del rp_d, ci_d, out_d
         log(f"dense causal (same kernel, all-ones lists) {ms_dense:.3f} ms")
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)                           # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
 
     flop_block = 4.0 * B * B * d
     flop_dense = flop_block * pairs

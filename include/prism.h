@@ -136,7 +136,8 @@ int prism_causal_csr(const prism_params* params, int32_t* row_ptr, int32_t* col_
  *                      col_idx (row_ptr values are clamped to it).
  *   out_bf16         : [n_q_heads, L, d] bf16, fully overwritten.
  *   lse              : [n_q_heads, L] float natural-log sum-exp of the scaled scores, or NULL.
- * workspace: prism_sparse_attn_workspace_bytes() bytes (holds a transposed copy of V).
+ * workspace: prism_sparse_attn_workspace_bytes() bytes (a transposed copy of V plus the
+ *            kernel's work queue: rows sorted by list length).
  * top_p, d_high, d_low and flags of `params` are ignored here.
  * ---------------------------------------------------------------------------------- */
 int prism_sparse_attn_workspace_bytes(const prism_params* params, size_t* bytes /* host, out */);
@@ -153,13 +154,16 @@ int prism_sparse_attn(const prism_params* params,
  *                            kernel reads into `v_image` (prism_sparse_attn_workspace_bytes()
  *                            bytes, 256-byte aligned).
  *   prism_sparse_attn_pre  : same computation and arguments as prism_sparse_attn, with the
- *                            image in place of V.
+ *                            image in place of V.  The tail of the same buffer (beyond the
+ *                            image) is scratch for the kernel's work queue and is rewritten
+ *                            by every call, so calls sharing one image must not overlap.
  * prism_sparse_attn(...) == prism_v_image(..., workspace) ; prism_sparse_attn_pre(..., workspace). */
 int prism_v_image(const prism_params* params, const void* v_bf16, void* v_image,
                   size_t v_image_bytes, void* stream);
 
 int prism_sparse_attn_pre(const prism_params* params,
-                          const void* q_bf16, const void* k_bf16, const void* v_image,
+                          const void* q_bf16, const void* k_bf16,
+                          void* v_image, size_t v_image_bytes,
                           const int32_t* row_ptr, const int32_t* col_idx, int64_t col_count,
                           void* out_bf16, float* lse, void* stream);
 

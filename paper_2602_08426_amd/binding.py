@@ -69,7 +69,7 @@ def _load() -> ctypes.CDLL:
     lib.prism_sparse_attn_workspace_bytes.argtypes = [P, ctypes.POINTER(sz)]
     lib.prism_sparse_attn.argtypes = [P, vp, vp, vp, vp, vp, i64, vp, vp, vp, sz, vp]
     lib.prism_v_image.argtypes = [P, vp, vp, sz, vp]
-    lib.prism_sparse_attn_pre.argtypes = [P, vp, vp, vp, vp, vp, i64, vp, vp, vp]
+    lib.prism_sparse_attn_pre.argtypes = [P, vp, vp, vp, sz, vp, vp, i64, vp, vp, vp]
     for name in EXPORTS[2:]:
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
@@ -189,8 +189,8 @@ def prism_sparse_attn_pre(params: prism_params, q: torch.Tensor, k: torch.Tensor
                           v_image: torch.Tensor, row_ptr: torch.Tensor, col_idx: torch.Tensor,
                           col_count: int, out: torch.Tensor, lse: Optional[torch.Tensor]) -> None:
     _check(_load().prism_sparse_attn_pre(ctypes.byref(params), _ptr(q), _ptr(k), _ptr(v_image),
-                                         _ptr(row_ptr), _ptr(col_idx), col_count, _ptr(out),
-                                         _ptr(lse), _stream()), "prism_sparse_attn_pre")
+                                         v_image.numel(), _ptr(row_ptr), _ptr(col_idx), col_count,
+                                         _ptr(out), _ptr(lse), _stream()), "prism_sparse_attn_pre")
 
 
 # ---- conveniences for callers holding numpy bf16 bit patterns --------------------------

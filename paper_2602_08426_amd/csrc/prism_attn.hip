@@ -112,25 +112,44 @@ template <int BLK>
 __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ vt,
     const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx, int64_t col_count,
+    const int32_t* __restrict__ order, int32_t* __restrict__ counter,
     uint16_t* __restrict__ out, float* __restrict__ lse, int h, int h_kv, int L, int N) {
   using C = AttnCfg<BLK>;
   constexpr int KT = BLK / 32;                       // 32-key tiles per kv block
   __shared__ __attribute__((aligned(16))) char lds_k[C::kTileBytes];
   __shared__ __attribute__((aligned(16))) char lds_v[C::kTileBytes];
-
-  // work item: longest rows (large u) first; consecutive workgroups share a kv head
-  const int bid = blockIdx.x;
-  const int u = N - 1 - bid / h;
-  const int rr = bid % h;
-  const int g = h / h_kv;
-  const int kvh = rr % h_kv;
-  const int hq = kvh * g + rr / h_kv;
+  __shared__ int next_item;
 
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int l32 = lane & 31, hf = lane >> 5;
+  const int g = h / h_kv;
+  const int R = h * N;
+  const float sm_scale = 1.4426950408889634f * 0.08838834764831845f;   // log2(e) / sqrt(128)
 
-  const size_t row = (size_t)hq * N + u;
-  int64_t beg = row_ptr[row], end = row_ptr[row + 1];
+  // LDS read offsets of this lane inside a 32-row slab: row l32, swizzled chunk
+  // (2*step + hf) ^ (row mod chunks-per-row).  The K tile has 16 chunks per row; the V^T
+  // tile has BLK/8 (for BLK = 128 the two tables coincide).
+  constexpr int kDepth = 4;                                // LDS reads kept in flight
+  int koff[8], voff[KT * 2];
+#pragma unroll
+  for (int st = 0; st < 8; ++st) koff[st] = l32 * 256 + (((2 * st + hf) ^ (l32 & 15)) << 4);
+#pragma unroll
+  for (int st = 0; st < KT * 2; ++st)
+    voff[st] = l32 * (BLK * 2) + (((2 * st + hf) ^ (l32 & (C::kVtCpr - 1))) << 4);
+
+  // Persistent workgroups pull (head, q-block) rows from a queue ordered longest list
+  // first, so that heads of very different density keep every CU busy until the end.
+  // Every workgroup leaves the loop as soon as the queue is empty.
+  for (;;) {
+  if (t == 0) next_item = atomicAdd(counter, 1);
+  __syncthreads();
+  const int item = next_item;
+  if (item >= R) break;
+  const int row_id = order[item];
+  const int hq = row_id / N, u = row_id - hq * N;
+  const int kvh = hq / g;
+
+  int64_t beg = row_ptr[row_id], end = row_ptr[row_id + 1];
   beg = beg < 0 ? 0 : (beg > col_count ? col_count : beg);
   end = end < beg ? beg : (end > col_count ? col_count : end);
 
@@ -153,18 +172,6 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
     for (int r = 0; r < 16; ++r) oacc[i][r] = 0.f;
   float m_run = -INFINITY;          // running max, in units of log2: s * sm_scale
   float l_run = 0.f;                // this lane's share of the running sum
-  const float sm_scale = 1.4426950408889634f * 0.08838834764831845f;   // log2(e) / sqrt(128)
-
-  // LDS read offsets of this lane inside a 32-row slab: row l32, swizzled chunk
-  // (2*step + hf) ^ (row mod chunks-per-row).  The K tile has 16 chunks per row; the V^T
-  // tile has BLK/8 (for BLK = 128 the two tables coincide).
-  constexpr int kDepth = 4;                                // LDS reads kept in flight
-  int koff[8], voff[KT * 2];
-#pragma unroll
-  for (int st = 0; st < 8; ++st) koff[st] = l32 * 256 + (((2 * st + hf) ^ (l32 & 15)) << 4);
-#pragma unroll
-  for (int st = 0; st < KT * 2; ++st)
-    voff[st] = l32 * (BLK * 2) + (((2 * st + hf) ^ (l32 & (C::kVtCpr - 1))) << 4);
 
   // find the first valid entry (v <= u) and start its K tile
   int64_t it = beg;
@@ -311,24 +318,121 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
   if (lse != nullptr && hf == 0)
     lse[(size_t)hq * L + qrow] =
         l_tot > 0.f ? (m_run + log2f(l_tot)) * 0.6931471805599453f : -INFINITY;
+  }  // persistent loop; the barrier at its top also orders next_item and the LDS tiles
+}
+
+// =====================================================================================
+// Work queue: rows sorted by list length, longest first (counting sort on 0..N).
+//   queue_reset_kernel : zero the histogram and the queue counter
+//   queue_hist_kernel  : hist[len] over all rows (LDS-private histograms, integer atomics)
+//   queue_scan_kernel  : start[len] = number of rows with a longer list
+//   queue_fill_kernel  : order[start[len]++] = row   (order inside one length is arbitrary)
+// =====================================================================================
+__global__ __launch_bounds__(256) void queue_reset_kernel(int32_t* __restrict__ hist, int nbins,
+                                                          int32_t* __restrict__ counter) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < nbins) hist[i] = 0;
+  if (i == 0) *counter = 0;
+}
+
+__device__ __forceinline__ int row_len(const int32_t* __restrict__ row_ptr, int r, int N) {
+  const int n = row_ptr[r + 1] - row_ptr[r];
+  return n < 0 ? 0 : (n > N ? N : n);
+}
+
+__global__ __launch_bounds__(256) void queue_hist_kernel(const int32_t* __restrict__ row_ptr, int R,
+                                                         int N, int32_t* __restrict__ hist) {
+  __shared__ int lh[kMaxBlocks + 1];
+  for (int i = threadIdx.x; i <= N; i += 256) lh[i] = 0;
+  __syncthreads();
+  for (int r = blockIdx.x * 256 + threadIdx.x; r < R; r += gridDim.x * 256)
+    atomicAdd(&lh[row_len(row_ptr, r, N)], 1);
+  __syncthreads();
+  for (int i = threadIdx.x; i <= N; i += 256)
+    if (lh[i] != 0) atomicAdd(&hist[i], lh[i]);
+}
+
+// single workgroup: start[len] = sum of hist[l] for l > len   (in place)
+__global__ __launch_bounds__(1024) void queue_scan_kernel(int32_t* __restrict__ hist, int N) {
+  __shared__ int wave_tot[16];
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int nb = N + 1;
+  const int per = (nb + 1023) / 1024;
+  // thread t owns positions lo..hi-1 of the array read from the longest length down
+  const int lo = min(nb, t * per), hi = min(nb, lo + per);
+  int s = 0;
+  for (int i = lo; i < hi; ++i) s += hist[N - i];
+  int inc = s;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const int y = __shfl_up(inc, off, 64);
+    if (lane >= off) inc += y;
+  }
+  if (lane == 63) wave_tot[wave] = inc;
+  __syncthreads();
+  int run = inc - s;
+  for (int w = 0; w < wave; ++w) run += wave_tot[w];
+  for (int i = lo; i < hi; ++i) {
+    const int c = hist[N - i];
+    hist[N - i] = run;
+    run += c;
+  }
+}
+
+__global__ __launch_bounds__(256) void queue_fill_kernel(const int32_t* __restrict__ row_ptr, int R,
+                                                         int N, int32_t* __restrict__ start,
+                                                         int32_t* __restrict__ order) {
+  const int r = blockIdx.x * 256 + threadIdx.x;
+  if (r >= R) return;
+  const int pos = atomicAdd(&start[row_len(row_ptr, r, N)], 1);
+  if (pos >= 0 && pos < R) order[pos] = r;
 }
 
 }  // namespace prism
 
 using namespace prism;
 
+// ---- workspace layout: [ V image | order[h*N] | hist[N+1] | counter ] -------------------
+struct AttnWs {
+  size_t image, order, hist, counter, total;
+};
+static AttnWs attn_ws(const prism_params* p) {
+  const size_t N = p->seq_len / p->block;
+  AttnWs w;
+  size_t off = 0;
+  w.image = off;   off = align_up(off + (size_t)p->n_kv_heads * p->seq_len * kHeadDim * 2, 256);
+  w.order = off;   off = align_up(off + (size_t)p->n_q_heads * N * sizeof(int32_t), 256);
+  w.hist = off;    off = align_up(off + (N + 1) * sizeof(int32_t), 256);
+  w.counter = off; off = align_up(off + sizeof(int32_t), 256);
+  w.total = off;
+  return w;
+}
+
+static int check_image(const prism_params* params, const void* img, size_t bytes) {
+  if (img == nullptr || (reinterpret_cast<uintptr_t>(img) & 255u) != 0 ||
+      bytes < attn_ws(params).total)
+    return PRISM_ERR_WORKSPACE;
+  return PRISM_OK;
+}
+
+static int persistent_grid(int rows) {
+  static int cus = 0;                       // compute units of the current device
+  if (cus == 0) {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess)
+      return -1;
+    cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+  }
+  const int resident = cus * 2;             // two workgroups per CU (LDS and registers)
+  return rows < resident ? rows : resident;
+}
+
 extern "C" int prism_sparse_attn_workspace_bytes(const prism_params* params, size_t* bytes) {
   if (bytes == nullptr) return PRISM_ERR_INVALID_ARG;
   int rc = check_params(params);
   if (rc != PRISM_OK) return rc;
-  *bytes = align_up((size_t)params->n_kv_heads * params->seq_len * kHeadDim * 2, 256);
-  return PRISM_OK;
-}
-
-static int check_image(const prism_params* params, const void* img, size_t bytes) {
-  const size_t need = (size_t)params->n_kv_heads * params->seq_len * kHeadDim * 2;
-  if (img == nullptr || (reinterpret_cast<uintptr_t>(img) & 255u) != 0 || bytes < need)
-    return PRISM_ERR_WORKSPACE;
+  *bytes = attn_ws(params).total;
   return PRISM_OK;
 }
 
@@ -351,26 +455,43 @@ extern "C" int prism_v_image(const prism_params* params, const void* v_bf16, voi
 }
 
 extern "C" int prism_sparse_attn_pre(const prism_params* params, const void* q_bf16,
-                                     const void* k_bf16, const void* v_image, const int32_t* row_ptr,
-                                     const int32_t* col_idx, int64_t col_count, void* out_bf16,
-                                     float* lse, void* stream) {
+                                     const void* k_bf16, void* v_image, size_t v_image_bytes,
+                                     const int32_t* row_ptr, const int32_t* col_idx,
+                                     int64_t col_count, void* out_bf16, float* lse, void* stream) {
   int rc = check_params(params);
   if (rc != PRISM_OK) return rc;
   if (!q_bf16 || !k_bf16 || !row_ptr || !col_idx || !out_bf16 || col_count < 0)
     return PRISM_ERR_INVALID_ARG;
-  if (v_image == nullptr || (reinterpret_cast<uintptr_t>(v_image) & 255u) != 0)
-    return PRISM_ERR_WORKSPACE;
+  rc = check_image(params, v_image, v_image_bytes);
+  if (rc != PRISM_OK) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
   const int N = params->seq_len / params->block;
   const int h = params->n_q_heads, h_kv = params->n_kv_heads, L = params->seq_len;
+  const int R = h * N;
+  const AttnWs W = attn_ws(params);
+  char* ws = static_cast<char*>(v_image);
+  int32_t* order = reinterpret_cast<int32_t*>(ws + W.order);
+  int32_t* hist = reinterpret_cast<int32_t*>(ws + W.hist);
+  int32_t* counter = reinterpret_cast<int32_t*>(ws + W.counter);
+  const int grid = persistent_grid(R);
+  if (grid <= 0) return PRISM_ERR_HIP;
+
+  hipLaunchKernelGGL(queue_reset_kernel, dim3((N + 1 + 255) / 256), dim3(256), 0, st, hist, N + 1,
+                     counter);
+  hipLaunchKernelGGL(queue_hist_kernel, dim3(64), dim3(256), 0, st, row_ptr, R, N, hist);
+  hipLaunchKernelGGL(queue_scan_kernel, dim3(1), dim3(1024), 0, st, hist, N);
+  hipLaunchKernelGGL(queue_fill_kernel, dim3((R + 255) / 256), dim3(256), 0, st, row_ptr, R, N, hist,
+                     order);
   if (params->block == 128)
-    hipLaunchKernelGGL(sparse_attn_kernel<128>, dim3(h * N), dim3(AttnCfg<128>::kThreads), 0, st,
+    hipLaunchKernelGGL(sparse_attn_kernel<128>, dim3(grid), dim3(AttnCfg<128>::kThreads), 0, st,
                        (const uint16_t*)q_bf16, (const uint16_t*)k_bf16, (const uint16_t*)v_image,
-                       row_ptr, col_idx, col_count, (uint16_t*)out_bf16, lse, h, h_kv, L, N);
+                       row_ptr, col_idx, col_count, order, counter, (uint16_t*)out_bf16, lse, h,
+                       h_kv, L, N);
   else
-    hipLaunchKernelGGL(sparse_attn_kernel<64>, dim3(h * N), dim3(AttnCfg<64>::kThreads), 0, st,
+    hipLaunchKernelGGL(sparse_attn_kernel<64>, dim3(grid), dim3(AttnCfg<64>::kThreads), 0, st,
                        (const uint16_t*)q_bf16, (const uint16_t*)k_bf16, (const uint16_t*)v_image,
-                       row_ptr, col_idx, col_count, (uint16_t*)out_bf16, lse, h, h_kv, L, N);
+                       row_ptr, col_idx, col_count, order, counter, (uint16_t*)out_bf16, lse, h,
+                       h_kv, L, N);
   return launch_status();
 }
 
@@ -386,6 +507,6 @@ extern "C" int prism_sparse_attn(const prism_params* params, const void* q_bf16,
   if (rc != PRISM_OK) return rc;
   rc = prism_v_image(params, v_bf16, workspace, workspace_bytes, stream);
   if (rc != PRISM_OK) return rc;
-  return prism_sparse_attn_pre(params, q_bf16, k_bf16, workspace, row_ptr, col_idx, col_count,
-                               out_bf16, lse, stream);
+  return prism_sparse_attn_pre(params, q_bf16, k_bf16, workspace, workspace_bytes, row_ptr, col_idx,
+                               col_count, out_bf16, lse, stream);
 }

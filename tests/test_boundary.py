@@ -46,7 +46,8 @@ def test_workspace_queries(lib):
     heads, N = 40, 1024
     assert n >= heads * N * 128 * 2 * 3 + heads * N * 16
     assert n < 64 << 20
-    assert pb.prism_sparse_attn_workspace_bytes(p) == 8 * 131072 * 128 * 2
+    ws = pb.prism_sparse_attn_workspace_bytes(p)
+    assert 8 * 131072 * 128 * 2 + 32 * 1024 * 4 <= ws < 8 * 131072 * 128 * 2 + (1 << 20)
 
 
 @pytest.mark.parametrize("kw,status", [
