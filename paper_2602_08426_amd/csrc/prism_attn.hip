@@ -72,38 +72,59 @@ struct AttnCfg {
   static constexpr int kVtCpr = BLK / 8;                   // chunks per V^T row
 };
 
-// Asynchronous global -> LDS tile copies (global_load_lds_dwordx4: every lane fetches 16
-// bytes from its own global address and the wave's 64 pieces land contiguously in LDS at
-// M0-base + 16*lane).  LDS slot p (16-byte units) of a tile belongs to (row, c') with
-// c' the swizzled chunk position; the lane that fills it reads global chunk
+// Asynchronous global -> LDS tile copies (buffer_load_dwordx4 ... lds: every lane fetches 16
+// bytes at rsrc.base + voffset + soffset and the wave's 64 pieces land contiguously in LDS
+// at M0-base + 16*lane).  LDS slot p (16-byte units) of a tile belongs to (row, c') with c'
+// the swizzled chunk position; the lane that fills it reads global chunk
 // c = c' ^ (row mod chunks-per-row), i.e. the swizzle is applied on the global side.
-typedef const __attribute__((address_space(1))) void* gptr_t;
+// Buffer (not flat/global) addressing is used on purpose: LDS reads issued while such
+// copies are in flight then keep exact lgkmcnt tracking in the compiler.
 typedef __attribute__((address_space(3))) void* lptr_t;
 
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, uint32_t bytes) {
+  // raw buffer, 32-bit data format, no swizzle, no TID addition
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
+}
+
+// byte offset inside a tile of the 16-byte piece that LDS slot p holds
 template <int BLK>
-__device__ __forceinline__ void async_load_k_tile(const uint16_t* __restrict__ src, char* lds, int t) {
+__device__ __forceinline__ int k_piece_offset(int p) {
+  const int row = p >> 4;
+  return row * 256 + (((p & 15) ^ (row & 15)) << 4);
+}
+template <int BLK>
+__device__ __forceinline__ int vt_piece_offset(int p) {
   using C = AttnCfg<BLK>;
-  const int wave_base = (t & ~63);
-#pragma unroll
-  for (int i = 0; i < C::kPerThread; ++i) {
-    const int p = i * C::kThreads + t;
-    const int row = p >> 4, c = (p & 15) ^ (row & 15);
-    __builtin_amdgcn_global_load_lds((gptr_t)(src + row * kHeadDim + c * 8),
-                                     (lptr_t)(lds + (i * C::kThreads + wave_base) * 16), 16, 0, 0);
-  }
+  const int row = p / C::kVtCpr;
+  return row * (BLK * 2) + (((p % C::kVtCpr) ^ (row & (C::kVtCpr - 1))) << 4);
 }
 
 template <int BLK>
-__device__ __forceinline__ void async_load_vt_tile(const uint16_t* __restrict__ src, char* lds, int t) {
+__device__ __forceinline__ void async_load_k_tile(__amdgpu_buffer_rsrc_t rs, int tile_off, char* lds,
+                                                  int t) {
   using C = AttnCfg<BLK>;
-  const int wave_base = (t & ~63);
+  // wave-uniform LDS base, re-materialised here so that the per-piece M0 values are formed
+  // with scalar adds instead of being kept live (and spilled) across the whole loop
+  int wave_base = __builtin_amdgcn_readfirstlane(t & ~63);
+  asm volatile("" : "+s"(wave_base));
 #pragma unroll
-  for (int i = 0; i < C::kPerThread; ++i) {
-    const int p = i * C::kThreads + t;
-    const int row = p / C::kVtCpr, c = (p % C::kVtCpr) ^ (row & (C::kVtCpr - 1));
-    __builtin_amdgcn_global_load_lds((gptr_t)(src + row * BLK + c * 8),
-                                     (lptr_t)(lds + (i * C::kThreads + wave_base) * 16), 16, 0, 0);
-  }
+  for (int i = 0; i < C::kPerThread; ++i)
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lptr_t)(lds + (i * C::kThreads + wave_base) * 16), 16,
+                                             k_piece_offset<BLK>(i * C::kThreads + t), tile_off, 0, 0);
+}
+
+template <int BLK>
+__device__ __forceinline__ void async_load_vt_tile(__amdgpu_buffer_rsrc_t rs, int tile_off, char* lds,
+                                                   int t) {
+  using C = AttnCfg<BLK>;
+  // wave-uniform LDS base, re-materialised here so that the per-piece M0 values are formed
+  // with scalar adds instead of being kept live (and spilled) across the whole loop
+  int wave_base = __builtin_amdgcn_readfirstlane(t & ~63);
+  asm volatile("" : "+s"(wave_base));
+#pragma unroll
+  for (int i = 0; i < C::kPerThread; ++i)
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lptr_t)(lds + (i * C::kThreads + wave_base) * 16), 16,
+                                             vt_piece_offset<BLK>(i * C::kThreads + t), tile_off, 0, 0);
 }
 
 __device__ __forceinline__ void wait_async_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
@@ -129,7 +150,7 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
   // LDS read offsets of this lane inside a 32-row slab: row l32, swizzled chunk
   // (2*step + hf) ^ (row mod chunks-per-row).  The K tile has 16 chunks per row; the V^T
   // tile has BLK/8 (for BLK = 128 the two tables coincide).
-  constexpr int kDepth = 4;                                // LDS reads kept in flight
+  constexpr int kDepth = 8;                                // LDS reads kept in flight
   int koff[8], voff[KT * 2];
 #pragma unroll
   for (int st = 0; st < 8; ++st) koff[st] = l32 * 256 + (((2 * st + hf) ^ (l32 & 15)) << 4);
@@ -143,18 +164,23 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
   for (;;) {
   if (t == 0) next_item = atomicAdd(counter, 1);
   __syncthreads();
-  const int item = next_item;
+  const int item = __builtin_amdgcn_readfirstlane(next_item);   // wave-uniform from here on
   if (item >= R) break;
-  const int row_id = order[item];
+  const int row_id = __builtin_amdgcn_readfirstlane(order[item]);
   const int hq = row_id / N, u = row_id - hq * N;
   const int kvh = hq / g;
 
-  int64_t beg = row_ptr[row_id], end = row_ptr[row_id + 1];
-  beg = beg < 0 ? 0 : (beg > col_count ? col_count : beg);
-  end = end < beg ? beg : (end > col_count ? col_count : end);
+  // list bounds as 32-bit scalars (CSR offsets are int32; col_count is clamped to that range)
+  const int cap = col_count > 0x7fffffff ? 0x7fffffff : (int)col_count;
+  int beg = __builtin_amdgcn_readfirstlane(row_ptr[row_id]);
+  int end = __builtin_amdgcn_readfirstlane(row_ptr[row_id + 1]);
+  beg = beg < 0 ? 0 : (beg > cap ? cap : beg);
+  end = end < beg ? beg : (end > cap ? cap : end);
 
-  const uint16_t* kbase = k + (size_t)kvh * L * kHeadDim;
-  const uint16_t* vbase = vt + (size_t)kvh * N * (size_t)kHeadDim * BLK;
+  // K and V^T of this kv head as buffer resources (tile v starts at byte v * kTileBytes)
+  const uint32_t head_bytes = (uint32_t)L * kHeadDim * 2;
+  const __amdgpu_buffer_rsrc_t krs = make_rsrc(k + (size_t)kvh * L * kHeadDim, head_bytes);
+  const __amdgpu_buffer_rsrc_t vrs = make_rsrc(vt + (size_t)kvh * L * kHeadDim, head_bytes);
 
   // Q fragments (B operand of S^T = K Q^T): query row 32*wave + l32, dims 16*ks + 8*hf ..+7
   const int qrow = u * BLK + wave * 32 + l32;
@@ -174,43 +200,49 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
   float l_run = 0.f;                // this lane's share of the running sum
 
   // find the first valid entry (v <= u) and start its K tile
-  int64_t it = beg;
-  while (it < end && (col_idx[it] < 0 || col_idx[it] > u)) ++it;
-  if (it < end) async_load_k_tile<BLK>(kbase + (size_t)col_idx[it] * BLK * kHeadDim, lds_k, t);
+  int it = beg;
+  int v = -1;
+  while (it < end) {
+    v = __builtin_amdgcn_readfirstlane(col_idx[it]);
+    if (v >= 0 && v <= u) break;
+    ++it;
+  }
+  if (it < end) async_load_k_tile<BLK>(krs, v * C::kTileBytes, lds_k, t);
   wait_async_loads();
   __syncthreads();
 
   while (it < end) {
-    const int v = col_idx[it];
-    int64_t nx = it + 1;
-    while (nx < end && (col_idx[nx] < 0 || col_idx[nx] > u)) ++nx;
+    // next valid entry (v_next <= u), looked up before the MFMA phases start
+    int nx = it + 1;
+    int v_next = -1;
+    while (nx < end) {
+      v_next = __builtin_amdgcn_readfirstlane(col_idx[nx]);
+      if (v_next >= 0 && v_next <= u) break;
+      ++nx;
+    }
 
     // ---- V(j) -> LDS, in flight during S^T and the softmax ----
-    async_load_vt_tile<BLK>(vbase + (size_t)v * kHeadDim * BLK, lds_v, t);
+    async_load_vt_tile<BLK>(vrs, v * C::kTileBytes, lds_v, t);
 
     // ---- S^T = K Q^T ----
     // Flat software pipeline over the KT*8 (tile, k-step) pairs: the LDS read of step
     // i + kDepth is issued right after the MFMA of step i, in source order.
     f32x16 sacc[KT];
-#pragma unroll
-    for (int kt = 0; kt < KT; ++kt) {
-#pragma unroll
-      for (int r = 0; r < 16; ++r) sacc[kt][r] = 0.f;
-    }
+    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     {
       constexpr int kSteps = KT * 8;
       bf16x8 fr[kDepth];
 #pragma unroll
       for (int i = 0; i < kDepth; ++i)
-        fr[i] = *reinterpret_cast<const bf16x8*>(lds_k + (i >> 3) * 8192 + koff[i & 7]);
+        fr[i] = *reinterpret_cast<const bf16x8*>(lds_k + (i % KT) * 8192 + koff[i / KT]);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int i = 0; i < kSteps; ++i) {
-        const int kt = i >> 3, ks = i & 7;
-        sacc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i % kDepth], qf[ks], sacc[kt], 0, 0, 0);
+        const int kt = i % KT, ks = i / KT;          // consecutive MFMAs: independent accumulators
+        sacc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i % kDepth], qf[ks], ks == 0 ? zero16 : sacc[kt], 0, 0, 0);
         if (i + kDepth < kSteps) {
           const int j = i + kDepth;
-          fr[i % kDepth] = *reinterpret_cast<const bf16x8*>(lds_k + (j >> 3) * 8192 + koff[j & 7]);
+          fr[i % kDepth] = *reinterpret_cast<const bf16x8*>(lds_k + (j % KT) * 8192 + koff[j / KT]);
         }
         __builtin_amdgcn_sched_barrier(0);
       }
@@ -269,7 +301,7 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
     __syncthreads();                 // V(j) complete; everyone is done reading K(j)
 
     // ---- K(j+1) -> LDS, in flight during PV ----
-    if (nx < end) async_load_k_tile<BLK>(kbase + (size_t)col_idx[nx] * BLK * kHeadDim, lds_k, t);
+    if (nx < end) async_load_k_tile<BLK>(krs, v_next * C::kTileBytes, lds_k, t);
 
     // ---- O^T += V^T P^T ----  (same flat pipeline over the 4*KT*2 (d-tile, k-step) pairs)
     {
@@ -278,15 +310,15 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
       bf16x8 fr[kDepth];
 #pragma unroll
       for (int i = 0; i < kDepth; ++i)
-        fr[i] = *reinterpret_cast<const bf16x8*>(lds_v + (i / kPer) * (32 * BLK * 2) + voff[i % kPer]);
+        fr[i] = *reinterpret_cast<const bf16x8*>(lds_v + (i % 4) * (32 * BLK * 2) + voff[i / 4]);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int i = 0; i < kSteps; ++i) {
-        const int dt = i / kPer, st = i % kPer;
+        const int dt = i % 4, st = i / 4;            // consecutive MFMAs: independent accumulators
         oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i % kDepth], pf[st >> 1][st & 1], oacc[dt], 0, 0, 0);
         if (i + kDepth < kSteps) {
           const int j = i + kDepth;
-          fr[i % kDepth] = *reinterpret_cast<const bf16x8*>(lds_v + (j / kPer) * (32 * BLK * 2) + voff[j % kPer]);
+          fr[i % kDepth] = *reinterpret_cast<const bf16x8*>(lds_v + (j % 4) * (32 * BLK * 2) + voff[j / 4]);
         }
         __builtin_amdgcn_sched_barrier(0);
       }
@@ -295,6 +327,7 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
     wait_async_loads();              // this wave's share of K(j+1) has landed
     __syncthreads();                 // K(j+1) complete; everyone is done reading V(j)
     it = nx;
+    v = v_next;
   }
 
   // ---- epilogue: O = O^T / l, bf16, [q][d] ----
