@@ -32,6 +32,22 @@ def log(msg: str) -> None:
     print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
 
+def profiled_traffic(workload: str, kernel: str):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 summary of this workload
+    (profiles/hot_path_<workload>.txt, lines 'TRAFFIC kernel=... read_bytes=... write_bytes=...');
+    None when no summary is there."""
+    path = os.path.join(ROOT, "profiles", f"hot_path_{workload}.txt")
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith("TRAFFIC") and f"kernel={kernel} " in line:
+                    kv = dict(x.split("=") for x in line.split()[1:])
+                    return float(kv["read_bytes"]) + float(kv["write_bytes"])
+    except OSError:
+        pass
+    return None
+
+
 def cpu_baseline(w, Qb, Kb, Vb, mask, flop_dense: float, budget_rows: int = 48):
     """Time the oracle (as it stands) on a bounded sample and scale to the whole workload:
     selection on one kv group, block-masked attention on a seeded sample of (head, q-block)
@@ -200,8 +216,13 @@ def main() -> int:
         },
         "roofline": {"kernel": "sparse_attn_kernel<128>", "bound": "mfma", "achieved": round(exec_tflops, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(exec_tflops / PEAK_BF16_TFLOPS, 4),
-                     "traffic": None,
+                     "traffic": profiled_traffic(w.name, "sparse_attn_kernel"),
                      "flops_per_launch": flop_exec, "avg_launch_ms": round(ms_attn, 4)},
+        "roofline_estimate": {"kernel": "prism_estimate (5 kernels; pool_energy_kernel carries the bytes)",
+                              "bound": "hbm", "achieved": round(est_gbs, 1), "peak": PEAK_HBM_GBS,
+                              "unit": "GB/s", "frac": round(est_gbs / PEAK_HBM_GBS, 4),
+                              "traffic": profiled_traffic(w.name, "pool_energy_kernel"),
+                              "bytes_per_launch": est_bytes, "avg_launch_ms": round(ms_est, 4)},
     }
 
     if not args.no_cpu_baseline:
