@@ -277,7 +277,11 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
         for (int r = 0; r < 16; ++r) oacc[i][r] *= alpha;
       m_run = m_new;
     }
-    float psum = 0.f;
+    // p = 2^(s*scale - m) as bf16 pairs (the PV operand); the row sum adds the rounded values
+    // (one v_dot2c per pair), so numerator and normaliser see the same P.  Two partial sums
+    // keep the dependent chain short.
+    float psum0 = 0.f, psum1 = 0.f;
+    const bf16x2 ones2 = {(__bf16)1.0f, (__bf16)1.0f};
     bf16x8 pf[KT][2];
 #pragma unroll
     for (int kt = 0; kt < KT; ++kt) {
@@ -287,15 +291,18 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
         for (int j = 0; j < 8; j += 2) {
           const float p0 = __builtin_amdgcn_exp2f(fmaf(sacc[kt][8 * s + j], sm_scale, -m_new));
           const float p1 = __builtin_amdgcn_exp2f(fmaf(sacc[kt][8 * s + j + 1], sm_scale, -m_new));
-          psum += p0 + p1;
           const f32x2 pp = {p0, p1};
           const bf16x2 pb = __builtin_convertvector(pp, bf16x2);
           pf[kt][s][j] = pb[0];
           pf[kt][s][j + 1] = pb[1];
+          if ((j & 2) == 0)
+            psum0 = __builtin_amdgcn_fdot2_f32_bf16(pb, ones2, psum0, false);
+          else
+            psum1 = __builtin_amdgcn_fdot2_f32_bf16(pb, ones2, psum1, false);
         }
       }
     }
-    l_run += psum;
+    l_run += psum0 + psum1;
 
     wait_async_loads();              // this wave's share of V(j) has landed
     __syncthreads();                 // V(j) complete; everyone is done reading K(j)
