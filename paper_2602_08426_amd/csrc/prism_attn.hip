@@ -366,7 +366,7 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
 //   queue_reset_kernel : zero the histogram and the queue counter
 //   queue_hist_kernel  : hist[len] over all rows (LDS-private histograms, integer atomics)
 //   queue_scan_kernel  : start[len] = number of rows with a longer list
-//   queue_fill_kernel  : order[start[len]++] = row   (order inside one length is arbitrary)
+//   queue_fill_kernel  : order[start[len] + k] = row  (order inside one length is arbitrary)
 // =====================================================================================
 __global__ __launch_bounds__(256) void queue_reset_kernel(int32_t* __restrict__ hist, int nbins,
                                                           int32_t* __restrict__ counter) {
@@ -419,13 +419,30 @@ __global__ __launch_bounds__(1024) void queue_scan_kernel(int32_t* __restrict__ 
   }
 }
 
+// Each workgroup ranks its 256 rows per length in LDS and reserves one range per distinct
+// length with a single global atomic, so rows of equal length do not serialise on one address.
 __global__ __launch_bounds__(256) void queue_fill_kernel(const int32_t* __restrict__ row_ptr, int R,
                                                          int N, int32_t* __restrict__ start,
                                                          int32_t* __restrict__ order) {
+  __shared__ int cnt[kMaxBlocks + 1];
+  for (int i = threadIdx.x; i <= N; i += 256) cnt[i] = 0;
+  __syncthreads();
   const int r = blockIdx.x * 256 + threadIdx.x;
-  if (r >= R) return;
-  const int pos = atomicAdd(&start[row_len(row_ptr, r, N)], 1);
-  if (pos >= 0 && pos < R) order[pos] = r;
+  int len = 0, rank = 0;
+  if (r < R) {
+    len = row_len(row_ptr, r, N);
+    rank = atomicAdd(&cnt[len], 1);
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i <= N; i += 256) {
+    const int c = cnt[i];
+    if (c != 0) cnt[i] = atomicAdd(&start[i], c);  // count -> first position of this workgroup's range
+  }
+  __syncthreads();
+  if (r < R) {
+    const int pos = cnt[len] + rank;
+    if (pos >= 0 && pos < R) order[pos] = r;
+  }
 }
 
 }  // namespace prism

@@ -52,19 +52,43 @@ inline int launch_status() {
 }
 
 // ---- device helpers -------------------------------------------------------------
+// Wave-wide reductions on the DPP cross-lane paths (no LDS round trips): two quad
+// permutes, half-row and row mirrors, then the row broadcasts; lane 63 ends up with the
+// result, which is returned to every lane through a scalar register.
+template <int CTRL, int ROW_MASK = 0xF>
+__device__ __forceinline__ float dpp_f32(float old, float x) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, old),
+                                                               __builtin_bit_cast(int, x), CTRL,
+                                                               ROW_MASK, 0xF, false));
+}
+constexpr int kDppQuadSwap1 = 0xB1;      // quad_perm [1,0,3,2]
+constexpr int kDppQuadSwap2 = 0x4E;      // quad_perm [2,3,0,1]
+constexpr int kDppRowHalfMirror = 0x141;
+constexpr int kDppRowMirror = 0x140;
+constexpr int kDppRowBcast15 = 0x142;
+constexpr int kDppRowBcast31 = 0x143;
+
 __device__ __forceinline__ float wave_sum(float x) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off, 64);
-  return x;
+  x += dpp_f32<kDppQuadSwap1>(0.f, x);
+  x += dpp_f32<kDppQuadSwap2>(0.f, x);
+  x += dpp_f32<kDppRowHalfMirror>(0.f, x);
+  x += dpp_f32<kDppRowMirror>(0.f, x);
+  x += dpp_f32<kDppRowBcast15, 0xA>(0.f, x);
+  x += dpp_f32<kDppRowBcast31, 0xC>(0.f, x);
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 63));
+}
+__device__ __forceinline__ float wave_max(float x) {
+  x = fmaxf(x, dpp_f32<kDppQuadSwap1>(x, x));
+  x = fmaxf(x, dpp_f32<kDppQuadSwap2>(x, x));
+  x = fmaxf(x, dpp_f32<kDppRowHalfMirror>(x, x));
+  x = fmaxf(x, dpp_f32<kDppRowMirror>(x, x));
+  x = fmaxf(x, dpp_f32<kDppRowBcast15, 0xA>(x, x));
+  x = fmaxf(x, dpp_f32<kDppRowBcast31, 0xC>(x, x));
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 63));
 }
 __device__ __forceinline__ double wave_sum(double x) {
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off, 64);
-  return x;
-}
-__device__ __forceinline__ float wave_max(float x) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) x = fmaxf(x, __shfl_xor(x, off, 64));
   return x;
 }
 __device__ __forceinline__ int wave_sum(int x) {

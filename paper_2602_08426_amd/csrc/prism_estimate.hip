@@ -153,6 +153,74 @@ __global__ __launch_bounds__(64) void scale_kernel(const float* __restrict__ ene
 // =====================================================================================
 constexpr int kStripRows = 16;
 
+// Top-p selection of one row of one band by one wave.  The row (n <= 64*NCH causal logits)
+// lives in registers: column 64*i + lane in e[i].  Selected bits are OR-ed into bits_row
+// (LDS, one 64-bit word per 64 columns).
+template <int NCH>
+__device__ __forceinline__ void select_row(const float* __restrict__ row_logits, int n, float top_p,
+                                           int lane, uint64_t* __restrict__ bits_row) {
+  float e[NCH];
+  float mx = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) {
+    const int idx = i * 64 + lane;
+    e[i] = idx < n ? row_logits[idx] : -INFINITY;
+    mx = fmaxf(mx, e[i]);
+  }
+  mx = wave_max(mx);
+  float part = 0.f;
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) {
+    e[i] = (e[i] == -INFINITY) ? 0.f : __expf(e[i] - mx);       // softmax numerators, max one = 1
+    part += e[i];
+  }
+  const float total = wave_sum(part);
+  const float target = top_p * total;
+  const bool all = top_p >= 1.0f;
+
+  uint32_t tstar = 0;
+  float gstar = 0.f;
+  if (!all) {
+    // largest key T with mass{key > T} >= target; T* = T + 1 is then the smallest key whose
+    // strictly-larger mass is < target (and T* is some element's key).  Keys are bit patterns of
+    // values in [0, 1], i.e. <= 0x3F800000: bit 30 is never set.
+    uint32_t T = 0;
+    for (int bit = 29; bit >= 0; --bit) {
+      const uint32_t cand = T | (1u << bit);
+      float gp = 0.f;
+#pragma unroll
+      for (int i = 0; i < NCH; ++i) gp += (__float_as_uint(e[i]) > cand) ? e[i] : 0.f;
+      if (!(wave_sum(gp) < target)) T = cand;
+    }
+    tstar = T + 1;
+    float gp = 0.f;
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) gp += (__float_as_uint(e[i]) > tstar) ? e[i] : 0.f;
+    gstar = wave_sum(gp);
+  }
+  // elements above T* are selected; elements equal to T* in ascending block order while the
+  // mass before them stays < target (stable descending order, exclusive cumulative mass < p)
+  const float tie_val = __uint_as_float(tstar);
+  int tie_base = 0;
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) {
+    const int idx = i * 64 + lane;
+    bool sel;
+    if (all) {
+      sel = idx < n;
+    } else {
+      const uint32_t key = __float_as_uint(e[i]);
+      const bool tie = key == tstar;
+      const uint64_t tb = __ballot(tie);
+      const int rank = tie_base + __popcll(tb & ((1ull << lane) - 1ull));
+      sel = (key > tstar) || (tie && (gstar + (float)rank * tie_val < target));
+      tie_base += __popcll(tb);
+    }
+    const uint64_t bal = __ballot(sel);
+    if (lane == 0) bits_row[i] |= bal;
+  }
+}
+
 template <int MAXCH, bool DUMP>
 __global__ __launch_bounds__(256) void select_kernel(
     const uint16_t* __restrict__ pooled_hi, const uint16_t* __restrict__ pooled_mid,
@@ -161,17 +229,24 @@ __global__ __launch_bounds__(256) void select_kernel(
     uint64_t* __restrict__ mask_bits, int32_t* __restrict__ row_ptr,
     float* __restrict__ logits_high, float* __restrict__ logits_low) {
   extern __shared__ float lds_logits[];
-  const int strip = blockIdx.x, hq = blockIdx.y;
+  __shared__ uint64_t lds_bits[kStripRows][kMaxBlocks / 64];
+  // heavy strips (large u) first
+  const int strip = gridDim.x - 1 - blockIdx.x, hq = blockIdx.y;
   const int kvh = h + hq / (h / h_kv);
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // uniform: scalar branches below
   const int u0 = strip * kStripRows;
   const int ncols = min(N, u0 + kStripRows);
   const int ntiles = (ncols + 15) >> 4;
   const int ld = ntiles * 16 + 4;
   const int W = (N + 63) >> 6;
 
-  uint64_t myword[4] = {0, 0, 0, 0};
+  if (!DUMP) {
+    for (int i = threadIdx.x; i < kStripRows * (kMaxBlocks / 64); i += 256)
+      (&lds_bits[0][0])[i] = 0ull;
+  }
 
+#pragma unroll 1
   for (int z = 0; z < 2; ++z) {
     const int dz = z == 0 ? d_high : d_low;
     if (dz == 0) continue;                         // uniform: same for the whole grid
@@ -179,7 +254,7 @@ __global__ __launch_bounds__(256) void select_kernel(
     const int ksteps = dz >> 5;
     const float inv = inv_scale[hq * 2 + z];
 
-    // ---------------- phase A ----------------
+    // ---------------- phase A: logits of the strip into LDS ----------------
     {
       const int arow = min(u0 + (lane & 15), N - 1);
       const size_t aoff = ((size_t)hq * N + arow) * kHeadDim + band_off + (lane >> 4) * 8;
@@ -192,23 +267,41 @@ __global__ __launch_bounds__(256) void select_kernel(
           al[ks] = *reinterpret_cast<const bf16x8*>(pooled_lo + aoff + ks * 32);
         }
       }
-      for (int ct = wave; ct < ntiles; ct += 4) {
+      // B fragments of the next tile are fetched while the MFMAs of the current one run
+      bf16x8 bh[4], bm[4], bl[4];
+      auto load_b = [&](int ct) {
         const int brow = min(ct * 16 + (lane & 15), N - 1);
         const size_t boff = ((size_t)kvh * N + brow) * kHeadDim + band_off + (lane >> 4) * 8;
-        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
           if (ks < ksteps) {
-            const bf16x8 bh = *reinterpret_cast<const bf16x8*>(pooled_hi + boff + ks * 32);
-            const bf16x8 bm = *reinterpret_cast<const bf16x8*>(pooled_mid + boff + ks * 32);
-            const bf16x8 bl = *reinterpret_cast<const bf16x8*>(pooled_lo + boff + ks * 32);
+            bh[ks] = *reinterpret_cast<const bf16x8*>(pooled_hi + boff + ks * 32);
+            bm[ks] = *reinterpret_cast<const bf16x8*>(pooled_mid + boff + ks * 32);
+            bl[ks] = *reinterpret_cast<const bf16x8*>(pooled_lo + boff + ks * 32);
+          }
+        }
+      };
+      if (wave < ntiles) load_b(wave);
+      for (int ct = wave; ct < ntiles; ct += 4) {
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        bf16x8 ch[4], cm[4], cl[4];
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+          ch[ks] = bh[ks];
+          cm[ks] = bm[ks];
+          cl[ks] = bl[ks];
+        }
+        if (ct + 4 < ntiles) load_b(ct + 4);
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+          if (ks < ksteps) {
             // all cross terms down to 2^-24 relative, smallest first
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al[ks], bh, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah[ks], bl, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(am[ks], bm, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(am[ks], bh, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah[ks], bm, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah[ks], bh, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al[ks], ch[ks], acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah[ks], cl[ks], acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(am[ks], cm[ks], acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(am[ks], ch[ks], acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah[ks], cm[ks], acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah[ks], ch[ks], acc, 0, 0, 0);
           }
         }
         const int col = ct * 16 + (lane & 15);
@@ -227,94 +320,36 @@ __global__ __launch_bounds__(256) void select_kernel(
     }
     __syncthreads();
 
-    // ---------------- phase B ----------------
+    // ---------------- phase B: one wave per row ----------------
     if (!DUMP) {
-#pragma unroll
+#pragma unroll 1
       for (int rr = 0; rr < 4; ++rr) {
         const int r = wave * 4 + rr;
         const int u = u0 + r;
-        if (u >= N) continue;                      // uniform per wave
+        if (u >= N) break;                         // uniform per wave
         const int n = u + 1;
-        const int nch = (n + 63) >> 6;
-        float e[MAXCH];
-        float mx = -INFINITY;
-#pragma unroll
-        for (int i = 0; i < MAXCH; ++i) {
-          const int idx = i * 64 + lane;
-          e[i] = (i < nch && idx < n) ? lds_logits[r * ld + idx] : -INFINITY;
-          mx = fmaxf(mx, e[i]);
-        }
-        mx = wave_max(mx);
-        float part = 0.f;
-#pragma unroll
-        for (int i = 0; i < MAXCH; ++i) {
-          if (i < nch) {
-            e[i] = (e[i] == -INFINITY) ? 0.f : __expf(e[i] - mx);
-            part += e[i];
-          } else {
-            e[i] = 0.f;
-          }
-        }
-        const float total = wave_sum(part);
-        const float target = top_p * total;
-
-        uint32_t tstar = 0;       // selected: key > tstar_minus ... see below
-        float gstar = 0.f;
-        const bool all = top_p >= 1.0f;
-        if (!all) {
-          // largest key T with mass{key > T} >= target; T* = T + 1 is then the smallest
-          // key whose strictly-larger mass is < target (and T* is some element's key).
-          uint32_t T = 0;
-          for (int bit = 30; bit >= 0; --bit) {
-            const uint32_t cand = T | (1u << bit);
-            float gp = 0.f;
-#pragma unroll
-            for (int i = 0; i < MAXCH; ++i)
-              if (i < nch) gp += (__float_as_uint(e[i]) > cand) ? e[i] : 0.f;
-            const float G = wave_sum(gp);
-            if (!(G < target)) T = cand;
-          }
-          tstar = T + 1;
-          float gp = 0.f;
-#pragma unroll
-          for (int i = 0; i < MAXCH; ++i)
-            if (i < nch) gp += (__float_as_uint(e[i]) > tstar) ? e[i] : 0.f;
-          gstar = wave_sum(gp);
-        }
-        const float tie_val = __uint_as_float(tstar);
-        int tie_base = 0;
-#pragma unroll
-        for (int i = 0; i < MAXCH; ++i) {
-          if (i < nch) {
-            const int idx = i * 64 + lane;
-            bool sel;
-            if (all) {
-              sel = idx < n;
-            } else {
-              const uint32_t key = __float_as_uint(e[i]);
-              const bool tie = key == tstar;
-              const uint64_t tb = __ballot(tie);
-              const int rank = tie_base + __popcll(tb & ((1ull << lane) - 1ull));
-              sel = (key > tstar) || (tie && (gstar + (float)rank * tie_val < target));
-              tie_base += __popcll(tb);
-            }
-            const uint64_t bal = __ballot(sel);
-            if (lane == i) myword[rr] |= bal;
-          }
-        }
+        const float* row_logits = lds_logits + r * ld;
+        uint64_t* bits_row = &lds_bits[r][0];
+        if (n <= 128) select_row<2>(row_logits, n, top_p, lane, bits_row);
+        else if (n <= 256) select_row<4>(row_logits, n, top_p, lane, bits_row);
+        else if (n <= 512) select_row<8>(row_logits, n, top_p, lane, bits_row);
+        else if (MAXCH <= 16 || n <= 1024) select_row<16>(row_logits, n, top_p, lane, bits_row);
+        else select_row<MAXCH>(row_logits, n, top_p, lane, bits_row);
       }
-      __syncthreads();                             // LDS is reused by the next band
+      __syncthreads();                             // LDS logits are reused by the next band
     }
   }
 
   if (!DUMP) {
-#pragma unroll
+#pragma unroll 1
     for (int rr = 0; rr < 4; ++rr) {
-      const int u = u0 + wave * 4 + rr;
-      if (u >= N) continue;
+      const int r = wave * 4 + rr;
+      const int u = u0 + r;
+      if (u >= N) break;
       const size_t row = (size_t)hq * N + u;
-      const int cnt = wave_sum((int)(lane < W ? __popcll(myword[rr]) : 0));
-      if (lane < W) mask_bits[row * W + lane] = myword[rr];
+      const uint64_t word = lane < W ? lds_bits[r][lane] : 0ull;
+      const int cnt = wave_sum((int)__popcll(word));
+      if (lane < W) mask_bits[row * W + lane] = word;
       if (lane == 0) row_ptr[row + 1] = cnt;
     }
   }
@@ -333,35 +368,47 @@ __global__ __launch_bounds__(256) void row_count_kernel(const uint64_t* __restri
 }
 
 // In-place: row_ptr[r+1] holds the count of row r on entry, the inclusive prefix sum on
-// exit; row_ptr[0] = 0.  Single workgroup of 1024 threads, each owning a contiguous span.
+// exit; row_ptr[0] = 0.  Single workgroup of 1024 threads sweeping the array in chunks of
+// 4096 counts (4 consecutive counts per thread, so loads and stores are coalesced).
 __global__ __launch_bounds__(1024) void scan_kernel(int32_t* __restrict__ row_ptr, int R,
                                                     int64_t capacity, int32_t* __restrict__ info) {
   __shared__ int wave_tot[16];
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  const int per = (R + 1023) / 1024;
-  const int lo = min(R, t * per), hi = min(R, lo + per);
-  int s = 0;
-  for (int i = lo; i < hi; ++i) s += row_ptr[i + 1];
-  // inclusive scan of s across the workgroup
-  int inc = s;
+  int carry = 0;
+  for (int base = 0; base < R; base += 4096) {
+    const int i0 = base + t * 4;
+    int v[4];
 #pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    const int y = __shfl_up(inc, off, 64);
-    if (lane >= off) inc += y;
+    for (int k = 0; k < 4; ++k) v[k] = (i0 + k < R) ? row_ptr[1 + i0 + k] : 0;
+    v[1] += v[0];
+    v[2] += v[1];
+    v[3] += v[2];
+    int inc = v[3];
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const int y = __shfl_up(inc, off, 64);
+      if (lane >= off) inc += y;
+    }
+    if (lane == 63) wave_tot[wave] = inc;
+    __syncthreads();
+    int before = carry + inc - v[3];               // everything ahead of this thread's 4 counts
+    int chunk_total = 0;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) {
+      const int wt = wave_tot[w];
+      if (w < wave) before += wt;
+      chunk_total += wt;
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+      if (i0 + k < R) row_ptr[1 + i0 + k] = before + v[k];
+    carry += chunk_total;
+    __syncthreads();                               // wave_tot is rewritten by the next chunk
   }
-  if (lane == 63) wave_tot[wave] = inc;
-  __syncthreads();
-  int base = 0;
-  for (int w = 0; w < wave; ++w) base += wave_tot[w];
-  int run = base + inc - s;                        // exclusive prefix of this thread's span
-  for (int i = lo; i < hi; ++i) {
-    run += row_ptr[i + 1];
-    row_ptr[i + 1] = run;
-  }
-  if (t == 0) row_ptr[0] = 0;
-  if (t == 1023) {
-    info[0] = run;
-    info[1] = ((int64_t)run > capacity) ? 1 : 0;
+  if (t == 0) {
+    row_ptr[0] = 0;
+    info[0] = carry;
+    info[1] = ((int64_t)carry > capacity) ? 1 : 0;
     info[2] = 0;
     info[3] = 0;
   }
