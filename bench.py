@@ -84,6 +84,47 @@ def cpu_baseline(w, Qb, Kb, Vb, mask, flop_dense: float, budget_rows: int = 48):
     }
 
 
+def estimate_curve(args) -> int:
+    """prism_estimate latency at 8K..128K for B = 128 and 64 on the Llama-shaped layer."""
+    import numpy as np
+    import torch
+
+    from paper_2602_08426_amd import binding as pb
+    from paper_2602_08426_amd import workloads as wl
+
+    base = wl.WORKLOADS["c4_llama_128k"]
+    rows = []
+    for L in (8192, 16384, 32768, 65536, 131072):
+        w = wl.small_variant(base, L)
+        Qb, Kb, _ = wl.generate(w, n_threads=args.gen_threads)
+        q, k = pb.bf16_bits_to_device(Qb), pb.bf16_bits_to_device(Kb)
+        for B in (128, 64):
+            params = pb.make_params(w.n_q_heads, w.n_kv_heads, L, B, w.d_high, w.d_low, w.top_p)
+            N = L // B
+            pairs = w.n_q_heads * N * (N + 1) // 2
+            mask_bits, row_ptr, col_idx, info = pb.alloc_estimate_outputs(params, pairs)
+            ws = pb.alloc_workspace(pb.prism_estimate_workspace_bytes(params))
+            for _ in range(3):
+                pb.prism_estimate(params, q, k, mask_bits, row_ptr, col_idx, pairs, info, ws)
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(10):
+                pb.prism_estimate(params, q, k, mask_bits, row_ptr, col_idx, pairs, info, ws)
+            b.record()
+            torch.cuda.synchronize()
+            ms = a.elapsed_time(b) / 10
+            dens = int(info.cpu()[0]) / pairs
+            rows.append({"seq_len": L, "block": B, "ms_estimate": round(ms, 4), "block_density": round(dens, 4)})
+            log(f"L={L} B={B}: estimate {ms:.3f} ms, density {dens:.3f}")
+            del mask_bits, row_ptr, col_idx, info, ws
+        del q, k
+    print(json.dumps({"metric": "prism_estimate latency vs sequence length", "unit": "ms", "data": "synthetic",
+                      "paper_context": "paper: ~9 ms (B=128) and ~22 ms (B=64) at 128K on its hardware",
+                      "rows": rows}), flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -93,6 +134,9 @@ def main() -> int:
     ap.add_argument("--dense-reps", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--gen-threads", type=int, default=16)
+    ap.add_argument("--estimate-curve", action="store_true",
+                    help="instead of the step benchmark: prism_estimate time vs sequence length for "
+                         "B = 128 and B = 64 (the block-size study of the paper's App. E), one JSON line")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (known HBM traffic) for counter calibration")
     args = ap.parse_args()
@@ -111,6 +155,8 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     pb._load()                                   # fails loudly if libprism.so is missing
+    if args.estimate_curve:
+        return estimate_curve(args)
     w = wl.WORKLOADS[args.workload]
     h, hkv, L, B, N, d = w.n_q_heads, w.n_kv_heads, w.seq_len, w.block, w.n_blocks, w.head_dim
 

@@ -472,7 +472,7 @@ static int check_image(const prism_params* params, const void* img, size_t bytes
   return PRISM_OK;
 }
 
-static int persistent_grid(int rows) {
+static int persistent_grid(int rows, int wgs_per_cu) {
   static int cus = 0;                       // compute units of the current device
   if (cus == 0) {
     int dev = 0;
@@ -481,7 +481,7 @@ static int persistent_grid(int rows) {
       return -1;
     cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
   }
-  const int resident = cus * 2;             // two workgroups per CU (LDS and registers)
+  const int resident = cus * wgs_per_cu;
   return rows < resident ? rows : resident;
 }
 
@@ -530,7 +530,8 @@ extern "C" int prism_sparse_attn_pre(const prism_params* params, const void* q_b
   int32_t* order = reinterpret_cast<int32_t*>(ws + W.order);
   int32_t* hist = reinterpret_cast<int32_t*>(ws + W.hist);
   int32_t* counter = reinterpret_cast<int32_t*>(ws + W.counter);
-  const int grid = persistent_grid(R);
+  // resident workgroups per CU: 64 KB of LDS and 4 waves each at B = 128, half of that at B = 64
+  const int grid = persistent_grid(R, params->block == 128 ? 2 : 4);
   if (grid <= 0) return PRISM_ERR_HIP;
 
   hipLaunchKernelGGL(queue_reset_kernel, dim3((N + 1 + 255) / 256), dim3(256), 0, st, hist, N + 1,
