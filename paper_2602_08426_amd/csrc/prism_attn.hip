@@ -144,7 +144,6 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int l32 = lane & 31, hf = lane >> 5;
   const int g = h / h_kv;
-  const int R = h * N;
   const float sm_scale = 1.4426950408889634f * 0.08838834764831845f;   // log2(e) / sqrt(128)
 
   // LDS read offsets of this lane inside a 32-row slab: row l32, swizzled chunk
@@ -158,17 +157,28 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
   for (int st = 0; st < KT * 2; ++st)
     voff[st] = l32 * (BLK * 2) + (((2 * st + hf) ^ (l32 & (C::kVtCpr - 1))) << 4);
 
-  // Persistent workgroups pull (head, q-block) rows from a queue ordered longest list
-  // first, so that heads of very different density keep every CU busy until the end.
-  // Every workgroup leaves the loop as soon as the queue is empty.
+  // Persistent workgroups pull work from queues ordered longest list first, so that heads
+  // of very different density keep every CU busy until the end.  The unit of the order is the
+  // GQA group (kv head, q-block): its g rows are handed out back to back to workgroups of the
+  // same XCD (workgroups are dealt round-robin to the 8 XCDs, and each XCD has its own L2), so
+  // that the K/V tiles the rows of a group share are fetched from HBM once.  Groups are dealt
+  // to the XCD queues round-robin in sorted order, which keeps the queues balanced.
+  // Every workgroup leaves the loop as soon as its queue is exhausted.
+  const int n_queues = gridDim.x < 8 ? 1 : 8;
+  const int my_queue = blockIdx.x % n_queues;
+  const int n_groups = h_kv * N;
   for (;;) {
-  if (t == 0) next_item = atomicAdd(counter, 1);
+  if (t == 0) next_item = atomicAdd(counter + my_queue, 1);
   __syncthreads();
-  const int item = __builtin_amdgcn_readfirstlane(next_item);   // wave-uniform from here on
-  if (item >= R) break;
-  const int row_id = __builtin_amdgcn_readfirstlane(order[item]);
-  const int hq = row_id / N, u = row_id - hq * N;
-  const int kvh = hq / g;
+  const int pulled = __builtin_amdgcn_readfirstlane(next_item);   // wave-uniform from here on
+  const int round = pulled / g, member = pulled - round * g;
+  if ((int64_t)round * n_queues >= n_groups) break;               // this deal round is past the end
+  const int slot = round * n_queues + my_queue;
+  if (slot >= n_groups) continue;                                  // hole in the last deal round
+  const int group_id = __builtin_amdgcn_readfirstlane(order[slot]);
+  const int kvh = group_id / N, u = group_id - kvh * N;
+  const int hq = kvh * g + member;
+  const int row_id = hq * N + u;
 
   // list bounds as 32-bit scalars (CSR offsets are int32; col_count is clamped to that range)
   const int cap = col_count > 0x7fffffff ? 0x7fffffff : (int)col_count;
@@ -362,31 +372,39 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
 }
 
 // =====================================================================================
-// Work queue: rows sorted by list length, longest first (counting sort on 0..N).
-//   queue_reset_kernel : zero the histogram and the queue counter
-//   queue_hist_kernel  : hist[len] over all rows (LDS-private histograms, integer atomics)
-//   queue_scan_kernel  : start[len] = number of rows with a longer list
-//   queue_fill_kernel  : order[start[len] + k] = row  (order inside one length is arbitrary)
+// Work queue: GQA groups (kv head, q-block) sorted by their longest list, longest first
+// (counting sort on 0..N).
+//   queue_reset_kernel : zero the histogram and the queue counters
+//   queue_hist_kernel  : hist[len] over all groups (LDS-private histograms, integer atomics)
+//   queue_scan_kernel  : start[len] = number of groups with a longer list
+//   queue_fill_kernel  : order[start[len] + k] = group  (order inside one length is arbitrary)
 // =====================================================================================
 __global__ __launch_bounds__(256) void queue_reset_kernel(int32_t* __restrict__ hist, int nbins,
-                                                          int32_t* __restrict__ counter) {
+                                                          int32_t* __restrict__ counters) {
   const int i = blockIdx.x * 256 + threadIdx.x;
   if (i < nbins) hist[i] = 0;
-  if (i == 0) *counter = 0;
+  if (i < 8) counters[i] = 0;
 }
 
-__device__ __forceinline__ int row_len(const int32_t* __restrict__ row_ptr, int r, int N) {
-  const int n = row_ptr[r + 1] - row_ptr[r];
-  return n < 0 ? 0 : (n > N ? N : n);
+// sort key of a GQA group (kv head, q-block): the longest list among its g rows
+__device__ __forceinline__ int group_len(const int32_t* __restrict__ row_ptr, int gid, int g, int N) {
+  const int kvh = gid / N, u = gid - kvh * N;
+  int m = 0;
+  for (int j = 0; j < g; ++j) {
+    const int r = (kvh * g + j) * N + u;
+    const int n = row_ptr[r + 1] - row_ptr[r];
+    m = max(m, n < 0 ? 0 : (n > N ? N : n));
+  }
+  return m;
 }
 
-__global__ __launch_bounds__(256) void queue_hist_kernel(const int32_t* __restrict__ row_ptr, int R,
-                                                         int N, int32_t* __restrict__ hist) {
+__global__ __launch_bounds__(256) void queue_hist_kernel(const int32_t* __restrict__ row_ptr, int G,
+                                                         int g, int N, int32_t* __restrict__ hist) {
   __shared__ int lh[kMaxBlocks + 1];
   for (int i = threadIdx.x; i <= N; i += 256) lh[i] = 0;
   __syncthreads();
-  for (int r = blockIdx.x * 256 + threadIdx.x; r < R; r += gridDim.x * 256)
-    atomicAdd(&lh[row_len(row_ptr, r, N)], 1);
+  for (int gid = blockIdx.x * 256 + threadIdx.x; gid < G; gid += gridDim.x * 256)
+    atomicAdd(&lh[group_len(row_ptr, gid, g, N)], 1);
   __syncthreads();
   for (int i = threadIdx.x; i <= N; i += 256)
     if (lh[i] != 0) atomicAdd(&hist[i], lh[i]);
@@ -419,18 +437,18 @@ __global__ __launch_bounds__(1024) void queue_scan_kernel(int32_t* __restrict__ 
   }
 }
 
-// Each workgroup ranks its 256 rows per length in LDS and reserves one range per distinct
-// length with a single global atomic, so rows of equal length do not serialise on one address.
-__global__ __launch_bounds__(256) void queue_fill_kernel(const int32_t* __restrict__ row_ptr, int R,
-                                                         int N, int32_t* __restrict__ start,
+// Each workgroup ranks its 256 groups per length in LDS and reserves one range per distinct
+// length with a single global atomic, so groups of equal length do not serialise on one address.
+__global__ __launch_bounds__(256) void queue_fill_kernel(const int32_t* __restrict__ row_ptr, int G,
+                                                         int g, int N, int32_t* __restrict__ start,
                                                          int32_t* __restrict__ order) {
   __shared__ int cnt[kMaxBlocks + 1];
   for (int i = threadIdx.x; i <= N; i += 256) cnt[i] = 0;
   __syncthreads();
-  const int r = blockIdx.x * 256 + threadIdx.x;
+  const int gid = blockIdx.x * 256 + threadIdx.x;
   int len = 0, rank = 0;
-  if (r < R) {
-    len = row_len(row_ptr, r, N);
+  if (gid < G) {
+    len = group_len(row_ptr, gid, g, N);
     rank = atomicAdd(&cnt[len], 1);
   }
   __syncthreads();
@@ -439,9 +457,9 @@ __global__ __launch_bounds__(256) void queue_fill_kernel(const int32_t* __restri
     if (c != 0) cnt[i] = atomicAdd(&start[i], c);  // count -> first position of this workgroup's range
   }
   __syncthreads();
-  if (r < R) {
+  if (gid < G) {
     const int pos = cnt[len] + rank;
-    if (pos >= 0 && pos < R) order[pos] = r;
+    if (pos >= 0 && pos < G) order[pos] = gid;
   }
 }
 
@@ -449,7 +467,7 @@ __global__ __launch_bounds__(256) void queue_fill_kernel(const int32_t* __restri
 
 using namespace prism;
 
-// ---- workspace layout: [ V image | order[h*N] | hist[N+1] | counter ] -------------------
+// ---- workspace layout: [ V image | order[h_kv*N] | hist[N+1] | 8 queue counters ] -------------------
 struct AttnWs {
   size_t image, order, hist, counter, total;
 };
@@ -458,9 +476,9 @@ static AttnWs attn_ws(const prism_params* p) {
   AttnWs w;
   size_t off = 0;
   w.image = off;   off = align_up(off + (size_t)p->n_kv_heads * p->seq_len * kHeadDim * 2, 256);
-  w.order = off;   off = align_up(off + (size_t)p->n_q_heads * N * sizeof(int32_t), 256);
+  w.order = off;   off = align_up(off + (size_t)p->n_kv_heads * N * sizeof(int32_t), 256);
   w.hist = off;    off = align_up(off + (N + 1) * sizeof(int32_t), 256);
-  w.counter = off; off = align_up(off + sizeof(int32_t), 256);
+  w.counter = off; off = align_up(off + 8 * sizeof(int32_t), 256);
   w.total = off;
   return w;
 }
@@ -536,10 +554,11 @@ extern "C" int prism_sparse_attn_pre(const prism_params* params, const void* q_b
 
   hipLaunchKernelGGL(queue_reset_kernel, dim3((N + 1 + 255) / 256), dim3(256), 0, st, hist, N + 1,
                      counter);
-  hipLaunchKernelGGL(queue_hist_kernel, dim3(64), dim3(256), 0, st, row_ptr, R, N, hist);
+  const int G = h_kv * N, g = h / h_kv;
+  hipLaunchKernelGGL(queue_hist_kernel, dim3(64), dim3(256), 0, st, row_ptr, G, g, N, hist);
   hipLaunchKernelGGL(queue_scan_kernel, dim3(1), dim3(1024), 0, st, hist, N);
-  hipLaunchKernelGGL(queue_fill_kernel, dim3((R + 255) / 256), dim3(256), 0, st, row_ptr, R, N, hist,
-                     order);
+  hipLaunchKernelGGL(queue_fill_kernel, dim3((G + 255) / 256), dim3(256), 0, st, row_ptr, G, g, N,
+                     hist, order);
   if (params->block == 128)
     hipLaunchKernelGGL(sparse_attn_kernel<128>, dim3(grid), dim3(AttnCfg<128>::kThreads), 0, st,
                        (const uint16_t*)q_bf16, (const uint16_t*)k_bf16, (const uint16_t*)v_image,

@@ -47,7 +47,7 @@ def test_workspace_queries(lib):
     assert n >= heads * N * 128 * 2 * 3 + heads * N * 16
     assert n < 64 << 20
     ws = pb.prism_sparse_attn_workspace_bytes(p)
-    assert 8 * 131072 * 128 * 2 + 32 * 1024 * 4 <= ws < 8 * 131072 * 128 * 2 + (1 << 20)
+    assert 8 * 131072 * 128 * 2 + 8 * 1024 * 4 <= ws < 8 * 131072 * 128 * 2 + (1 << 20)
 
 
 @pytest.mark.parametrize("kw,status", [
