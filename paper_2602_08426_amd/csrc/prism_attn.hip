@@ -372,13 +372,21 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
 }
 
 // =====================================================================================
-// Work queue: GQA groups (kv head, q-block) sorted by their longest list, longest first
-// (counting sort on 0..N).
+// Work queue: GQA groups (kv head, q-block) in the order  (phase ascending, longest list
+// descending), by a counting sort.
+//   phase  = kv head / heads_per_phase: the kv heads are taken a few at a time so that the K
+//            and V^T of the heads in flight fit the 256 MB memory-side cache (at 128K tokens a
+//            kv head is 67 MB of K + V^T and all eight do not fit);
+//   length = the longest list among the g rows of the group, quantised to `levels` steps.
 //   queue_reset_kernel : zero the histogram and the queue counters
-//   queue_hist_kernel  : hist[len] over all groups (LDS-private histograms, integer atomics)
-//   queue_scan_kernel  : start[len] = number of groups with a longer list
-//   queue_fill_kernel  : order[start[len] + k] = group  (order inside one length is arbitrary)
+//   queue_hist_kernel  : hist[bin] over all groups (LDS-private histograms, integer atomics)
+//   queue_scan_kernel  : start[bin] = number of groups in earlier bins
+//   queue_fill_kernel  : order[start[bin] + k] = group  (order inside one bin is arbitrary)
 // =====================================================================================
+struct QueueCfg {
+  int n_groups, g, N, heads_per_phase, levels, n_bins;
+};
+
 __global__ __launch_bounds__(256) void queue_reset_kernel(int32_t* __restrict__ hist, int nbins,
                                                           int32_t* __restrict__ counters) {
   const int i = blockIdx.x * 256 + threadIdx.x;
@@ -386,40 +394,38 @@ __global__ __launch_bounds__(256) void queue_reset_kernel(int32_t* __restrict__ 
   if (i < 8) counters[i] = 0;
 }
 
-// sort key of a GQA group (kv head, q-block): the longest list among its g rows
-__device__ __forceinline__ int group_len(const int32_t* __restrict__ row_ptr, int gid, int g, int N) {
-  const int kvh = gid / N, u = gid - kvh * N;
+__device__ __forceinline__ int group_bin(const int32_t* __restrict__ row_ptr, int gid, const QueueCfg& c) {
+  const int kvh = gid / c.N, u = gid - kvh * c.N;
   int m = 0;
-  for (int j = 0; j < g; ++j) {
-    const int r = (kvh * g + j) * N + u;
+  for (int j = 0; j < c.g; ++j) {
+    const int r = (kvh * c.g + j) * c.N + u;
     const int n = row_ptr[r + 1] - row_ptr[r];
-    m = max(m, n < 0 ? 0 : (n > N ? N : n));
+    m = max(m, n < 0 ? 0 : (n > c.N ? c.N : n));
   }
-  return m;
+  const int q = (int)(((int64_t)m * (c.levels - 1)) / c.N);          // 0 .. levels-1
+  return (kvh / c.heads_per_phase) * c.levels + (c.levels - 1 - q);
 }
 
-__global__ __launch_bounds__(256) void queue_hist_kernel(const int32_t* __restrict__ row_ptr, int G,
-                                                         int g, int N, int32_t* __restrict__ hist) {
+__global__ __launch_bounds__(256) void queue_hist_kernel(const int32_t* __restrict__ row_ptr,
+                                                         QueueCfg c, int32_t* __restrict__ hist) {
   __shared__ int lh[kMaxBlocks + 1];
-  for (int i = threadIdx.x; i <= N; i += 256) lh[i] = 0;
+  for (int i = threadIdx.x; i < c.n_bins; i += 256) lh[i] = 0;
   __syncthreads();
-  for (int gid = blockIdx.x * 256 + threadIdx.x; gid < G; gid += gridDim.x * 256)
-    atomicAdd(&lh[group_len(row_ptr, gid, g, N)], 1);
+  for (int gid = blockIdx.x * 256 + threadIdx.x; gid < c.n_groups; gid += gridDim.x * 256)
+    atomicAdd(&lh[group_bin(row_ptr, gid, c)], 1);
   __syncthreads();
-  for (int i = threadIdx.x; i <= N; i += 256)
+  for (int i = threadIdx.x; i < c.n_bins; i += 256)
     if (lh[i] != 0) atomicAdd(&hist[i], lh[i]);
 }
 
-// single workgroup: start[len] = sum of hist[l] for l > len   (in place)
-__global__ __launch_bounds__(1024) void queue_scan_kernel(int32_t* __restrict__ hist, int N) {
+// single workgroup: exclusive prefix sum over the bins, in place
+__global__ __launch_bounds__(1024) void queue_scan_kernel(int32_t* __restrict__ hist, int nb) {
   __shared__ int wave_tot[16];
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  const int nb = N + 1;
   const int per = (nb + 1023) / 1024;
-  // thread t owns positions lo..hi-1 of the array read from the longest length down
   const int lo = min(nb, t * per), hi = min(nb, lo + per);
   int s = 0;
-  for (int i = lo; i < hi; ++i) s += hist[N - i];
+  for (int i = lo; i < hi; ++i) s += hist[i];
   int inc = s;
 #pragma unroll
   for (int off = 1; off < 64; off <<= 1) {
@@ -431,35 +437,35 @@ __global__ __launch_bounds__(1024) void queue_scan_kernel(int32_t* __restrict__ 
   int run = inc - s;
   for (int w = 0; w < wave; ++w) run += wave_tot[w];
   for (int i = lo; i < hi; ++i) {
-    const int c = hist[N - i];
-    hist[N - i] = run;
+    const int c = hist[i];
+    hist[i] = run;
     run += c;
   }
 }
 
-// Each workgroup ranks its 256 groups per length in LDS and reserves one range per distinct
-// length with a single global atomic, so groups of equal length do not serialise on one address.
-__global__ __launch_bounds__(256) void queue_fill_kernel(const int32_t* __restrict__ row_ptr, int G,
-                                                         int g, int N, int32_t* __restrict__ start,
+// Each workgroup ranks its 256 groups per bin in LDS and reserves one range per distinct bin
+// with a single global atomic, so groups of one bin do not serialise on one address.
+__global__ __launch_bounds__(256) void queue_fill_kernel(const int32_t* __restrict__ row_ptr,
+                                                         QueueCfg c, int32_t* __restrict__ start,
                                                          int32_t* __restrict__ order) {
   __shared__ int cnt[kMaxBlocks + 1];
-  for (int i = threadIdx.x; i <= N; i += 256) cnt[i] = 0;
+  for (int i = threadIdx.x; i < c.n_bins; i += 256) cnt[i] = 0;
   __syncthreads();
   const int gid = blockIdx.x * 256 + threadIdx.x;
-  int len = 0, rank = 0;
-  if (gid < G) {
-    len = group_len(row_ptr, gid, g, N);
-    rank = atomicAdd(&cnt[len], 1);
+  int bin = 0, rank = 0;
+  if (gid < c.n_groups) {
+    bin = group_bin(row_ptr, gid, c);
+    rank = atomicAdd(&cnt[bin], 1);
   }
   __syncthreads();
-  for (int i = threadIdx.x; i <= N; i += 256) {
-    const int c = cnt[i];
-    if (c != 0) cnt[i] = atomicAdd(&start[i], c);  // count -> first position of this workgroup's range
+  for (int i = threadIdx.x; i < c.n_bins; i += 256) {
+    const int k = cnt[i];
+    if (k != 0) cnt[i] = atomicAdd(&start[i], k);  // count -> first position of this workgroup's range
   }
   __syncthreads();
-  if (gid < G) {
-    const int pos = cnt[len] + rank;
-    if (pos >= 0 && pos < G) order[pos] = gid;
+  if (gid < c.n_groups) {
+    const int pos = cnt[bin] + rank;
+    if (pos >= 0 && pos < c.n_groups) order[pos] = gid;
   }
 }
 
@@ -467,7 +473,7 @@ __global__ __launch_bounds__(256) void queue_fill_kernel(const int32_t* __restri
 
 using namespace prism;
 
-// ---- workspace layout: [ V image | order[h_kv*N] | hist[N+1] | 8 queue counters ] -------------------
+// ---- workspace layout: [ V image | order[h_kv*N] | hist[bins] | 8 queue counters ] -------------------
 struct AttnWs {
   size_t image, order, hist, counter, total;
 };
@@ -477,7 +483,7 @@ static AttnWs attn_ws(const prism_params* p) {
   size_t off = 0;
   w.image = off;   off = align_up(off + (size_t)p->n_kv_heads * p->seq_len * kHeadDim * 2, 256);
   w.order = off;   off = align_up(off + (size_t)p->n_kv_heads * N * sizeof(int32_t), 256);
-  w.hist = off;    off = align_up(off + (N + 1) * sizeof(int32_t), 256);
+  w.hist = off;    off = align_up(off + (kMaxBlocks + 1) * sizeof(int32_t), 256);
   w.counter = off; off = align_up(off + 8 * sizeof(int32_t), 256);
   w.total = off;
   return w;
@@ -552,12 +558,27 @@ extern "C" int prism_sparse_attn_pre(const prism_params* params, const void* q_b
   const int grid = persistent_grid(R, params->block == 128 ? 2 : 4);
   if (grid <= 0) return PRISM_ERR_HIP;
 
-  hipLaunchKernelGGL(queue_reset_kernel, dim3((N + 1 + 255) / 256), dim3(256), 0, st, hist, N + 1,
-                     counter);
-  const int G = h_kv * N, g = h / h_kv;
-  hipLaunchKernelGGL(queue_hist_kernel, dim3(64), dim3(256), 0, st, row_ptr, G, g, N, hist);
-  hipLaunchKernelGGL(queue_scan_kernel, dim3(1), dim3(1024), 0, st, hist, N);
-  hipLaunchKernelGGL(queue_fill_kernel, dim3((G + 255) / 256), dim3(256), 0, st, row_ptr, G, g, N,
+  // queue order: kv heads in phases that fit the memory-side cache, longest lists first
+  QueueCfg qc;
+  qc.n_groups = h_kv * N;
+  qc.g = h / h_kv;
+  qc.N = N;
+  const size_t head_bytes = (size_t)L * kHeadDim * 2 * 2;                 // K + V^T of one kv head
+  const size_t cache_budget = (size_t)160 << 20;
+  qc.heads_per_phase = (int)(cache_budget / head_bytes) < 1 ? 1 : (int)(cache_budget / head_bytes);
+  const int n_phases = (h_kv + qc.heads_per_phase - 1) / qc.heads_per_phase;
+  qc.levels = (N + 1) < (kMaxBlocks + 1) / n_phases ? (N + 1) : (kMaxBlocks + 1) / n_phases;
+  if (qc.levels < 2) {                                                     // more phases than bins
+    qc.heads_per_phase = (h_kv + (kMaxBlocks + 1) / 2 - 1) / ((kMaxBlocks + 1) / 2);
+    qc.levels = 2;
+  }
+  qc.n_bins = ((h_kv + qc.heads_per_phase - 1) / qc.heads_per_phase) * qc.levels;
+
+  hipLaunchKernelGGL(queue_reset_kernel, dim3((qc.n_bins + 255) / 256), dim3(256), 0, st, hist,
+                     qc.n_bins, counter);
+  hipLaunchKernelGGL(queue_hist_kernel, dim3(64), dim3(256), 0, st, row_ptr, qc, hist);
+  hipLaunchKernelGGL(queue_scan_kernel, dim3(1), dim3(1024), 0, st, hist, qc.n_bins);
+  hipLaunchKernelGGL(queue_fill_kernel, dim3((qc.n_groups + 255) / 256), dim3(256), 0, st, row_ptr, qc,
                      hist, order);
   if (params->block == 128)
     hipLaunchKernelGGL(sparse_attn_kernel<128>, dim3(grid), dim3(AttnCfg<128>::kThreads), 0, st,
