@@ -153,71 +153,101 @@ __global__ __launch_bounds__(64) void scale_kernel(const float* __restrict__ ene
 // =====================================================================================
 constexpr int kStripRows = 16;
 
-// Top-p selection of one row of one band by one wave.  The row (n <= 64*NCH causal logits)
-// lives in registers: column 64*i + lane in e[i].  Selected bits are OR-ed into bits_row
-// (LDS, one 64-bit word per 64 columns).
+// Top-p selection of the four consecutive rows of one band that a wave owns.  Row k has
+// n0 + k causal logits (rows with n <= 0 are skipped); each row lives in registers: column
+// 64*i + lane in e[k][i].  The four rows are advanced together so that their wave reductions
+// (dependent DPP chains) overlap.  Selected bits are OR-ed into the rows' LDS bit words.
+constexpr int kRowsPerWave = 4;
+
 template <int NCH>
-__device__ __forceinline__ void select_row(const float* __restrict__ row_logits, int n, float top_p,
-                                           int lane, uint64_t* __restrict__ bits_row) {
-  float e[NCH];
-  float mx = -INFINITY;
+__device__ __forceinline__ void select_rows(const float* __restrict__ logits, int ld, int n0, int nrows,
+                                            float top_p, int lane, uint64_t* __restrict__ bits,
+                                            int bits_ld) {
+  float e[kRowsPerWave][NCH];
+  float total[kRowsPerWave], target[kRowsPerWave];
 #pragma unroll
-  for (int i = 0; i < NCH; ++i) {
-    const int idx = i * 64 + lane;
-    e[i] = idx < n ? row_logits[idx] : -INFINITY;
-    mx = fmaxf(mx, e[i]);
-  }
-  mx = wave_max(mx);
-  float part = 0.f;
+  for (int k = 0; k < kRowsPerWave; ++k) {
+    const int n = k < nrows ? n0 + k : 0;
+    float mx = -INFINITY;
 #pragma unroll
-  for (int i = 0; i < NCH; ++i) {
-    e[i] = (e[i] == -INFINITY) ? 0.f : __expf(e[i] - mx);       // softmax numerators, max one = 1
-    part += e[i];
+    for (int i = 0; i < NCH; ++i) {
+      const int idx = i * 64 + lane;
+      e[k][i] = idx < n ? logits[k * ld + idx] : -INFINITY;
+      mx = fmaxf(mx, e[k][i]);
+    }
+    mx = wave_max(mx);
+    float part = 0.f;
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      e[k][i] = (e[k][i] == -INFINITY) ? 0.f : __expf(e[k][i] - mx);   // softmax numerators, max one = 1
+      part += e[k][i];
+    }
+    total[k] = wave_sum(part);
+    target[k] = top_p * total[k];
   }
-  const float total = wave_sum(part);
-  const float target = top_p * total;
   const bool all = top_p >= 1.0f;
 
-  uint32_t tstar = 0;
-  float gstar = 0.f;
+  uint32_t tstar[kRowsPerWave];
+  float gstar[kRowsPerWave];
+#pragma unroll
+  for (int k = 0; k < kRowsPerWave; ++k) {
+    tstar[k] = 0;
+    gstar[k] = 0.f;
+  }
   if (!all) {
-    // largest key T with mass{key > T} >= target; T* = T + 1 is then the smallest key whose
-    // strictly-larger mass is < target (and T* is some element's key).  Keys are bit patterns of
-    // values in [0, 1], i.e. <= 0x3F800000: bit 30 is never set.
-    uint32_t T = 0;
+    // per row: largest key T with mass{key > T} >= target; T* = T + 1 is then the smallest key
+    // whose strictly-larger mass is < target (and T* is some element's key).  Keys are bit
+    // patterns of values in [0, 1], i.e. <= 0x3F800000: bit 30 is never set.
+    uint32_t T[kRowsPerWave];
+#pragma unroll
+    for (int k = 0; k < kRowsPerWave; ++k) T[k] = 0;
     for (int bit = 29; bit >= 0; --bit) {
-      const uint32_t cand = T | (1u << bit);
+      float gp[kRowsPerWave];
+#pragma unroll
+      for (int k = 0; k < kRowsPerWave; ++k) {
+        const uint32_t cand = T[k] | (1u << bit);
+        gp[k] = 0.f;
+#pragma unroll
+        for (int i = 0; i < NCH; ++i) gp[k] += (__float_as_uint(e[k][i]) > cand) ? e[k][i] : 0.f;
+      }
+#pragma unroll
+      for (int k = 0; k < kRowsPerWave; ++k)
+        if (!(wave_sum(gp[k]) < target[k])) T[k] |= (1u << bit);
+    }
+#pragma unroll
+    for (int k = 0; k < kRowsPerWave; ++k) {
+      tstar[k] = T[k] + 1;
       float gp = 0.f;
 #pragma unroll
-      for (int i = 0; i < NCH; ++i) gp += (__float_as_uint(e[i]) > cand) ? e[i] : 0.f;
-      if (!(wave_sum(gp) < target)) T = cand;
+      for (int i = 0; i < NCH; ++i) gp += (__float_as_uint(e[k][i]) > tstar[k]) ? e[k][i] : 0.f;
+      gstar[k] = wave_sum(gp);
     }
-    tstar = T + 1;
-    float gp = 0.f;
-#pragma unroll
-    for (int i = 0; i < NCH; ++i) gp += (__float_as_uint(e[i]) > tstar) ? e[i] : 0.f;
-    gstar = wave_sum(gp);
   }
   // elements above T* are selected; elements equal to T* in ascending block order while the
   // mass before them stays < target (stable descending order, exclusive cumulative mass < p)
-  const float tie_val = __uint_as_float(tstar);
-  int tie_base = 0;
 #pragma unroll
-  for (int i = 0; i < NCH; ++i) {
-    const int idx = i * 64 + lane;
-    bool sel;
-    if (all) {
-      sel = idx < n;
-    } else {
-      const uint32_t key = __float_as_uint(e[i]);
-      const bool tie = key == tstar;
-      const uint64_t tb = __ballot(tie);
-      const int rank = tie_base + __popcll(tb & ((1ull << lane) - 1ull));
-      sel = (key > tstar) || (tie && (gstar + (float)rank * tie_val < target));
-      tie_base += __popcll(tb);
+  for (int k = 0; k < kRowsPerWave; ++k) {
+    if (k >= nrows) break;
+    const int n = n0 + k;
+    const float tie_val = __uint_as_float(tstar[k]);
+    int tie_base = 0;
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      const int idx = i * 64 + lane;
+      bool sel;
+      if (all) {
+        sel = idx < n;
+      } else {
+        const uint32_t key = __float_as_uint(e[k][i]);
+        const bool tie = key == tstar[k];
+        const uint64_t tb = __ballot(tie);
+        const int rank = tie_base + __popcll(tb & ((1ull << lane) - 1ull));
+        sel = (key > tstar[k]) || (tie && (gstar[k] + (float)rank * tie_val < target[k]));
+        tie_base += __popcll(tb);
+      }
+      const uint64_t bal = __ballot(sel);
+      if (lane == 0) bits[k * bits_ld + i] |= bal;
     }
-    const uint64_t bal = __ballot(sel);
-    if (lane == 0) bits_row[i] |= bal;
   }
 }
 
@@ -320,21 +350,21 @@ __global__ __launch_bounds__(256) void select_kernel(
     }
     __syncthreads();
 
-    // ---------------- phase B: one wave per row ----------------
+    // ---------------- phase B: each wave selects its four rows ----------------
     if (!DUMP) {
-#pragma unroll 1
-      for (int rr = 0; rr < 4; ++rr) {
-        const int r = wave * 4 + rr;
-        const int u = u0 + r;
-        if (u >= N) break;                         // uniform per wave
-        const int n = u + 1;
-        const float* row_logits = lds_logits + r * ld;
-        uint64_t* bits_row = &lds_bits[r][0];
-        if (n <= 128) select_row<2>(row_logits, n, top_p, lane, bits_row);
-        else if (n <= 256) select_row<4>(row_logits, n, top_p, lane, bits_row);
-        else if (n <= 512) select_row<8>(row_logits, n, top_p, lane, bits_row);
-        else if (MAXCH <= 16 || n <= 1024) select_row<16>(row_logits, n, top_p, lane, bits_row);
-        else select_row<MAXCH>(row_logits, n, top_p, lane, bits_row);
+      const int r0 = wave * kRowsPerWave;
+      const int nrows = min(kRowsPerWave, N - (u0 + r0));          // uniform per wave, may be <= 0
+      if (nrows > 0) {
+        const int n0 = u0 + r0 + 1;                                // columns of the first row
+        const int nmax = n0 + nrows - 1;
+        const float* lg = lds_logits + r0 * ld;
+        uint64_t* bits = &lds_bits[r0][0];
+        constexpr int bld = kMaxBlocks / 64;
+        if (nmax <= 128) select_rows<2>(lg, ld, n0, nrows, top_p, lane, bits, bld);
+        else if (nmax <= 256) select_rows<4>(lg, ld, n0, nrows, top_p, lane, bits, bld);
+        else if (nmax <= 512) select_rows<8>(lg, ld, n0, nrows, top_p, lane, bits, bld);
+        else if (MAXCH <= 16 || nmax <= 1024) select_rows<16>(lg, ld, n0, nrows, top_p, lane, bits, bld);
+        else select_rows<MAXCH>(lg, ld, n0, nrows, top_p, lane, bits, bld);
       }
       __syncthreads();                             // LDS logits are reused by the next band
     }
