@@ -217,19 +217,28 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
     if (v >= 0 && v <= u) break;
     ++it;
   }
+  // The list is walked one entry ahead of its use: col_idx[it + 1] is requested here and
+  // before the MFMA phases of every block, and read only after the waits that end the block,
+  // so the latency of the index load is never on the critical path of a block.
+  int ahead = it + 1 < end ? col_idx[it + 1] : -1;
   if (it < end) async_load_k_tile<BLK>(krs, v * C::kTileBytes, lds_k, t);
   wait_async_loads();
   __syncthreads();
 
   while (it < end) {
-    // next valid entry (v_next <= u), looked up before the MFMA phases start
+    // next valid entry (v_next <= u): normally the entry fetched one block ago; entries
+    // that must be skipped (negative or beyond the diagonal) take the slow path
     int nx = it + 1;
-    int v_next = -1;
-    while (nx < end) {
-      v_next = __builtin_amdgcn_readfirstlane(col_idx[nx]);
-      if (v_next >= 0 && v_next <= u) break;
+    int v_next = __builtin_amdgcn_readfirstlane(ahead);
+    if (nx < end && !(v_next >= 0 && v_next <= u)) {
       ++nx;
+      while (nx < end) {
+        v_next = __builtin_amdgcn_readfirstlane(col_idx[nx]);
+        if (v_next >= 0 && v_next <= u) break;
+        ++nx;
+      }
     }
+    ahead = nx + 1 < end ? col_idx[nx + 1] : -1;
 
     // ---- V(j) -> LDS, in flight during S^T and the softmax ----
     async_load_vt_tile<BLK>(vrs, v * C::kTileBytes, lds_v, t);
@@ -287,11 +296,10 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
         for (int r = 0; r < 16; ++r) oacc[i][r] *= alpha;
       m_run = m_new;
     }
-    // p = 2^(s*scale - m) as bf16 pairs (the PV operand); the row sum adds the rounded values
-    // (one v_dot2c per pair), so numerator and normaliser see the same P.  Two partial sums
-    // keep the dependent chain short.
+    // p = 2^(s*scale - m) as bf16 pairs (the PV operand); the row sum adds the fp32 values with
+    // plain adds: the dot-product instructions that would add the rounded pairs run on the
+    // matrix pipe and stall behind the other workgroup's MFMAs (measured: 2.2x slower there).
     float psum0 = 0.f, psum1 = 0.f;
-    const bf16x2 ones2 = {(__bf16)1.0f, (__bf16)1.0f};
     bf16x8 pf[KT][2];
 #pragma unroll
     for (int kt = 0; kt < KT; ++kt) {
@@ -305,10 +313,8 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
           const bf16x2 pb = __builtin_convertvector(pp, bf16x2);
           pf[kt][s][j] = pb[0];
           pf[kt][s][j + 1] = pb[1];
-          if ((j & 2) == 0)
-            psum0 = __builtin_amdgcn_fdot2_f32_bf16(pb, ones2, psum0, false);
-          else
-            psum1 = __builtin_amdgcn_fdot2_f32_bf16(pb, ones2, psum1, false);
+          psum0 += p0;
+          psum1 += p1;
         }
       }
     }
