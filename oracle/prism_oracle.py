@@ -28,7 +28,16 @@ Readings taken where the paper is silent (all listed in the design notes):
     softmax; nothing (diagonal, sink) is forced;
   - top-p ties: stable descending order (lower block index first);
   - a band with d_z = 0 is skipped; zero band energy gives zero logits;
-  - p >= 1 selects every causal block.
+  - p >= 1 selects every causal block;
+  - a band may be given as a list of (start, width) slices of the head dimension
+    instead of one contiguous slice: the band vector is their concatenation and
+    d_z the total width.  This covers the axis-wise bands of App. "HunyuanVideo
+    Spectral Configuration" (first d_high^a / last d_low^a dims of each axis subspace)
+    and RoPE stored as (j, j + d/2) pairs;
+  - causal=False (bidirectional attention, the video setting) drops the block-causal
+    restriction in the selection and the token-causal one in the attention;
+  - force_diagonal / force_sink are optional extras (not in the paper): after the
+    union, block u (resp. block 0) of every row is switched on.
 
 Pins (tests/test_oracle_*.py): Dirichlet-kernel closed form for pooled RoPE
 content (Eq. "attenuation"), printed cutoff dimensions, 1/sqrt(B) residual,
@@ -107,6 +116,30 @@ def top_p(probs: np.ndarray, p: float) -> np.ndarray:
     return mask
 
 
+Segments = Sequence[Tuple[int, int]]          # (start, width) slices of the head dim
+
+
+def band_dims(d: int, d_h: int, d_l: int,
+              bands: Optional[Dict[str, Segments]] = None) -> Dict[str, np.ndarray]:
+    """Feature dims of the two bands, in band order.  Default (Sec. 3.4, Fig.
+    "PyTorch-style implementation"): high = first d_h dims, low = last d_l dims.
+    With `bands`, each band is the concatenation of its (start, width) slices."""
+    if bands is None:
+        bands = {"high": [(0, d_h)] if d_h > 0 else [],
+                 "low": [(d - d_l, d_l)] if d_l > 0 else []}
+    out = {}
+    for z in ("high", "low"):
+        idx: List[int] = []
+        for start, width in bands.get(z, []):
+            if width <= 0 or start < 0 or start + width > d:
+                raise ValueError(f"bad segment ({start}, {width}) for head_dim {d}")
+            idx.extend(range(start, start + width))
+        if len(set(idx)) != len(idx):
+            raise ValueError("segments of one band overlap")
+        out[z] = np.asarray(idx, dtype=np.int64)
+    return out
+
+
 @dataclass
 class Selection:
     """Everything the selection produces for one call (all q-heads)."""
@@ -120,11 +153,16 @@ class Selection:
     k_pooled: np.ndarray             # [h_kv, N, d]
     rms_q: Dict[str, np.ndarray]     # "full"/"high"/"low" -> [h]
     rms_k: Dict[str, np.ndarray]     # -> [h_kv]
+    valid: np.ndarray                # [N, N] bool: block pairs that may be selected at all
+    forced: np.ndarray               # [h, N, N] bool: blocks switched on by force_* options
 
 
 def prism_select(Q: np.ndarray, K: np.ndarray, d_h: int, d_l: int, B: int, p: float,
-                 causal: bool = True, calibrate: bool = True) -> Selection:
-    """Block mask of Sec. 3.4.  Q: [h, L, d] fp64, K: [h_kv, L, d] fp64."""
+                 causal: bool = True, calibrate: bool = True,
+                 bands: Optional[Dict[str, Segments]] = None,
+                 force_diagonal: bool = False, force_sink: bool = False) -> Selection:
+    """Block mask of Sec. 3.4.  Q: [h, L, d] fp64, K: [h_kv, L, d] fp64.
+    d_h / d_l are ignored when `bands` is given."""
     h, L, d = Q.shape
     h_kv = K.shape[0]
     if h % h_kv:
@@ -135,8 +173,8 @@ def prism_select(Q: np.ndarray, K: np.ndarray, d_h: int, d_l: int, B: int, p: fl
     # 1. pooling & slicing
     Qb, Kb = pool(Q, B), pool(K, B)
     N = Qb.shape[1]
-    bands = {"high": slice(0, d_h), "low": slice(d - d_l, d)}
-    width = {"high": d_h, "low": d_l}
+    bands = band_dims(d, d_h, d_l, bands)
+    width = {z: len(idx) for z, idx in bands.items()}
 
     # 2. RMS energies
     rms_q = {"full": rms(Qb)}
@@ -149,7 +187,7 @@ def prism_select(Q: np.ndarray, K: np.ndarray, d_h: int, d_l: int, B: int, p: fl
             rms_q[z] = np.zeros(h)
             rms_k[z] = np.zeros(h_kv)
 
-    tri = np.tril(np.ones((N, N), dtype=bool))
+    tri = np.tril(np.ones((N, N), dtype=bool)) if causal else np.ones((N, N), dtype=bool)
     tau: Dict[str, np.ndarray] = {}
     scale: Dict[str, np.ndarray] = {}
     logits: Dict[str, np.ndarray] = {}
@@ -180,8 +218,7 @@ def prism_select(Q: np.ndarray, K: np.ndarray, d_h: int, d_l: int, B: int, p: fl
                 lz[hq] = raw[hq] / s
             else:                                   # zero band energy -> flat logits
                 lz[hq] = 0.0
-        if causal:
-            lz = np.where(tri[None], lz, -np.inf)
+        lz = np.where(tri[None], lz, -np.inf)
         logits[z] = lz
         # 5. selection
         probs[z] = softmax_rows(lz)
@@ -189,12 +226,18 @@ def prism_select(Q: np.ndarray, K: np.ndarray, d_h: int, d_l: int, B: int, p: fl
             mz = np.ones((h, N, N), dtype=bool)
         else:
             mz = top_p(probs[z], p)
-        if causal:
-            mz &= tri[None]
+        mz &= tri[None]
         band_masks[z] = mz
 
     mask = band_masks["high"] | band_masks["low"]
-    return Selection(mask, band_masks, logits, probs, tau, scale, Qb, Kb, rms_q, rms_k)
+    forced = np.zeros((h, N, N), dtype=bool)
+    if force_diagonal:
+        forced[:, np.arange(N), np.arange(N)] = True
+    if force_sink:
+        forced[:, :, 0] = True
+    mask = mask | forced
+    return Selection(mask, band_masks, logits, probs, tau, scale, Qb, Kb, rms_q, rms_k,
+                     tri, forced)
 
 
 def mask_to_csr(mask: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
@@ -214,15 +257,14 @@ class Tolerance:
     """Per-block verdict classes for comparing another implementation's mask."""
     must: np.ndarray        # [h, N, N] bool — has to be selected
     must_not: np.ndarray    # [h, N, N] bool — has to be unselected
+    valid: np.ndarray       # [N, N] bool — block pairs open to selection
     # everything else is "don't care"
 
     @property
     def dont_care_fraction(self) -> float:
-        h, N, _ = self.must.shape
-        causal = h * N * (N + 1) // 2
-        tri = np.tril(np.ones((N, N), dtype=bool))[None]
-        dc = (~self.must) & (~self.must_not) & tri
-        return float(dc.sum()) / float(causal)
+        h = self.must.shape[0]
+        dc = (~self.must) & (~self.must_not) & self.valid[None]
+        return float(dc.sum()) / float(h * self.valid.sum())
 
 
 def selection_tolerance(sel: Selection, p: float, logit_margin: float = 1e-3,
@@ -240,7 +282,7 @@ def selection_tolerance(sel: Selection, p: float, logit_margin: float = 1e-3,
     must = union over bands of (selected minus don't-care); must_not = complement of the
     union over bands of (selected or don't-care)."""
     h, N, _ = sel.mask.shape
-    tri = np.tril(np.ones((N, N), dtype=bool))[None]
+    tri = sel.valid[None]
     keep = np.zeros((h, N, N), dtype=bool)       # union_z (M_z \ D_z)
     cover = np.zeros((h, N, N), dtype=bool)      # union_z (M_z | D_z)
     for z in ("high", "low"):
@@ -261,17 +303,20 @@ def selection_tolerance(sel: Selection, p: float, logit_margin: float = 1e-3,
         dz = (swap_out | swap_in | shell) & tri
         keep |= mz & ~dz
         cover |= (mz | dz)
-    return Tolerance(must=keep, must_not=(~cover) | (~tri))
+    keep |= sel.forced
+    cover |= sel.forced
+    return Tolerance(must=keep, must_not=(~cover) | (~tri), valid=sel.valid)
 
 
 # --------------------------------------------------------------------------- #
 # Part 2 — attention by its plain definition
 # --------------------------------------------------------------------------- #
 def block_sparse_attention_row(Qh: np.ndarray, Kh: np.ndarray, Vh: np.ndarray,
-                               u: int, blocks: Sequence[int], B: int
+                               u: int, blocks: Sequence[int], B: int, causal: bool = True
                                ) -> Tuple[np.ndarray, np.ndarray]:
     """One q-block of one head.  For token i in block u the visible set is
-    J(i) = { j <= i : block(j) in `blocks` }; o_i = sum_J softmax_J(q_i.k_j/sqrt(d)) v_j.
+    J(i) = { j <= i : block(j) in `blocks` } (without `j <= i` when causal is False);
+    o_i = sum_J softmax_J(q_i.k_j/sqrt(d)) v_j.
     Qh/Kh/Vh: [L, d] fp64.  Returns (O [rows, d], lse [rows]); a token with an empty
     visible set gets a zero output row and lse = -inf."""
     L, d = Qh.shape
@@ -281,7 +326,8 @@ def block_sparse_attention_row(Qh: np.ndarray, Kh: np.ndarray, Vh: np.ndarray,
         return np.zeros((r1 - r0, d)), np.full(r1 - r0, -np.inf)
     cols = np.concatenate([np.arange(v * B, min(L, (v + 1) * B)) for v in blocks])
     s = (Qh[r0:r1] @ Kh[cols].T) / np.sqrt(d)
-    s = np.where(cols[None, :] <= rows[:, None], s, -np.inf)
+    if causal:
+        s = np.where(cols[None, :] <= rows[:, None], s, -np.inf)
     m = s.max(axis=1, keepdims=True)
     out = np.zeros((r1 - r0, d))
     lse = np.full(r1 - r0, -np.inf)
@@ -294,10 +340,12 @@ def block_sparse_attention_row(Qh: np.ndarray, Kh: np.ndarray, Vh: np.ndarray,
 
 
 def block_sparse_attention(Q: np.ndarray, K: np.ndarray, V: np.ndarray, mask: np.ndarray,
-                           B: int, rows: Optional[Sequence[Tuple[int, int]]] = None
+                           B: int, rows: Optional[Sequence[Tuple[int, int]]] = None,
+                           causal: bool = True
                            ) -> Dict[Tuple[int, int], Tuple[np.ndarray, np.ndarray]]:
-    """Block-masked causal attention for the listed (head, q-block) rows (all rows
-    when `rows` is None).  Q: [h, L, d]; K, V: [h_kv, L, d]; mask: [h, N, N] bool."""
+    """Block-masked attention (causal unless causal=False) for the listed (head, q-block)
+    rows (all rows when `rows` is None).  Q: [h, L, d]; K, V: [h_kv, L, d];
+    mask: [h, N, N] bool."""
     h, L, d = Q.shape
     g = h // K.shape[0]
     N = mask.shape[1]
@@ -305,8 +353,9 @@ def block_sparse_attention(Q: np.ndarray, K: np.ndarray, V: np.ndarray, mask: np
         rows = [(hq, u) for hq in range(h) for u in range(N)]
     out = {}
     for hq, u in rows:
-        blocks = np.nonzero(mask[hq, u, :u + 1])[0]
-        out[(hq, u)] = block_sparse_attention_row(Q[hq], K[hq // g], V[hq // g], u, blocks, B)
+        blocks = np.nonzero(mask[hq, u, :u + 1] if causal else mask[hq, u])[0]
+        out[(hq, u)] = block_sparse_attention_row(Q[hq], K[hq // g], V[hq // g], u, blocks, B,
+                                                  causal)
     return out
 
 
@@ -331,4 +380,22 @@ def dense_causal_attention(Q: np.ndarray, K: np.ndarray, V: np.ndarray,
             den = e.sum(axis=1, keepdims=True)
             O[hq, r0:r1] = (e / den) @ Vh[:r1]
             lse[hq, r0:r1] = m[:, 0] + np.log(den[:, 0])
+    return O, lse
+
+
+def dense_full_attention(Q: np.ndarray, K: np.ndarray, V: np.ndarray
+                         ) -> Tuple[np.ndarray, np.ndarray]:
+    """softmax(Q K^T / sqrt(d)) V with every key visible to every query
+    (bidirectional attention).  Returns (O [h, L, d], lse [h, L])."""
+    h, L, d = Q.shape
+    g = h // K.shape[0]
+    O = np.empty((h, L, d))
+    lse = np.empty((h, L))
+    for hq in range(h):
+        s = (Q[hq] @ K[hq // g].T) / np.sqrt(d)
+        m = s.max(axis=1, keepdims=True)
+        e = np.exp(s - m)
+        den = e.sum(axis=1, keepdims=True)
+        O[hq] = (e / den) @ V[hq // g]
+        lse[hq] = m[:, 0] + np.log(den[:, 0])
     return O, lse

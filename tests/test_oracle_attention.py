@@ -11,7 +11,7 @@ import torch.nn.functional as F
 from oracle import prism_oracle as orc
 
 
-def _naive(Q, K, V, mask, B):
+def _naive(Q, K, V, mask, B, causal=True):
     """Token-by-token definition with Python scalars: softmax over visible keys."""
     h, L, d = Q.shape
     g = h // K.shape[0]
@@ -20,7 +20,7 @@ def _naive(Q, K, V, mask, B):
     for hq in range(h):
         kv = hq // g
         for i in range(L):
-            vis = [j for j in range(i + 1) if mask[hq, i // B, j // B]]
+            vis = [j for j in range(i + 1 if causal else L) if mask[hq, i // B, j // B]]
             if not vis:
                 continue
             s = [sum(Q[hq, i, c] * K[kv, j, c] for c in range(d)) / math.sqrt(d) for j in vis]
@@ -46,6 +46,32 @@ def test_block_sparse_matches_naive_loops(seed, h, h_kv, L, B, d):
         r0, r1 = u * B, min(L, (u + 1) * B)
         np.testing.assert_allclose(o, ref_o[hq, r0:r1], atol=1e-13)
         np.testing.assert_allclose(l, ref_l[hq, r0:r1], atol=1e-13)
+
+
+def test_bidirectional_block_sparse_matches_naive_loops_and_sdpa():
+    """causal=False: every token of a listed block is visible; the all-ones mask is plain
+    softmax attention (checked against torch SDPA in fp64)."""
+    rng = np.random.default_rng(7)
+    h, h_kv, L, B, d = 4, 2, 24, 4, 8
+    Q = rng.standard_normal((h, L, d)); K = rng.standard_normal((h_kv, L, d)); V = rng.standard_normal((h_kv, L, d))
+    N = L // B
+    mask = rng.random((h, N, N)) < 0.5
+    mask[:, 1, :] = False
+    ref_o, ref_l = _naive(Q, K, V, mask, B, causal=False)
+    got = orc.block_sparse_attention(Q, K, V, mask, B, causal=False)
+    for (hq, u), (o, l) in got.items():
+        np.testing.assert_allclose(o, ref_o[hq, u * B:(u + 1) * B], atol=1e-13)
+        np.testing.assert_allclose(l, ref_l[hq, u * B:(u + 1) * B], atol=1e-13)
+    assert (mask & ~np.tril(np.ones((N, N), bool))).any()          # blocks above the diagonal were used
+    full_o, full_l = orc.dense_full_attention(Q, K, V)
+    ones = np.ones((h, N, N), bool)
+    for (hq, u), (o, l) in orc.block_sparse_attention(Q, K, V, ones, B, causal=False).items():
+        np.testing.assert_allclose(o, full_o[hq, u * B:(u + 1) * B], atol=1e-13)
+        np.testing.assert_allclose(l, full_l[hq, u * B:(u + 1) * B], atol=1e-13)
+    tq, tk, tv = (torch.from_numpy(x) for x in (Q, K, V))
+    ref = F.scaled_dot_product_attention(tq[None], tk.repeat_interleave(h // h_kv, 0)[None],
+                                         tv.repeat_interleave(h // h_kv, 0)[None], is_causal=False)[0]
+    np.testing.assert_allclose(full_o, ref.numpy(), atol=1e-12)
 
 
 def test_all_ones_mask_equals_dense():

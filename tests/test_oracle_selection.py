@@ -120,8 +120,9 @@ def test_pool_ragged_tail_divides_by_actual_count():
 # --------------------------------------------------------------------------- #
 # scalar brute force of the whole selection on tiny inputs
 # --------------------------------------------------------------------------- #
-def _scalar_prism(Q, K, d_h, d_l, B, p, calibrate=True):
-    """Index-by-index restatement of Sec. 3.4 with Python scalars (tiny sizes only)."""
+def _scalar_prism(Q, K, d_h, d_l, B, p, calibrate=True, causal=True, dims=None):
+    """Index-by-index restatement of Sec. 3.4 with Python scalars (tiny sizes only).
+    `dims` optionally gives the feature dims of each band explicitly."""
     h, L, d = len(Q), len(Q[0]), len(Q[0][0])
     h_kv = len(K)
     g = h // h_kv
@@ -134,6 +135,8 @@ def _scalar_prism(Q, K, d_h, d_l, B, p, calibrate=True):
     Qb, Kb = pooled(Q), pooled(K)
 
     def band(z):
+        if dims is not None:
+            return list(dims[z])
         return list(range(0, d_h)) if z == "high" else list(range(d - d_l, d))
 
     def rms_of(Xb_head, dims):
@@ -146,28 +149,29 @@ def _scalar_prism(Q, K, d_h, d_l, B, p, calibrate=True):
     masks = {}
     logits = {}
     for z in ("high", "low"):
-        dims = band(z)
-        dz = len(dims)
+        zdims = band(z)
+        dz = len(zdims)
         M = [[[False] * N for _ in range(N)] for _ in range(h)]
         Lg = [[[-math.inf] * N for _ in range(N)] for _ in range(h)]
         for hq in range(h):
             kv = hq // g
             if calibrate:
-                tau = math.sqrt(dz / d) * (rms_of(Qb[hq], dims) / rms_of(Qb[hq], range(d))) \
-                    * (rms_of(Kb[kv], dims) / rms_of(Kb[kv], range(d)))
+                tau = math.sqrt(dz / d) * (rms_of(Qb[hq], zdims) / rms_of(Qb[hq], range(d))) \
+                    * (rms_of(Kb[kv], zdims) / rms_of(Kb[kv], range(d)))
             else:
                 tau = 1.0
             for u in range(N):
                 row = []
-                for v in range(u + 1):
-                    dot = sum(Qb[hq][u][c] * Kb[kv][v][c] for c in dims)
+                nvis = u + 1 if causal else N
+                for v in range(nvis):
+                    dot = sum(Qb[hq][u][c] * Kb[kv][v][c] for c in zdims)
                     row.append(dot / (tau * math.sqrt(dz)))
                     Lg[hq][u][v] = row[-1]
                 mx = max(row)
                 ex = [math.exp(x - mx) for x in row]
                 s = sum(ex)
                 pr = [e / s for e in ex]
-                order = sorted(range(u + 1), key=lambda i: (-pr[i], i))
+                order = sorted(range(nvis), key=lambda i: (-pr[i], i))
                 before = 0.0
                 for i in order:
                     if before < p:
@@ -199,6 +203,70 @@ def test_selection_matches_scalar_brute_force(seed, h, h_kv, d, d_h, d_l, B, N, 
         np.testing.assert_allclose(sel.logits[z][fin], lg[fin], rtol=1e-12, atol=1e-12)
     union = np.array(masks["high"]) | np.array(masks["low"])
     np.testing.assert_array_equal(sel.mask, union)
+
+
+@pytest.mark.parametrize("seed,causal", [(10, True), (11, False), (12, False)])
+def test_segment_bands_and_bidirectional_match_scalar_brute_force(seed, causal):
+    """Bands given as lists of slices (axis-wise bands of App. "HunyuanVideo Spectral
+    Configuration": first d_high^a / last d_low^a dims of each axis subspace) and the
+    bidirectional variant, against the scalar restatement."""
+    rng = np.random.default_rng(seed)
+    h, h_kv, d, B, N, p = 4, 2, 16, 2, 6, 0.8
+    # three axis subspaces [4, 6, 6]: high = first 2 / 3 / 3 dims, low = last 4 / 4 / 4
+    bands = {"high": [(0, 2), (4, 3), (10, 3)], "low": [(0, 4), (6, 4), (12, 4)]}
+    dims = {z: [c for s0, w in segs for c in range(s0, s0 + w)] for z, segs in bands.items()}
+    Q = rng.standard_normal((h, B * N, d)) * 3.0
+    K = rng.standard_normal((h_kv, B * N, d)) * 3.0
+    sel = orc.prism_select(Q, K, 0, 0, B, p, causal=causal, bands=bands)
+    masks, logits = _scalar_prism(Q.tolist(), K.tolist(), 0, 0, B, p, causal=causal, dims=dims)
+    for z in ("high", "low"):
+        np.testing.assert_array_equal(sel.band_masks[z], np.array(masks[z]))
+        lg = np.array(logits[z])
+        fin = np.isfinite(lg)
+        np.testing.assert_array_equal(np.isfinite(sel.logits[z]), fin)
+        np.testing.assert_allclose(sel.logits[z][fin], lg[fin], rtol=1e-12, atol=1e-12)
+    if not causal:
+        assert np.isfinite(sel.logits["high"]).all() and sel.mask[:, 0, :].sum() >= h
+
+
+def test_single_slice_descriptor_is_the_default_and_dims_may_be_permuted():
+    """One slice per band == the d_h / d_l form; permuting the feature dims of Q and K
+    together with the band descriptors leaves every logit unchanged."""
+    rng = np.random.default_rng(21)
+    h, h_kv, d, B, N, p = 2, 1, 16, 4, 8, 0.9
+    Q = rng.standard_normal((h, B * N, d)); K = rng.standard_normal((h_kv, B * N, d))
+    a = orc.prism_select(Q, K, 8, 12, B, p)
+    b = orc.prism_select(Q, K, 0, 0, B, p, bands={"high": [(0, 8)], "low": [(4, 12)]})
+    np.testing.assert_array_equal(a.mask, b.mask)
+    np.testing.assert_array_equal(a.logits["low"], b.logits["low"])
+    # half-split storage: pair j lives in dims (j, j + d/2) instead of (2j, 2j+1)
+    to_half = np.concatenate([np.arange(0, d, 2), np.arange(1, d, 2)])   # new dim i holds old dim to_half[i]
+    Qp, Kp = Q[:, :, to_half], K[:, :, to_half]
+    half = {"high": [(0, 4), (8, 4)], "low": [(2, 6), (10, 6)]}          # pairs 0..3 and pairs 2..7
+    c = orc.prism_select(Qp, Kp, 0, 0, B, p, bands=half)
+    for z in ("high", "low"):
+        fin = np.isfinite(a.logits[z])
+        np.testing.assert_allclose(c.logits[z][fin], a.logits[z][fin], rtol=1e-12, atol=1e-12)
+    np.testing.assert_array_equal(c.mask, a.mask)
+    with pytest.raises(ValueError):
+        orc.band_dims(d, 0, 0, {"high": [(0, 8), (4, 8)], "low": []})     # overlapping slices
+    with pytest.raises(ValueError):
+        orc.band_dims(d, 0, 0, {"high": [(12, 8)], "low": []})            # runs past the head dim
+
+
+def test_forced_blocks_are_added_after_the_union():
+    rng = np.random.default_rng(22)
+    h, h_kv, d, B, N, p = 2, 1, 8, 2, 9, 0.3
+    Q = rng.standard_normal((h, B * N, d)) * 4; K = rng.standard_normal((h_kv, B * N, d)) * 4
+    base = orc.prism_select(Q, K, 4, 4, B, p)
+    forced = orc.prism_select(Q, K, 4, 4, B, p, force_diagonal=True, force_sink=True)
+    eye = np.eye(N, dtype=bool)[None]
+    sink = np.zeros((1, N, N), bool); sink[:, :, 0] = True
+    np.testing.assert_array_equal(forced.mask, base.mask | eye | sink)
+    assert not base.forced.any() and (forced.mask & ~base.mask).any()
+    tol = orc.selection_tolerance(forced, p)
+    assert (tol.must & (eye | sink)).sum() == (eye | sink).sum() * h      # forced blocks are never "don't care"
+    assert not (tol.must & tol.must_not).any()
 
 
 def test_band_slices_are_first_dh_and_last_dl():
