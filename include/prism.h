@@ -45,6 +45,12 @@ typedef enum prism_status {
 
 /* flags */
 #define PRISM_FLAG_NO_CALIBRATION 1u   /* tau_high = tau_low = 1 (ablation of Sec. 4.4) */
+#define PRISM_FLAG_BIDIRECTIONAL  2u   /* no causal restriction (the video-generation setting of
+                                          Sec. 4.2 "Main Results"): every row may select any of
+                                          the N key blocks and attends to every token of a
+                                          listed block */
+#define PRISM_FLAG_FORCE_DIAGONAL 4u   /* extra, not in the paper: block u of row u is always selected */
+#define PRISM_FLAG_FORCE_SINK     8u   /* extra, not in the paper: block 0 is always selected */
 
 /* Problem description shared by all calls (plain data, host memory). */
 typedef struct prism_params {
@@ -53,11 +59,27 @@ typedef struct prism_params {
   int32_t seq_len;      /* L, multiple of `block`                                   */
   int32_t head_dim;     /* d, must be 128                                           */
   int32_t block;        /* B, 64 or 128; N = L / B blocks, N <= 2048                */
-  int32_t d_high;       /* width of the high-frequency band, multiple of 32, 0..d   */
-  int32_t d_low;        /* width of the low-frequency band,  multiple of 32, 0..d   */
-  float   top_p;        /* p in (0,1]; p >= 1 selects every causal block            */
+  int32_t d_high;       /* width of the high-frequency band, 0..d (0 = band off)    */
+  int32_t d_low;        /* width of the low-frequency band,  0..d (0 = band off)    */
+  float   top_p;        /* p in (0,1]; p >= 1 selects every admissible block        */
   uint32_t flags;       /* PRISM_FLAG_*                                              */
 } prism_params;
+
+/* A band as up to PRISM_MAX_SEGMENTS slices [start, start+width) of the head dim; the band
+ * vector is their concatenation and d_z their total width.  One slice per band gives the
+ * contiguous bands of Sec. 3.4; several give the axis-wise bands of App. "HunyuanVideo
+ * Spectral Configuration" (first d_high^a / last d_low^a dims of each axis subspace), or the
+ * bands of RoPE stored as pairs (j, j + d/2): high = [0, d_high/2) + [d/2, d/2 + d_high/2).
+ * Slices of one band must not overlap; the two bands may.  n_segments = 0 switches a band off. */
+#define PRISM_MAX_SEGMENTS 8
+typedef struct prism_band {
+  int32_t n_segments;
+  int32_t start[PRISM_MAX_SEGMENTS];
+  int32_t width[PRISM_MAX_SEGMENTS];
+} prism_band;
+typedef struct prism_bands {
+  prism_band high, low;
+} prism_bands;
 
 /* Library version as major*10000 + minor*100 + patch. */
 int prism_version(void);
@@ -72,8 +94,9 @@ const char* prism_status_string(int status);
  * Computes, per q-head:  mean-pooled Qbar, Kbar (Eq. "mean-pooling");  RMS energies of
  * the full / high / low slices;  tau_z = sqrt(d_z/d) (RMS(Qbar_z)/RMS(Qbar))
  * (RMS(Kbar_z)/RMS(Kbar));  logits_z = Qbar_z Kbar_z^T / (tau_z sqrt(d_z)) for key
- * blocks v <= u (block-causal);  row softmax;  top-p (smallest set of highest-probability
- * blocks whose mass reaches p; equal probabilities are taken in ascending block order);
+ * blocks v <= u (block-causal; every v with PRISM_FLAG_BIDIRECTIONAL);  row softmax;
+ * top-p (smallest set of highest-probability blocks whose mass reaches p; equal
+ * probabilities are taken in ascending block order);
  * M = M_high | M_low;  and the compacted per-(head, q-block) index lists of M.
  * A band with d_z == 0 is skipped.  Zero band energy gives flat logits.
  *
@@ -82,7 +105,7 @@ const char* prism_status_string(int status);
  *               row (head, u) is M[u, v].  Fully overwritten.
  *   row_ptr   : [n_q_heads*N + 1] int32, CSR row offsets, row index = head*N + u.
  *   col_idx   : [col_capacity] int32, selected key blocks of each row in ascending order.
- *               n_q_heads*N*(N+1)/2 entries always suffice.
+ *               n_q_heads*N*(N+1)/2 entries always suffice (n_q_heads*N*N when bidirectional).
  *   info      : [4] int32: info[0] = number of selected (head,u,v) triples,
  *               info[1] = 1 if that number exceeds col_capacity (col_idx then holds only
  *               the entries that fit and must not be used), info[2..3] reserved (0).
@@ -97,18 +120,36 @@ int prism_estimate(const prism_params* params,
                    int32_t* info,
                    void* workspace, size_t workspace_bytes, void* stream);
 
+/* prism_estimate with the bands given as slice lists (host memory); d_high and d_low of
+ * `params` are ignored.  prism_estimate(params, ...) is this call with
+ * high = {[0, d_high)}, low = {[d - d_low, d)}. */
+int prism_estimate_bands(const prism_params* params, const prism_bands* bands /* host */,
+                         const void* q_bf16, const void* k_bf16,
+                         uint64_t* mask_bits, int32_t* row_ptr,
+                         int32_t* col_idx, int64_t col_capacity,
+                         int32_t* info,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
 /* Same computation as prism_estimate up to the block scores, for inspection at small
  * sizes: writes the pooled vectors, the two scales sqrt(d_z)*tau_z and the dual-band
  * logits (Sec. 3.4, step "Dual-Band Scoring").  Any output pointer may be NULL.
  *   pooled_q : [n_q_heads , N, d] float      pooled_k : [n_kv_heads, N, d] float
  *   scales   : [n_q_heads, 2] float (high, low); 0 when the band is disabled
  *   logits_high, logits_low : [n_q_heads, N, N] float; entries with v > u are not written
+ *                             (all N*N are written with PRISM_FLAG_BIDIRECTIONAL)
  * Uses the same workspace size as prism_estimate. */
 int prism_block_scores(const prism_params* params,
                        const void* q_bf16, const void* k_bf16,
                        float* pooled_q, float* pooled_k, float* scales,
                        float* logits_high, float* logits_low,
                        void* workspace, size_t workspace_bytes, void* stream);
+
+/* prism_block_scores with the bands given as slice lists (see prism_estimate_bands). */
+int prism_block_scores_bands(const prism_params* params, const prism_bands* bands /* host */,
+                             const void* q_bf16, const void* k_bf16,
+                             float* pooled_q, float* pooled_k, float* scales,
+                             float* logits_high, float* logits_low,
+                             void* workspace, size_t workspace_bytes, void* stream);
 
 /* Compaction of a caller-supplied block mask (same layouts and `info` semantics as
  * prism_estimate; the mask -> index-list step that block-sparse kernels need,
@@ -123,6 +164,11 @@ int prism_mask_to_csr(const prism_params* params, const uint64_t* mask_bits,
 int prism_causal_csr(const prism_params* params, int32_t* row_ptr, int32_t* col_idx,
                      int64_t col_capacity, void* stream);
 
+/* Index lists of the all-ones mask under params->flags: as prism_causal_csr, or every row =
+ * {0..N-1} with PRISM_FLAG_BIDIRECTIONAL (col_capacity >= n_q_heads*N*N). */
+int prism_dense_csr(const prism_params* params, int32_t* row_ptr, int32_t* col_idx,
+                    int64_t col_capacity, void* stream);
+
 /* ------------------------------------------------------------------------------------
  * Block-sparse causal attention — Sec. 2 "Block-Sparse Attention": the dense
  * computation and online accumulation restricted to the selected block pairs.
@@ -131,6 +177,8 @@ int prism_causal_csr(const prism_params* params, int32_t* row_ptr, int32_t* col_
  *    J(i) = { j <= i : block j / B is listed in row (hq,u) },
  *    o_i  = sum_{j in J} softmax_J( q_i . k_j / sqrt(d) )_j  v_j       (bf16 in, fp32 accumulate)
  * Listed blocks v > u are ignored; a row with an empty list gives o = 0, lse = -inf.
+ * With PRISM_FLAG_BIDIRECTIONAL the condition j <= i is dropped: J(i) is every token of every
+ * listed block v < N.
  *
  *   row_ptr, col_idx : CSR as produced above; col_count = number of valid entries in
  *                      col_idx (row_ptr values are clamped to it).
@@ -138,7 +186,7 @@ int prism_causal_csr(const prism_params* params, int32_t* row_ptr, int32_t* col_
  *   lse              : [n_q_heads, L] float natural-log sum-exp of the scaled scores, or NULL.
  * workspace: prism_sparse_attn_workspace_bytes() bytes (a transposed copy of V plus the
  *            kernel's work queue: rows sorted by list length).
- * top_p, d_high, d_low and flags of `params` are ignored here.
+ * top_p, d_high, d_low and the other flags of `params` are ignored here.
  * ---------------------------------------------------------------------------------- */
 int prism_sparse_attn_workspace_bytes(const prism_params* params, size_t* bytes /* host, out */);
 

@@ -17,6 +17,10 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libprism.s
 _lib: Optional[ctypes.CDLL] = None
 
 PRISM_FLAG_NO_CALIBRATION = 1
+PRISM_FLAG_BIDIRECTIONAL = 2
+PRISM_FLAG_FORCE_DIAGONAL = 4
+PRISM_FLAG_FORCE_SINK = 8
+PRISM_MAX_SEGMENTS = 8
 
 
 class PrismError(RuntimeError):
@@ -41,8 +45,18 @@ class prism_params(ctypes.Structure):
         return (self.n_blocks + 63) // 64
 
 
+class prism_band(ctypes.Structure):
+    _fields_ = [("n_segments", ctypes.c_int32), ("start", ctypes.c_int32 * PRISM_MAX_SEGMENTS),
+                ("width", ctypes.c_int32 * PRISM_MAX_SEGMENTS)]
+
+
+class prism_bands(ctypes.Structure):
+    _fields_ = [("high", prism_band), ("low", prism_band)]
+
+
 EXPORTS = ("prism_version", "prism_status_string", "prism_estimate_workspace_bytes",
-           "prism_estimate", "prism_block_scores", "prism_mask_to_csr", "prism_causal_csr",
+           "prism_estimate", "prism_estimate_bands", "prism_block_scores",
+           "prism_block_scores_bands", "prism_mask_to_csr", "prism_causal_csr", "prism_dense_csr",
            "prism_sparse_attn_workspace_bytes", "prism_sparse_attn", "prism_v_image",
            "prism_sparse_attn_pre")
 
@@ -57,13 +71,17 @@ def _load() -> ctypes.CDLL:
             "or __graft_entry__.build())")
     lib = ctypes.CDLL(_LIB_PATH)
     P, vp, i64, sz = ctypes.POINTER(prism_params), ctypes.c_void_p, ctypes.c_int64, ctypes.c_size_t
+    PB = ctypes.POINTER(prism_bands)
     lib.prism_version.restype = ctypes.c_int
     lib.prism_version.argtypes = []
     lib.prism_status_string.restype = ctypes.c_char_p
     lib.prism_status_string.argtypes = [ctypes.c_int]
     lib.prism_estimate_workspace_bytes.argtypes = [P, ctypes.POINTER(sz)]
     lib.prism_estimate.argtypes = [P, vp, vp, vp, vp, vp, i64, vp, vp, sz, vp]
+    lib.prism_estimate_bands.argtypes = [P, PB, vp, vp, vp, vp, vp, i64, vp, vp, sz, vp]
     lib.prism_block_scores.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.prism_block_scores_bands.argtypes = [P, PB, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.prism_dense_csr.argtypes = [P, vp, vp, i64, vp]
     lib.prism_mask_to_csr.argtypes = [P, vp, vp, vp, i64, vp, vp]
     lib.prism_causal_csr.argtypes = [P, vp, vp, i64, vp]
     lib.prism_sparse_attn_workspace_bytes.argtypes = [P, ctypes.POINTER(sz)]
@@ -83,6 +101,19 @@ def library_path() -> str:
 def make_params(n_q_heads: int, n_kv_heads: int, seq_len: int, block: int, d_high: int = 64,
                 d_low: int = 96, top_p: float = 0.95, flags: int = 0, head_dim: int = 128) -> prism_params:
     return prism_params(n_q_heads, n_kv_heads, seq_len, head_dim, block, d_high, d_low, top_p, flags)
+
+
+def make_bands(high, low) -> prism_bands:
+    """Band descriptors from two lists of (start, width) slices of the head dim."""
+    b = prism_bands()
+    for band, segs in ((b.high, high), (b.low, low)):
+        segs = list(segs)
+        if len(segs) > PRISM_MAX_SEGMENTS:
+            raise ValueError(f"at most {PRISM_MAX_SEGMENTS} slices per band")
+        band.n_segments = len(segs)
+        for i, (start, width) in enumerate(segs):
+            band.start[i], band.width[i] = start, width
+    return b
 
 
 def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
@@ -132,7 +163,7 @@ def alloc_workspace(nbytes: int, device="cuda") -> torch.Tensor:
 def alloc_estimate_outputs(params: prism_params, col_capacity: Optional[int] = None, device="cuda"):
     N, W, h = params.n_blocks, params.words_per_row, params.n_q_heads
     if col_capacity is None:
-        col_capacity = h * N * (N + 1) // 2
+        col_capacity = h * N * N if params.flags & PRISM_FLAG_BIDIRECTIONAL else h * N * (N + 1) // 2
     mask_bits = torch.empty((h, N, W), dtype=torch.int64, device=device)
     row_ptr = torch.empty(h * N + 1, dtype=torch.int32, device=device)
     col_idx = torch.empty(max(col_capacity, 1), dtype=torch.int32, device=device)
@@ -148,6 +179,15 @@ def prism_estimate(params: prism_params, q: torch.Tensor, k: torch.Tensor, mask_
                                   _ptr(workspace), workspace.numel(), _stream()), "prism_estimate")
 
 
+def prism_estimate_bands(params: prism_params, bands: prism_bands, q: torch.Tensor, k: torch.Tensor,
+                         mask_bits: torch.Tensor, row_ptr: torch.Tensor, col_idx: torch.Tensor,
+                         col_capacity: int, info: torch.Tensor, workspace: torch.Tensor) -> None:
+    _check(_load().prism_estimate_bands(ctypes.byref(params), ctypes.byref(bands), _ptr(q), _ptr(k),
+                                        _ptr(mask_bits), _ptr(row_ptr), _ptr(col_idx), col_capacity,
+                                        _ptr(info), _ptr(workspace), workspace.numel(), _stream()),
+           "prism_estimate_bands")
+
+
 def prism_block_scores(params: prism_params, q: torch.Tensor, k: torch.Tensor,
                        pooled_q: Optional[torch.Tensor], pooled_k: Optional[torch.Tensor],
                        scales: Optional[torch.Tensor], logits_high: Optional[torch.Tensor],
@@ -156,6 +196,17 @@ def prism_block_scores(params: prism_params, q: torch.Tensor, k: torch.Tensor,
                                       _ptr(pooled_k), _ptr(scales), _ptr(logits_high),
                                       _ptr(logits_low), _ptr(workspace), workspace.numel(),
                                       _stream()), "prism_block_scores")
+
+
+def prism_block_scores_bands(params: prism_params, bands: prism_bands, q: torch.Tensor,
+                             k: torch.Tensor, pooled_q: Optional[torch.Tensor],
+                             pooled_k: Optional[torch.Tensor], scales: Optional[torch.Tensor],
+                             logits_high: Optional[torch.Tensor], logits_low: Optional[torch.Tensor],
+                             workspace: torch.Tensor) -> None:
+    _check(_load().prism_block_scores_bands(ctypes.byref(params), ctypes.byref(bands), _ptr(q),
+                                            _ptr(k), _ptr(pooled_q), _ptr(pooled_k), _ptr(scales),
+                                            _ptr(logits_high), _ptr(logits_low), _ptr(workspace),
+                                            workspace.numel(), _stream()), "prism_block_scores_bands")
 
 
 def prism_mask_to_csr(params: prism_params, mask_bits: torch.Tensor, row_ptr: torch.Tensor,
@@ -169,6 +220,12 @@ def prism_causal_csr(params: prism_params, row_ptr: torch.Tensor, col_idx: torch
                      col_capacity: int) -> None:
     _check(_load().prism_causal_csr(ctypes.byref(params), _ptr(row_ptr), _ptr(col_idx),
                                     col_capacity, _stream()), "prism_causal_csr")
+
+
+def prism_dense_csr(params: prism_params, row_ptr: torch.Tensor, col_idx: torch.Tensor,
+                    col_capacity: int) -> None:
+    _check(_load().prism_dense_csr(ctypes.byref(params), _ptr(row_ptr), _ptr(col_idx),
+                                   col_capacity, _stream()), "prism_dense_csr")
 
 
 def prism_sparse_attn(params: prism_params, q: torch.Tensor, k: torch.Tensor, v: torch.Tensor,

@@ -134,7 +134,8 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ vt,
     const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx, int64_t col_count,
     const int32_t* __restrict__ order, int32_t* __restrict__ counter,
-    uint16_t* __restrict__ out, float* __restrict__ lse, int h, int h_kv, int L, int N) {
+    uint16_t* __restrict__ out, float* __restrict__ lse, int h, int h_kv, int L, int N,
+    int causal) {
   using C = AttnCfg<BLK>;
   constexpr int KT = BLK / 32;                       // 32-key tiles per kv block
   __shared__ __attribute__((aligned(16))) char lds_k[C::kTileBytes];
@@ -209,12 +210,14 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
   float m_run = -INFINITY;          // running max, in units of log2: s * sm_scale
   float l_run = 0.f;                // this lane's share of the running sum
 
-  // find the first valid entry (v <= u) and start its K tile
+  // find the first valid entry (v <= vmax) and start its K tile; vmax = u for causal
+  // attention (blocks beyond the diagonal are skipped), N - 1 otherwise
+  const int vmax = causal ? u : N - 1;
   int it = beg;
   int v = -1;
   while (it < end) {
     v = __builtin_amdgcn_readfirstlane(col_idx[it]);
-    if (v >= 0 && v <= u) break;
+    if (v >= 0 && v <= vmax) break;
     ++it;
   }
   // The list is walked one entry ahead of its use: col_idx[it + 1] is requested here and
@@ -226,15 +229,15 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
   __syncthreads();
 
   while (it < end) {
-    // next valid entry (v_next <= u): normally the entry fetched one block ago; entries
-    // that must be skipped (negative or beyond the diagonal) take the slow path
+    // next valid entry (v_next <= vmax): normally the entry fetched one block ago; entries
+    // that must be skipped (negative or beyond vmax) take the slow path
     int nx = it + 1;
     int v_next = __builtin_amdgcn_readfirstlane(ahead);
-    if (nx < end && !(v_next >= 0 && v_next <= u)) {
+    if (nx < end && !(v_next >= 0 && v_next <= vmax)) {
       ++nx;
       while (nx < end) {
         v_next = __builtin_amdgcn_readfirstlane(col_idx[nx]);
-        if (v_next >= 0 && v_next <= u) break;
+        if (v_next >= 0 && v_next <= vmax) break;
         ++nx;
       }
     }
@@ -268,7 +271,7 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
     }
 
     // ---- causal mask inside the diagonal block ----
-    if (v == u) {
+    if (causal && v == u) {
       const int qloc = wave * 32 + l32;
 #pragma unroll
       for (int kt = 0; kt < KT; ++kt)
@@ -586,16 +589,17 @@ extern "C" int prism_sparse_attn_pre(const prism_params* params, const void* q_b
   hipLaunchKernelGGL(queue_scan_kernel, dim3(1), dim3(1024), 0, st, hist, qc.n_bins);
   hipLaunchKernelGGL(queue_fill_kernel, dim3((qc.n_groups + 255) / 256), dim3(256), 0, st, row_ptr, qc,
                      hist, order);
+  const int causal = (params->flags & PRISM_FLAG_BIDIRECTIONAL) ? 0 : 1;
   if (params->block == 128)
     hipLaunchKernelGGL(sparse_attn_kernel<128>, dim3(grid), dim3(AttnCfg<128>::kThreads), 0, st,
                        (const uint16_t*)q_bf16, (const uint16_t*)k_bf16, (const uint16_t*)v_image,
                        row_ptr, col_idx, col_count, order, counter, (uint16_t*)out_bf16, lse, h,
-                       h_kv, L, N);
+                       h_kv, L, N, causal);
   else
     hipLaunchKernelGGL(sparse_attn_kernel<64>, dim3(grid), dim3(AttnCfg<64>::kThreads), 0, st,
                        (const uint16_t*)q_bf16, (const uint16_t*)k_bf16, (const uint16_t*)v_image,
                        row_ptr, col_idx, col_count, order, counter, (uint16_t*)out_bf16, lse, h,
-                       h_kv, L, N);
+                       h_kv, L, N, causal);
   return launch_status();
 }
 

@@ -30,7 +30,8 @@ inline int check_params(const prism_params* p) {
   const int64_t n = p->seq_len / p->block;
   if (n > kMaxBlocks) return PRISM_ERR_UNSUPPORTED;
   // CSR offsets are int32
-  const int64_t pairs = (int64_t)p->n_q_heads * n * (n + 1) / 2;
+  const int64_t pairs = (p->flags & PRISM_FLAG_BIDIRECTIONAL) ? (int64_t)p->n_q_heads * n * n
+                                                               : (int64_t)p->n_q_heads * n * (n + 1) / 2;
   if (pairs >= (int64_t)1 << 31) return PRISM_ERR_UNSUPPORTED;
   if ((int64_t)p->n_q_heads * n + 1 >= (int64_t)1 << 31) return PRISM_ERR_UNSUPPORTED;
   return PRISM_OK;
@@ -39,7 +40,6 @@ inline int check_params(const prism_params* p) {
 inline int check_bands(const prism_params* p) {
   if (p->d_high < 0 || p->d_low < 0 || p->d_high > p->head_dim || p->d_low > p->head_dim)
     return PRISM_ERR_INVALID_ARG;
-  if (p->d_high % 32 != 0 || p->d_low % 32 != 0) return PRISM_ERR_INVALID_ARG;
   if (p->d_high == 0 && p->d_low == 0) return PRISM_ERR_INVALID_ARG;
   if (!(p->top_p > 0.0f) || !(p->top_p <= 1.0f)) return PRISM_ERR_INVALID_ARG;   // also rejects NaN
   return PRISM_OK;

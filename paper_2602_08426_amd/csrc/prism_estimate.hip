@@ -10,20 +10,35 @@
 
 namespace prism {
 
+// The two bands as maps from head dims to band positions.  A band is a list of slices of
+// the head dim (Sec. 3.4: first d_high / last d_low dims; App. "HunyuanVideo Spectral
+// Configuration": first / last dims of every axis subspace); its vector is the
+// concatenation of the slices, zero-padded to a multiple of 32 for the MFMA k-steps.
+struct BandMap {
+  int8_t pos[2][kHeadDim];   // position of dim c inside band z (0 = high, 1 = low), -1: not a member
+  int32_t dz[2];             // dims in the band, 0 = band disabled
+  int32_t dpad[2];           // dz rounded up to a multiple of 32
+};
+
+// Band vectors of all heads and blocks: [z][term]([head][N][128] bf16), term = hi, mid, lo.
+struct BandVectors {
+  uint16_t* v[2][3];
+};
+
 // =====================================================================================
 // Mean pooling (Eq. "mean-pooling") and band energies (Sec. 3.4, RMS definition).
 // One workgroup per (block, head); 256 threads read B x 128 bf16 = B*256 contiguous bytes
 // as 16-byte pieces: thread t owns dims 8*(t%16)..+7 of rows t/16, t/16+16, ...
-// Outputs per (head, block): pooled vector as three bf16 terms hi + mid + lo (together
-// they carry the full fp32 mantissa), optional fp32 copy, and the three sums of squares
-// (full, first d_high dims, last d_low dims) in energy[(head*N + block)*4 + {0,1,2}].
-// Heads 0..h-1 are Q heads, h..h+h_kv-1 are K heads.
+// Outputs per (head, block): the two band vectors, each as three bf16 terms hi + mid + lo
+// (together they carry the full fp32 mantissa), an optional fp32 copy of the pooled vector,
+// and the three sums of squares (all dims, high band, low band) in
+// energy[(head*N + block)*4 + {0,1,2}].  Heads 0..h-1 are Q heads, h..h+h_kv-1 are K heads.
 // =====================================================================================
 template <int BLK>
 __global__ __launch_bounds__(256) void pool_energy_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, int h, int L, int N,
-    int d_high, int low_start, uint16_t* __restrict__ pooled_hi, uint16_t* __restrict__ pooled_mid,
-    uint16_t* __restrict__ pooled_lo, float* __restrict__ energy, float* __restrict__ pooled_q_f32, float* __restrict__ pooled_k_f32) {
+    BandMap map, BandVectors bv, float* __restrict__ energy,
+    float* __restrict__ pooled_q_f32, float* __restrict__ pooled_k_f32) {
   __shared__ float part[16][kHeadDim + 4];
   __shared__ float esum[2][4];
   const int blk = blockIdx.x, head = blockIdx.y, t = threadIdx.x;
@@ -64,9 +79,21 @@ __global__ __launch_bounds__(256) void pool_energy_kernel(
     const float rem2 = rem1 - bf16_bits_to_float(mid);
     const uint32_t lo = float_to_bf16_bits(rem2);
     const size_t o = ((size_t)head * N + blk) * kHeadDim + t;
-    pooled_hi[o] = (uint16_t)hi;
-    pooled_mid[o] = (uint16_t)mid;
-    pooled_lo[o] = (uint16_t)lo;
+    const size_t vec = ((size_t)head * N + blk) * kHeadDim;
+#pragma unroll
+    for (int z = 0; z < 2; ++z) {
+      const int pz = map.pos[z][t];
+      if (pz >= 0) {
+        bv.v[z][0][vec + pz] = (uint16_t)hi;
+        bv.v[z][1][vec + pz] = (uint16_t)mid;
+        bv.v[z][2][vec + pz] = (uint16_t)lo;
+      }
+      if (t >= map.dz[z] && t < map.dpad[z]) {           // zero padding of the last k-step
+        bv.v[z][0][vec + t] = 0;
+        bv.v[z][1][vec + t] = 0;
+        bv.v[z][2][vec + t] = 0;
+      }
+    }
     if (head < h) {
       if (pooled_q_f32) pooled_q_f32[o] = mean;
     } else if (pooled_k_f32) {
@@ -74,8 +101,8 @@ __global__ __launch_bounds__(256) void pool_energy_kernel(
     }
     const float sq = mean * mean;
     const float e_full = wave_sum(sq);
-    const float e_high = wave_sum(t < d_high ? sq : 0.f);
-    const float e_low = wave_sum(t >= low_start ? sq : 0.f);
+    const float e_high = wave_sum(map.pos[0][t] >= 0 ? sq : 0.f);
+    const float e_low = wave_sum(map.pos[1][t] >= 0 ? sq : 0.f);
     if ((t & 63) == 0) {
       esum[t >> 6][0] = e_full;
       esum[t >> 6][1] = e_high;
@@ -154,20 +181,20 @@ __global__ __launch_bounds__(64) void scale_kernel(const float* __restrict__ ene
 constexpr int kStripRows = 16;
 
 // Top-p selection of the four consecutive rows of one band that a wave owns.  Row k has
-// n0 + k causal logits (rows with n <= 0 are skipped); each row lives in registers: column
+// n0 + k*nstep logits (nstep = 1: block-causal rows, 0: every row sees all N blocks); each row lives in registers: column
 // 64*i + lane in e[k][i].  The four rows are advanced together so that their wave reductions
 // (dependent DPP chains) overlap.  Selected bits are OR-ed into the rows' LDS bit words.
 constexpr int kRowsPerWave = 4;
 
 template <int NCH>
-__device__ __forceinline__ void select_rows(const float* __restrict__ logits, int ld, int n0, int nrows,
-                                            float top_p, int lane, uint64_t* __restrict__ bits,
-                                            int bits_ld) {
+__device__ __forceinline__ void select_rows(const float* __restrict__ logits, int ld, int n0, int nstep,
+                                            int nrows, float top_p, int lane,
+                                            uint64_t* __restrict__ bits, int bits_ld) {
   float e[kRowsPerWave][NCH];
   float total[kRowsPerWave], target[kRowsPerWave];
 #pragma unroll
   for (int k = 0; k < kRowsPerWave; ++k) {
-    const int n = k < nrows ? n0 + k : 0;
+    const int n = k < nrows ? n0 + k * nstep : 0;
     float mx = -INFINITY;
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
@@ -228,7 +255,7 @@ __device__ __forceinline__ void select_rows(const float* __restrict__ logits, in
 #pragma unroll
   for (int k = 0; k < kRowsPerWave; ++k) {
     if (k >= nrows) break;
-    const int n = n0 + k;
+    const int n = n0 + k * nstep;
     const float tie_val = __uint_as_float(tstar[k]);
     int tie_base = 0;
 #pragma unroll
@@ -251,11 +278,15 @@ __device__ __forceinline__ void select_rows(const float* __restrict__ logits, in
   }
 }
 
+// select_flags
+constexpr int kSelCausal = 1;          // key blocks v > u are excluded (block-causal estimation)
+constexpr int kSelForceDiagonal = 2;   // block u of every row is switched on after the union
+constexpr int kSelForceSink = 4;       // block 0 of every row is switched on after the union
+
 template <int MAXCH, bool DUMP>
 __global__ __launch_bounds__(256) void select_kernel(
-    const uint16_t* __restrict__ pooled_hi, const uint16_t* __restrict__ pooled_mid,
-    const uint16_t* __restrict__ pooled_lo, const float* __restrict__ inv_scale, int h, int h_kv,
-    int N, int d_high, int d_low, float top_p,
+    BandVectors bv, const float* __restrict__ inv_scale, int h, int h_kv,
+    int N, int dpad_high, int dpad_low, float top_p, int select_flags,
     uint64_t* __restrict__ mask_bits, int32_t* __restrict__ row_ptr,
     float* __restrict__ logits_high, float* __restrict__ logits_low) {
   extern __shared__ float lds_logits[];
@@ -266,7 +297,8 @@ __global__ __launch_bounds__(256) void select_kernel(
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // uniform: scalar branches below
   const int u0 = strip * kStripRows;
-  const int ncols = min(N, u0 + kStripRows);
+  const bool causal = (select_flags & kSelCausal) != 0;
+  const int ncols = causal ? min(N, u0 + kStripRows) : N;
   const int ntiles = (ncols + 15) >> 4;
   const int ld = ntiles * 16 + 4;
   const int W = (N + 63) >> 6;
@@ -278,16 +310,18 @@ __global__ __launch_bounds__(256) void select_kernel(
 
 #pragma unroll 1
   for (int z = 0; z < 2; ++z) {
-    const int dz = z == 0 ? d_high : d_low;
+    const int dz = z == 0 ? dpad_high : dpad_low;
     if (dz == 0) continue;                         // uniform: same for the whole grid
-    const int band_off = z == 0 ? 0 : kHeadDim - d_low;
     const int ksteps = dz >> 5;
     const float inv = inv_scale[hq * 2 + z];
+    const uint16_t* __restrict__ pooled_hi = bv.v[z][0];
+    const uint16_t* __restrict__ pooled_mid = bv.v[z][1];
+    const uint16_t* __restrict__ pooled_lo = bv.v[z][2];
 
     // ---------------- phase A: logits of the strip into LDS ----------------
     {
       const int arow = min(u0 + (lane & 15), N - 1);
-      const size_t aoff = ((size_t)hq * N + arow) * kHeadDim + band_off + (lane >> 4) * 8;
+      const size_t aoff = ((size_t)hq * N + arow) * kHeadDim + (lane >> 4) * 8;
       bf16x8 ah[4], am[4], al[4];
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks) {
@@ -301,7 +335,7 @@ __global__ __launch_bounds__(256) void select_kernel(
       bf16x8 bh[4], bm[4], bl[4];
       auto load_b = [&](int ct) {
         const int brow = min(ct * 16 + (lane & 15), N - 1);
-        const size_t boff = ((size_t)kvh * N + brow) * kHeadDim + band_off + (lane >> 4) * 8;
+        const size_t boff = ((size_t)kvh * N + brow) * kHeadDim + (lane >> 4) * 8;
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
           if (ks < ksteps) {
@@ -343,7 +377,8 @@ __global__ __launch_bounds__(256) void select_kernel(
           if (DUMP) {
             const int u = u0 + row;
             float* dst = z == 0 ? logits_high : logits_low;
-            if (dst != nullptr && u < N && col <= u) dst[((size_t)hq * N + u) * N + col] = lg;
+            if (dst != nullptr && u < N && col < N && (col <= u || !causal))
+              dst[((size_t)hq * N + u) * N + col] = lg;
           }
         }
       }
@@ -355,16 +390,17 @@ __global__ __launch_bounds__(256) void select_kernel(
       const int r0 = wave * kRowsPerWave;
       const int nrows = min(kRowsPerWave, N - (u0 + r0));          // uniform per wave, may be <= 0
       if (nrows > 0) {
-        const int n0 = u0 + r0 + 1;                                // columns of the first row
-        const int nmax = n0 + nrows - 1;
+        const int n0 = causal ? u0 + r0 + 1 : N;                   // columns of the first row
+        const int nstep = causal ? 1 : 0;
+        const int nmax = n0 + (nrows - 1) * nstep;
         const float* lg = lds_logits + r0 * ld;
         uint64_t* bits = &lds_bits[r0][0];
         constexpr int bld = kMaxBlocks / 64;
-        if (nmax <= 128) select_rows<2>(lg, ld, n0, nrows, top_p, lane, bits, bld);
-        else if (nmax <= 256) select_rows<4>(lg, ld, n0, nrows, top_p, lane, bits, bld);
-        else if (nmax <= 512) select_rows<8>(lg, ld, n0, nrows, top_p, lane, bits, bld);
-        else if (MAXCH <= 16 || nmax <= 1024) select_rows<16>(lg, ld, n0, nrows, top_p, lane, bits, bld);
-        else select_rows<MAXCH>(lg, ld, n0, nrows, top_p, lane, bits, bld);
+        if (nmax <= 128) select_rows<2>(lg, ld, n0, nstep, nrows, top_p, lane, bits, bld);
+        else if (nmax <= 256) select_rows<4>(lg, ld, n0, nstep, nrows, top_p, lane, bits, bld);
+        else if (nmax <= 512) select_rows<8>(lg, ld, n0, nstep, nrows, top_p, lane, bits, bld);
+        else if (MAXCH <= 16 || nmax <= 1024) select_rows<16>(lg, ld, n0, nstep, nrows, top_p, lane, bits, bld);
+        else select_rows<MAXCH>(lg, ld, n0, nstep, nrows, top_p, lane, bits, bld);
       }
       __syncthreads();                             // LDS logits are reused by the next band
     }
@@ -377,7 +413,9 @@ __global__ __launch_bounds__(256) void select_kernel(
       const int u = u0 + r;
       if (u >= N) break;
       const size_t row = (size_t)hq * N + u;
-      const uint64_t word = lane < W ? lds_bits[r][lane] : 0ull;
+      uint64_t word = lane < W ? lds_bits[r][lane] : 0ull;
+      if ((select_flags & kSelForceDiagonal) && lane == (u >> 6)) word |= 1ull << (u & 63);
+      if ((select_flags & kSelForceSink) && lane == 0) word |= 1ull;
       const int cnt = wave_sum((int)__popcll(word));
       if (lane < W) mask_bits[row * W + lane] = word;
       if (lane == 0) row_ptr[row + 1] = cnt;
@@ -460,68 +498,119 @@ __global__ __launch_bounds__(256) void fill_kernel(const uint64_t* __restrict__ 
   }
 }
 
-__global__ __launch_bounds__(256) void causal_csr_kernel(int h, int N, int32_t* __restrict__ row_ptr,
-                                                         int32_t* __restrict__ col_idx) {
+// Index lists of the all-ones mask: row (head,u) = {0..u} (causal) or {0..N-1}.
+__global__ __launch_bounds__(256) void dense_csr_kernel(int h, int N, int causal,
+                                                        int32_t* __restrict__ row_ptr,
+                                                        int32_t* __restrict__ col_idx) {
   const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
   const int R = h * N;
   if (r > R) return;
+  const int64_t per_head = causal ? (int64_t)N * (N + 1) / 2 : (int64_t)N * N;
   if (r == R) {
-    if (lane == 0) row_ptr[R] = (int32_t)((int64_t)h * N * (N + 1) / 2);
+    if (lane == 0) row_ptr[R] = (int32_t)(h * per_head);
     return;
   }
   const int hq = r / N, u = r % N;
-  const int64_t base = (int64_t)hq * N * (N + 1) / 2 + (int64_t)u * (u + 1) / 2;
+  const int64_t base = hq * per_head + (causal ? (int64_t)u * (u + 1) / 2 : (int64_t)u * N);
+  const int len = causal ? u + 1 : N;
   if (lane == 0) row_ptr[r] = (int32_t)base;
-  for (int v = lane; v <= u; v += 64) col_idx[base + v] = v;
+  for (int v = lane; v < len; v += 64) col_idx[base + v] = v;
+}
+
+// ---- band descriptors (host) -------------------------------------------------------
+// Contiguous bands of Sec. 3.4: first d_high dims, last d_low dims.
+static prism_bands default_bands(const prism_params* p) {
+  prism_bands b = {};
+  if (p->d_high > 0) {
+    b.high.n_segments = 1;
+    b.high.start[0] = 0;
+    b.high.width[0] = p->d_high;
+  }
+  if (p->d_low > 0) {
+    b.low.n_segments = 1;
+    b.low.start[0] = p->head_dim - p->d_low;
+    b.low.width[0] = p->d_low;
+  }
+  return b;
+}
+
+// Validates the descriptors and builds the dim -> band position maps.
+static int make_band_map(const prism_params* p, const prism_bands* bands, BandMap* map) {
+  if (bands == nullptr) return PRISM_ERR_INVALID_ARG;
+  if (!(p->top_p > 0.0f) || !(p->top_p <= 1.0f)) return PRISM_ERR_INVALID_ARG;   // also rejects NaN
+  const prism_band* zb[2] = {&bands->high, &bands->low};
+  for (int z = 0; z < 2; ++z) {
+    for (int c = 0; c < kHeadDim; ++c) map->pos[z][c] = -1;
+    if (zb[z]->n_segments < 0 || zb[z]->n_segments > PRISM_MAX_SEGMENTS) return PRISM_ERR_INVALID_ARG;
+    int n = 0;
+    for (int i = 0; i < zb[z]->n_segments; ++i) {
+      const int64_t start = zb[z]->start[i], width = zb[z]->width[i];
+      if (start < 0 || width <= 0 || start + width > p->head_dim) return PRISM_ERR_INVALID_ARG;
+      for (int c = (int)start; c < (int)(start + width); ++c) {
+        if (map->pos[z][c] >= 0) return PRISM_ERR_INVALID_ARG;          // slices of one band overlap
+        map->pos[z][c] = (int8_t)n++;
+      }
+    }
+    map->dz[z] = n;
+    map->dpad[z] = (n + 31) / 32 * 32;
+  }
+  if (map->dz[0] == 0 && map->dz[1] == 0) return PRISM_ERR_INVALID_ARG;
+  return PRISM_OK;
 }
 
 // ---- workspace layout ------------------------------------------------------------
 struct EstimateWs {
-  size_t pooled_hi, pooled_mid, pooled_lo, energy, inv_scale, total;
+  size_t band[2][3], energy, inv_scale, total;
 };
 static EstimateWs estimate_ws(const prism_params* p) {
   const size_t N = p->seq_len / p->block;
   const size_t heads = (size_t)p->n_q_heads + p->n_kv_heads;
   EstimateWs w;
   size_t off = 0;
-  w.pooled_hi = off; off = align_up(off + heads * N * kHeadDim * 2, 256);
-  w.pooled_mid = off; off = align_up(off + heads * N * kHeadDim * 2, 256);
-  w.pooled_lo = off; off = align_up(off + heads * N * kHeadDim * 2, 256);
+  for (int z = 0; z < 2; ++z)
+    for (int term = 0; term < 3; ++term) {
+      w.band[z][term] = off;
+      off = align_up(off + heads * N * kHeadDim * 2, 256);
+    }
   w.energy = off;    off = align_up(off + heads * N * 4 * sizeof(float), 256);
   w.inv_scale = off; off = align_up(off + (size_t)p->n_q_heads * 2 * sizeof(float), 256);
   w.total = off;
   return w;
 }
 
-static int run_pool_and_scale(const prism_params* p, const void* q, const void* k, char* ws,
-                              const EstimateWs& L, float* pooled_q, float* pooled_k, float* scales,
-                              hipStream_t st) {
+static BandVectors band_vectors(char* ws, const EstimateWs& L) {
+  BandVectors bv;
+  for (int z = 0; z < 2; ++z)
+    for (int term = 0; term < 3; ++term) bv.v[z][term] = reinterpret_cast<uint16_t*>(ws + L.band[z][term]);
+  return bv;
+}
+
+static int run_pool_and_scale(const prism_params* p, const BandMap& map, const void* q, const void* k,
+                              char* ws, const EstimateWs& L, float* pooled_q, float* pooled_k,
+                              float* scales, hipStream_t st) {
   const int N = p->seq_len / p->block;
   const dim3 grid(N, p->n_q_heads + p->n_kv_heads);
-  uint16_t* hi = reinterpret_cast<uint16_t*>(ws + L.pooled_hi);
-  uint16_t* mid = reinterpret_cast<uint16_t*>(ws + L.pooled_mid);
-  uint16_t* lo = reinterpret_cast<uint16_t*>(ws + L.pooled_lo);
+  const BandVectors bv = band_vectors(ws, L);
   float* energy = reinterpret_cast<float*>(ws + L.energy);
   float* inv = reinterpret_cast<float*>(ws + L.inv_scale);
-  const int low_start = p->head_dim - p->d_low;
   if (p->block == 128)
     hipLaunchKernelGGL(pool_energy_kernel<128>, grid, dim3(256), 0, st, (const uint16_t*)q,
-                       (const uint16_t*)k, p->n_q_heads, p->seq_len, N, p->d_high, low_start, hi, mid,
-                       lo, energy, pooled_q, pooled_k);
+                       (const uint16_t*)k, p->n_q_heads, p->seq_len, N, map, bv, energy, pooled_q,
+                       pooled_k);
   else
     hipLaunchKernelGGL(pool_energy_kernel<64>, grid, dim3(256), 0, st, (const uint16_t*)q,
-                       (const uint16_t*)k, p->n_q_heads, p->seq_len, N, p->d_high, low_start, hi, mid,
-                       lo, energy, pooled_q, pooled_k);
+                       (const uint16_t*)k, p->n_q_heads, p->seq_len, N, map, bv, energy, pooled_q,
+                       pooled_k);
   hipLaunchKernelGGL(scale_kernel, dim3(p->n_q_heads), dim3(64), 0, st, energy, p->n_q_heads,
-                     p->n_kv_heads, N, p->d_high, p->d_low,
+                     p->n_kv_heads, N, map.dz[0], map.dz[1],
                      (p->flags & PRISM_FLAG_NO_CALIBRATION) ? 0 : 1, inv, scales);
   return launch_status();
 }
 
 template <int MAXCH, bool DUMP>
-static int launch_select(const prism_params* p, char* ws, const EstimateWs& L, uint64_t* mask_bits,
-                         int32_t* row_ptr, float* lh, float* ll, hipStream_t st) {
+static int launch_select(const prism_params* p, const BandMap& map, char* ws, const EstimateWs& L,
+                         uint64_t* mask_bits, int32_t* row_ptr, float* lh, float* ll, hipStream_t st) {
   const int N = p->seq_len / p->block;
   const int strips = (N + kStripRows - 1) / kStripRows;
   const size_t lds = (size_t)kStripRows * (((N + 15) / 16) * 16 + 4) * sizeof(float);
@@ -531,12 +620,13 @@ static int launch_select(const prism_params* p, char* ws, const EstimateWs& L, u
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
       return PRISM_ERR_HIP;
   }
-  hipLaunchKernelGGL(kern, dim3(strips, p->n_q_heads), dim3(256), lds, st,
-                     reinterpret_cast<const uint16_t*>(ws + L.pooled_hi),
-                     reinterpret_cast<const uint16_t*>(ws + L.pooled_mid),
-                     reinterpret_cast<const uint16_t*>(ws + L.pooled_lo),
+  int select_flags = 0;
+  if (!(p->flags & PRISM_FLAG_BIDIRECTIONAL)) select_flags |= kSelCausal;
+  if (p->flags & PRISM_FLAG_FORCE_DIAGONAL) select_flags |= kSelForceDiagonal;
+  if (p->flags & PRISM_FLAG_FORCE_SINK) select_flags |= kSelForceSink;
+  hipLaunchKernelGGL(kern, dim3(strips, p->n_q_heads), dim3(256), lds, st, band_vectors(ws, L),
                      reinterpret_cast<const float*>(ws + L.inv_scale), p->n_q_heads, p->n_kv_heads, N,
-                     p->d_high, p->d_low, p->top_p, mask_bits, row_ptr, lh, ll);
+                     map.dpad[0], map.dpad[1], p->top_p, select_flags, mask_bits, row_ptr, lh, ll);
   return launch_status();
 }
 
@@ -586,13 +676,15 @@ extern "C" int prism_estimate_workspace_bytes(const prism_params* params, size_t
   return PRISM_OK;
 }
 
-extern "C" int prism_estimate(const prism_params* params, const void* q_bf16, const void* k_bf16,
-                              uint64_t* mask_bits, int32_t* row_ptr, int32_t* col_idx,
-                              int64_t col_capacity, int32_t* info, void* workspace,
-                              size_t workspace_bytes, void* stream) {
+extern "C" int prism_estimate_bands(const prism_params* params, const prism_bands* bands,
+                                    const void* q_bf16, const void* k_bf16, uint64_t* mask_bits,
+                                    int32_t* row_ptr, int32_t* col_idx, int64_t col_capacity,
+                                    int32_t* info, void* workspace, size_t workspace_bytes,
+                                    void* stream) {
   int rc = check_params(params);
   if (rc != PRISM_OK) return rc;
-  rc = check_bands(params);
+  BandMap map;
+  rc = make_band_map(params, bands, &map);
   if (rc != PRISM_OK) return rc;
   if (!q_bf16 || !k_bf16 || !mask_bits || !row_ptr || !col_idx || !info || col_capacity < 0)
     return PRISM_ERR_INVALID_ARG;
@@ -601,13 +693,49 @@ extern "C" int prism_estimate(const prism_params* params, const void* q_bf16, co
   if (rc != PRISM_OK) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
   char* ws = static_cast<char*>(workspace);
-  rc = run_pool_and_scale(params, q_bf16, k_bf16, ws, L, nullptr, nullptr, nullptr, st);
+  rc = run_pool_and_scale(params, map, q_bf16, k_bf16, ws, L, nullptr, nullptr, nullptr, st);
   if (rc != PRISM_OK) return rc;
   const int N = params->seq_len / params->block;
-  rc = (N <= 1024) ? launch_select<16, false>(params, ws, L, mask_bits, row_ptr, nullptr, nullptr, st)
-                   : launch_select<32, false>(params, ws, L, mask_bits, row_ptr, nullptr, nullptr, st);
+  rc = (N <= 1024)
+           ? launch_select<16, false>(params, map, ws, L, mask_bits, row_ptr, nullptr, nullptr, st)
+           : launch_select<32, false>(params, map, ws, L, mask_bits, row_ptr, nullptr, nullptr, st);
   if (rc != PRISM_OK) return rc;
   return run_compaction(params, mask_bits, row_ptr, col_idx, col_capacity, info, false, st);
+}
+
+extern "C" int prism_estimate(const prism_params* params, const void* q_bf16, const void* k_bf16,
+                              uint64_t* mask_bits, int32_t* row_ptr, int32_t* col_idx,
+                              int64_t col_capacity, int32_t* info, void* workspace,
+                              size_t workspace_bytes, void* stream) {
+  int rc = check_params(params);
+  if (rc != PRISM_OK) return rc;
+  rc = check_bands(params);
+  if (rc != PRISM_OK) return rc;
+  const prism_bands bands = default_bands(params);
+  return prism_estimate_bands(params, &bands, q_bf16, k_bf16, mask_bits, row_ptr, col_idx,
+                              col_capacity, info, workspace, workspace_bytes, stream);
+}
+
+extern "C" int prism_block_scores_bands(const prism_params* params, const prism_bands* bands,
+                                        const void* q_bf16, const void* k_bf16, float* pooled_q,
+                                        float* pooled_k, float* scales, float* logits_high,
+                                        float* logits_low, void* workspace, size_t workspace_bytes,
+                                        void* stream) {
+  int rc = check_params(params);
+  if (rc != PRISM_OK) return rc;
+  BandMap map;
+  rc = make_band_map(params, bands, &map);
+  if (rc != PRISM_OK) return rc;
+  if (!q_bf16 || !k_bf16) return PRISM_ERR_INVALID_ARG;
+  const EstimateWs L = estimate_ws(params);
+  rc = check_ws(workspace, workspace_bytes, L.total);
+  if (rc != PRISM_OK) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  char* ws = static_cast<char*>(workspace);
+  rc = run_pool_and_scale(params, map, q_bf16, k_bf16, ws, L, pooled_q, pooled_k, scales, st);
+  if (rc != PRISM_OK) return rc;
+  if (logits_high == nullptr && logits_low == nullptr) return PRISM_OK;
+  return launch_select<16, true>(params, map, ws, L, nullptr, nullptr, logits_high, logits_low, st);
 }
 
 extern "C" int prism_block_scores(const prism_params* params, const void* q_bf16,
@@ -618,16 +746,9 @@ extern "C" int prism_block_scores(const prism_params* params, const void* q_bf16
   if (rc != PRISM_OK) return rc;
   rc = check_bands(params);
   if (rc != PRISM_OK) return rc;
-  if (!q_bf16 || !k_bf16) return PRISM_ERR_INVALID_ARG;
-  const EstimateWs L = estimate_ws(params);
-  rc = check_ws(workspace, workspace_bytes, L.total);
-  if (rc != PRISM_OK) return rc;
-  hipStream_t st = static_cast<hipStream_t>(stream);
-  char* ws = static_cast<char*>(workspace);
-  rc = run_pool_and_scale(params, q_bf16, k_bf16, ws, L, pooled_q, pooled_k, scales, st);
-  if (rc != PRISM_OK) return rc;
-  if (logits_high == nullptr && logits_low == nullptr) return PRISM_OK;
-  return launch_select<16, true>(params, ws, L, nullptr, nullptr, logits_high, logits_low, st);
+  const prism_bands bands = default_bands(params);
+  return prism_block_scores_bands(params, &bands, q_bf16, k_bf16, pooled_q, pooled_k, scales,
+                                  logits_high, logits_low, workspace, workspace_bytes, stream);
 }
 
 extern "C" int prism_mask_to_csr(const prism_params* params, const uint64_t* mask_bits,
@@ -640,15 +761,28 @@ extern "C" int prism_mask_to_csr(const prism_params* params, const uint64_t* mas
                         static_cast<hipStream_t>(stream));
 }
 
-extern "C" int prism_causal_csr(const prism_params* params, int32_t* row_ptr, int32_t* col_idx,
-                                int64_t col_capacity, void* stream) {
+static int dense_csr(const prism_params* params, bool causal, int32_t* row_ptr, int32_t* col_idx,
+                     int64_t col_capacity, void* stream) {
   int rc = check_params(params);
   if (rc != PRISM_OK) return rc;
   if (!row_ptr || !col_idx) return PRISM_ERR_INVALID_ARG;
   const int64_t N = params->seq_len / params->block;
-  if (col_capacity < (int64_t)params->n_q_heads * N * (N + 1) / 2) return PRISM_ERR_INVALID_ARG;
+  const int64_t need = (int64_t)params->n_q_heads * (causal ? N * (N + 1) / 2 : N * N);
+  if (col_capacity < need) return PRISM_ERR_INVALID_ARG;
   const int R = params->n_q_heads * (int)N;
-  hipLaunchKernelGGL(causal_csr_kernel, dim3((R + 1 + 3) / 4), dim3(256), 0,
-                     static_cast<hipStream_t>(stream), params->n_q_heads, (int)N, row_ptr, col_idx);
+  hipLaunchKernelGGL(dense_csr_kernel, dim3((R + 1 + 3) / 4), dim3(256), 0,
+                     static_cast<hipStream_t>(stream), params->n_q_heads, (int)N, causal ? 1 : 0,
+                     row_ptr, col_idx);
   return launch_status();
+}
+
+extern "C" int prism_causal_csr(const prism_params* params, int32_t* row_ptr, int32_t* col_idx,
+                                int64_t col_capacity, void* stream) {
+  return dense_csr(params, true, row_ptr, col_idx, col_capacity, stream);
+}
+
+extern "C" int prism_dense_csr(const prism_params* params, int32_t* row_ptr, int32_t* col_idx,
+                               int64_t col_capacity, void* stream) {
+  const bool causal = params == nullptr || !(params->flags & PRISM_FLAG_BIDIRECTIONAL);
+  return dense_csr(params, causal, row_ptr, col_idx, col_capacity, stream);
 }

@@ -31,12 +31,15 @@ def params_for(w, **over):
     return pb.make_params(**kw)
 
 
-def gpu_estimate(params, q_dev, k_dev, col_capacity=None):
-    """Returns dict of numpy results of prism_estimate."""
+def gpu_estimate(params, q_dev, k_dev, col_capacity=None, bands=None):
+    """Returns dict of numpy results of prism_estimate (prism_estimate_bands with `bands`)."""
     mask_bits, row_ptr, col_idx, info = pb.alloc_estimate_outputs(params, col_capacity)
     cap = col_idx.numel() if col_capacity is None else col_capacity
     ws = pb.alloc_workspace(pb.prism_estimate_workspace_bytes(params))
-    pb.prism_estimate(params, q_dev, k_dev, mask_bits, row_ptr, col_idx, cap, info, ws)
+    if bands is None:
+        pb.prism_estimate(params, q_dev, k_dev, mask_bits, row_ptr, col_idx, cap, info, ws)
+    else:
+        pb.prism_estimate_bands(params, bands, q_dev, k_dev, mask_bits, row_ptr, col_idx, cap, info, ws)
     torch.cuda.synchronize()
     N = params.n_blocks
     words = mask_bits.cpu().numpy().view(np.uint64)
@@ -45,7 +48,7 @@ def gpu_estimate(params, q_dev, k_dev, col_capacity=None):
                 dev=(mask_bits, row_ptr, col_idx, info))
 
 
-def gpu_block_scores(params, q_dev, k_dev, want_logits=True):
+def gpu_block_scores(params, q_dev, k_dev, want_logits=True, bands=None):
     h, hk, N = params.n_q_heads, params.n_kv_heads, params.n_blocks
     pq = torch.empty((h, N, 128), dtype=torch.float32, device="cuda")
     pk = torch.empty((hk, N, 128), dtype=torch.float32, device="cuda")
@@ -53,7 +56,10 @@ def gpu_block_scores(params, q_dev, k_dev, want_logits=True):
     lh = torch.full((h, N, N), float("nan"), dtype=torch.float32, device="cuda") if want_logits else None
     ll = torch.full((h, N, N), float("nan"), dtype=torch.float32, device="cuda") if want_logits else None
     ws = pb.alloc_workspace(pb.prism_estimate_workspace_bytes(params))
-    pb.prism_block_scores(params, q_dev, k_dev, pq, pk, sc, lh, ll, ws)
+    if bands is None:
+        pb.prism_block_scores(params, q_dev, k_dev, pq, pk, sc, lh, ll, ws)
+    else:
+        pb.prism_block_scores_bands(params, bands, q_dev, k_dev, pq, pk, sc, lh, ll, ws)
     torch.cuda.synchronize()
     out = dict(pooled_q=pq.cpu().numpy(), pooled_k=pk.cpu().numpy(), scales=sc.cpu().numpy())
     if want_logits:

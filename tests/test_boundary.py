@@ -44,8 +44,8 @@ def test_workspace_queries(lib):
     p = pb.make_params(32, 8, 131072, 128)
     n = pb.prism_estimate_workspace_bytes(p)
     heads, N = 40, 1024
-    assert n >= heads * N * 128 * 2 * 3 + heads * N * 16
-    assert n < 64 << 20
+    assert n >= heads * N * 128 * 2 * 6 + heads * N * 16      # two bands x three bf16 terms
+    assert n < 72 << 20
     ws = pb.prism_sparse_attn_workspace_bytes(p)
     assert 8 * 131072 * 128 * 2 + 8 * 1024 * 4 <= ws < 8 * 131072 * 128 * 2 + (1 << 20)
 
@@ -67,7 +67,7 @@ def test_bad_geometry_is_rejected(lib, kw, status):
     assert lib.prism_sparse_attn_workspace_bytes(ctypes.byref(p), ctypes.byref(n)) == status
 
 
-@pytest.mark.parametrize("kw", [dict(d_high=48), dict(d_low=160), dict(d_high=0, d_low=0),
+@pytest.mark.parametrize("kw", [dict(d_high=-32), dict(d_low=160), dict(d_high=0, d_low=0),
                                 dict(top_p=0.0), dict(top_p=1.5), dict(top_p=float("nan"))])
 def test_bad_bands_are_rejected_before_launch(lib, kw):
     base = dict(n_q_heads=4, n_kv_heads=2, seq_len=1024, block=128)
@@ -76,6 +76,40 @@ def test_bad_bands_are_rejected_before_launch(lib, kw):
     fake = ctypes.c_void_p(256)     # never dereferenced: validation fails first
     rc = lib.prism_estimate(ctypes.byref(p), fake, fake, fake, fake, fake, 10, fake, fake, 1 << 30, None)
     assert rc == -1
+
+
+@pytest.mark.parametrize("high,low", [
+    ([(0, 64), (32, 64)], [(32, 96)]),             # slices of one band overlap
+    ([(120, 16)], [(32, 96)]),                     # runs past the head dim
+    ([(0, 0)], [(32, 96)]),                        # empty slice
+    ([(-8, 16)], [(32, 96)]),
+    ([], []),                                      # both bands off
+])
+def test_bad_band_descriptors_are_rejected_before_launch(lib, high, low):
+    p = pb.make_params(4, 2, 1024, 128)
+    bands = pb.make_bands(high, low)
+    fake = ctypes.c_void_p(256)     # never dereferenced: validation fails first
+    rc = lib.prism_estimate_bands(ctypes.byref(p), ctypes.byref(bands), fake, fake, fake, fake, fake, 10,
+                                  fake, fake, 1 << 30, None)
+    assert rc == -1
+    bands.high.n_segments = 9                      # more than PRISM_MAX_SEGMENTS
+    assert lib.prism_estimate_bands(ctypes.byref(p), ctypes.byref(bands), fake, fake, fake, fake, fake,
+                                    10, fake, fake, 1 << 30, None) == -1
+    assert lib.prism_estimate_bands(ctypes.byref(p), None, fake, fake, fake, fake, fake, 10, fake, fake,
+                                    1 << 30, None) == -1
+
+
+def test_bidirectional_capacity_and_pair_limit(lib):
+    p = pb.make_params(4, 2, 1024, 128, flags=pb.PRISM_FLAG_BIDIRECTIONAL)
+    fake = ctypes.c_void_p(256)
+    N = 8
+    assert lib.prism_dense_csr(ctypes.byref(p), fake, fake, 4 * N * N - 1, None) == -1   # needs h*N*N
+    assert lib.prism_causal_csr(ctypes.byref(p), fake, fake, 4 * N * (N + 1) // 2 - 1, None) == -1
+    big = pb.make_params(512, 512, 128 * 2048, 128, flags=pb.PRISM_FLAG_BIDIRECTIONAL)   # h*N*N >= 2^31
+    n = ctypes.c_size_t(0)
+    assert lib.prism_estimate_workspace_bytes(ctypes.byref(big), ctypes.byref(n)) == -2
+    big.flags = 0                                                                          # h*N*(N+1)/2 fits
+    assert lib.prism_estimate_workspace_bytes(ctypes.byref(big), ctypes.byref(n)) == 0
 
 
 def test_null_pointers_and_workspace_are_rejected(lib):
