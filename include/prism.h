@@ -38,7 +38,7 @@ extern "C" {
 typedef enum prism_status {
   PRISM_OK = 0,
   PRISM_ERR_INVALID_ARG = -1,     /* null pointer, inconsistent sizes, p outside (0,1], ... */
-  PRISM_ERR_UNSUPPORTED = -2,     /* head_dim != 128, block not in {64,128}, seq_len % block != 0, ... */
+  PRISM_ERR_UNSUPPORTED = -2,     /* head_dim != 128, block not in {64,128}, more than 2048 blocks, ... */
   PRISM_ERR_WORKSPACE = -3,       /* workspace missing, misaligned or too small */
   PRISM_ERR_HIP = -4              /* a HIP runtime call failed (launch error) */
 } prism_status;
@@ -56,9 +56,9 @@ typedef enum prism_status {
 typedef struct prism_params {
   int32_t n_q_heads;    /* h   (batch folded in)                                   */
   int32_t n_kv_heads;   /* h_kv, must divide n_q_heads                             */
-  int32_t seq_len;      /* L, multiple of `block`                                   */
+  int32_t seq_len;      /* L; the last block may be ragged (holds L mod B tokens)   */
   int32_t head_dim;     /* d, must be 128                                           */
-  int32_t block;        /* B, 64 or 128; N = L / B blocks, N <= 2048                */
+  int32_t block;        /* B, 64 or 128; N = ceil(L / B) blocks, N <= 2048          */
   int32_t d_high;       /* width of the high-frequency band, 0..d (0 = band off)    */
   int32_t d_low;        /* width of the low-frequency band,  0..d (0 = band off)    */
   float   top_p;        /* p in (0,1]; p >= 1 selects every admissible block        */
@@ -91,7 +91,8 @@ const char* prism_status_string(int status);
  * Block importance estimation — Sec. 3.4 "Prism: Spectral-Aware Block Selection" and
  * App. C "Top-P Block Selection".
  *
- * Computes, per q-head:  mean-pooled Qbar, Kbar (Eq. "mean-pooling");  RMS energies of
+ * Computes, per q-head:  mean-pooled Qbar, Kbar (Eq. "mean-pooling"; a ragged last block is
+ * averaged over the tokens it holds);  RMS energies of
  * the full / high / low slices;  tau_z = sqrt(d_z/d) (RMS(Qbar_z)/RMS(Qbar))
  * (RMS(Kbar_z)/RMS(Kbar));  logits_z = Qbar_z Kbar_z^T / (tau_z sqrt(d_z)) for key
  * blocks v <= u (block-causal; every v with PRISM_FLAG_BIDIRECTIONAL);  row softmax;

@@ -38,7 +38,7 @@ class prism_params(ctypes.Structure):
 
     @property
     def n_blocks(self) -> int:
-        return self.seq_len // self.block
+        return -(-self.seq_len // self.block)
 
     @property
     def words_per_row(self) -> int:

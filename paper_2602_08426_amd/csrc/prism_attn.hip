@@ -20,7 +20,8 @@
 namespace prism {
 
 // =====================================================================================
-// V re-layout: V [h_kv, L, d]  ->  image [h_kv, N, d, B] with permuted key positions.
+// V re-layout: V [h_kv, L, d]  ->  image [h_kv, N, d, B] with permuted key positions; keys
+// past the end of a ragged last block are written as zeros.
 // =====================================================================================
 template <int BLK>
 __global__ __launch_bounds__(256) void vt_image_kernel(const uint16_t* __restrict__ v,
@@ -28,9 +29,11 @@ __global__ __launch_bounds__(256) void vt_image_kernel(const uint16_t* __restric
   __shared__ uint16_t tile[BLK][kHeadDim + 2];
   const int blk = blockIdx.x, kvh = blockIdx.y, t = threadIdx.x;
   const uint16_t* src = v + ((size_t)kvh * L + (size_t)blk * BLK) * kHeadDim;
+  const int cnt = min(BLK, L - blk * BLK);
   for (int idx = t; idx < BLK * 16; idx += 256) {
     const int row = idx >> 4, c = idx & 15;
-    const uint4 x = *reinterpret_cast<const uint4*>(src + (size_t)row * kHeadDim + c * 8);
+    const uint4 x = row < cnt ? *reinterpret_cast<const uint4*>(src + (size_t)row * kHeadDim + c * 8)
+                              : make_uint4(0u, 0u, 0u, 0u);
     uint32_t* dst = reinterpret_cast<uint32_t*>(&tile[row][c * 8]);   // 4-byte aligned: row stride 260 B
     dst[0] = x.x; dst[1] = x.y; dst[2] = x.z; dst[3] = x.w;
   }
@@ -188,16 +191,19 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
   beg = beg < 0 ? 0 : (beg > cap ? cap : beg);
   end = end < beg ? beg : (end > cap ? cap : end);
 
-  // K and V^T of this kv head as buffer resources (tile v starts at byte v * kTileBytes)
+  // K and V^T of this kv head as buffer resources (tile v starts at byte v * kTileBytes).
+  // K is the caller's tensor: rows past L in a ragged last block are outside the resource and
+  // read as zeros.  The V^T image is padded to whole blocks.
   const uint32_t head_bytes = (uint32_t)L * kHeadDim * 2;
+  const uint32_t image_head_bytes = (uint32_t)N * C::kTileBytes;
   const __amdgpu_buffer_rsrc_t krs = make_rsrc(k + (size_t)kvh * L * kHeadDim, head_bytes);
-  const __amdgpu_buffer_rsrc_t vrs = make_rsrc(vt + (size_t)kvh * L * kHeadDim, head_bytes);
+  const __amdgpu_buffer_rsrc_t vrs = make_rsrc(vt + (size_t)kvh * N * BLK * kHeadDim, image_head_bytes);
 
   // Q fragments (B operand of S^T = K Q^T): query row 32*wave + l32, dims 16*ks + 8*hf ..+7
-  const int qrow = u * BLK + wave * 32 + l32;
+  const int qrow = u * BLK + wave * 32 + l32;       // >= L for the padding rows of a ragged last block
   bf16x8 qf[8];
   {
-    const uint16_t* qp = q + ((size_t)hq * L + qrow) * kHeadDim + hf * 8;
+    const uint16_t* qp = q + ((size_t)hq * L + min(qrow, L - 1)) * kHeadDim + hf * 8;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16);
   }
@@ -213,6 +219,7 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
   // find the first valid entry (v <= vmax) and start its K tile; vmax = u for causal
   // attention (blocks beyond the diagonal are skipped), N - 1 otherwise
   const int vmax = causal ? u : N - 1;
+  const int tail = L - (N - 1) * BLK;              // tokens in the last block (BLK unless ragged)
   int it = beg;
   int v = -1;
   while (it < end) {
@@ -279,6 +286,17 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
         for (int r = 0; r < 16; ++r) {
           const int kloc = kt * 32 + 8 * (r >> 2) + 4 * hf + (r & 3);
           if (kloc > qloc) sacc[kt][r] = -INFINITY;
+        }
+    }
+
+    // ---- keys past the end of the sequence (ragged last block) ----
+    if (v == N - 1 && tail < BLK) {
+#pragma unroll
+      for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int kloc = kt * 32 + 8 * (r >> 2) + 4 * hf + (r & 3);
+          if (kloc >= tail) sacc[kt][r] = -INFINITY;
         }
     }
 
@@ -360,6 +378,7 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
   const float inv_l = l_tot > 0.f ? 1.0f / l_tot : 0.f;
   uint16_t* op = out + ((size_t)hq * L + qrow) * kHeadDim;
+  if (qrow < L) {
 #pragma unroll
   for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
@@ -374,7 +393,8 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
       w.y = *reinterpret_cast<const uint32_t*>(&bb);
       *reinterpret_cast<uint2*>(op + d0) = w;
     }
-  if (lse != nullptr && hf == 0)
+  }
+  if (lse != nullptr && hf == 0 && qrow < L)
     lse[(size_t)hq * L + qrow] =
         l_tot > 0.f ? (m_run + log2f(l_tot)) * 0.6931471805599453f : -INFINITY;
   }  // persistent loop; the barrier at its top also orders next_item and the LDS tiles
@@ -487,10 +507,10 @@ struct AttnWs {
   size_t image, order, hist, counter, total;
 };
 static AttnWs attn_ws(const prism_params* p) {
-  const size_t N = p->seq_len / p->block;
+  const size_t N = n_blocks(p);
   AttnWs w;
   size_t off = 0;
-  w.image = off;   off = align_up(off + (size_t)p->n_kv_heads * p->seq_len * kHeadDim * 2, 256);
+  w.image = off;   off = align_up(off + (size_t)p->n_kv_heads * N * p->block * kHeadDim * 2, 256);
   w.order = off;   off = align_up(off + (size_t)p->n_kv_heads * N * sizeof(int32_t), 256);
   w.hist = off;    off = align_up(off + (kMaxBlocks + 1) * sizeof(int32_t), 256);
   w.counter = off; off = align_up(off + 8 * sizeof(int32_t), 256);
@@ -534,7 +554,7 @@ extern "C" int prism_v_image(const prism_params* params, const void* v_bf16, voi
   rc = check_image(params, v_image, v_image_bytes);
   if (rc != PRISM_OK) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  const int N = params->seq_len / params->block;
+  const int N = n_blocks(params);
   if (params->block == 128)
     hipLaunchKernelGGL(vt_image_kernel<128>, dim3(N, params->n_kv_heads), dim3(256), 0, st,
                        (const uint16_t*)v_bf16, (uint16_t*)v_image, params->seq_len, N);
@@ -555,7 +575,7 @@ extern "C" int prism_sparse_attn_pre(const prism_params* params, const void* q_b
   rc = check_image(params, v_image, v_image_bytes);
   if (rc != PRISM_OK) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  const int N = params->seq_len / params->block;
+  const int N = n_blocks(params);
   const int h = params->n_q_heads, h_kv = params->n_kv_heads, L = params->seq_len;
   const int R = h * N;
   const AttnWs W = attn_ws(params);

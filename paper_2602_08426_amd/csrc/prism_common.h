@@ -26,8 +26,7 @@ inline int check_params(const prism_params* p) {
   if (p->n_q_heads % p->n_kv_heads != 0) return PRISM_ERR_INVALID_ARG;
   if (p->head_dim != kHeadDim) return PRISM_ERR_UNSUPPORTED;
   if (p->block != 64 && p->block != 128) return PRISM_ERR_UNSUPPORTED;
-  if (p->seq_len % p->block != 0) return PRISM_ERR_UNSUPPORTED;
-  const int64_t n = p->seq_len / p->block;
+  const int64_t n = ((int64_t)p->seq_len + p->block - 1) / p->block;   // a ragged last block is allowed
   if (n > kMaxBlocks) return PRISM_ERR_UNSUPPORTED;
   // CSR offsets are int32
   const int64_t pairs = (p->flags & PRISM_FLAG_BIDIRECTIONAL) ? (int64_t)p->n_q_heads * n * n
@@ -36,6 +35,9 @@ inline int check_params(const prism_params* p) {
   if ((int64_t)p->n_q_heads * n + 1 >= (int64_t)1 << 31) return PRISM_ERR_UNSUPPORTED;
   return PRISM_OK;
 }
+
+// N = ceil(L / B) (Sec. 3.1, Eq. "mean-pooling": the last block holds the remaining tokens)
+inline int n_blocks(const prism_params* p) { return (p->seq_len + p->block - 1) / p->block; }
 
 inline int check_bands(const prism_params* p) {
   if (p->d_high < 0 || p->d_low < 0 || p->d_high > p->head_dim || p->d_low > p->head_dim)

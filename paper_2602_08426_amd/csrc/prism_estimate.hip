@@ -47,10 +47,14 @@ __global__ __launch_bounds__(256) void pool_energy_kernel(
   src += (size_t)blk * BLK * kHeadDim;
   const int c = t & 15, rg = t >> 4;
 
+  const int cnt = min(BLK, L - blk * BLK);          // tokens in this block (ragged last block)
   uint4 v[BLK / 16];
 #pragma unroll
-  for (int it = 0; it < BLK / 16; ++it)
-    v[it] = *reinterpret_cast<const uint4*>(src + (size_t)(rg + it * 16) * kHeadDim + c * 8);
+  for (int it = 0; it < BLK / 16; ++it) {
+    const int row = rg + it * 16;
+    v[it] = row < cnt ? *reinterpret_cast<const uint4*>(src + (size_t)row * kHeadDim + c * 8)
+                      : make_uint4(0u, 0u, 0u, 0u);
+  }
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int it = 0; it < BLK / 16; ++it) {
@@ -71,7 +75,7 @@ __global__ __launch_bounds__(256) void pool_energy_kernel(
     float s = 0.f;
 #pragma unroll
     for (int r = 0; r < 16; ++r) s += part[r][t];
-    const float mean = s * (1.0f / BLK);
+    const float mean = s / (float)cnt;
     // mean = hi + mid + lo exactly up to 2^-26 relative (three bf16 terms of 8 bits each)
     const uint32_t hi = float_to_bf16_bits(mean);
     const float rem1 = mean - bf16_bits_to_float(hi);
@@ -564,7 +568,7 @@ struct EstimateWs {
   size_t band[2][3], energy, inv_scale, total;
 };
 static EstimateWs estimate_ws(const prism_params* p) {
-  const size_t N = p->seq_len / p->block;
+  const size_t N = n_blocks(p);
   const size_t heads = (size_t)p->n_q_heads + p->n_kv_heads;
   EstimateWs w;
   size_t off = 0;
@@ -589,7 +593,7 @@ static BandVectors band_vectors(char* ws, const EstimateWs& L) {
 static int run_pool_and_scale(const prism_params* p, const BandMap& map, const void* q, const void* k,
                               char* ws, const EstimateWs& L, float* pooled_q, float* pooled_k,
                               float* scales, hipStream_t st) {
-  const int N = p->seq_len / p->block;
+  const int N = n_blocks(p);
   const dim3 grid(N, p->n_q_heads + p->n_kv_heads);
   const BandVectors bv = band_vectors(ws, L);
   float* energy = reinterpret_cast<float*>(ws + L.energy);
@@ -611,7 +615,7 @@ static int run_pool_and_scale(const prism_params* p, const BandMap& map, const v
 template <int MAXCH, bool DUMP>
 static int launch_select(const prism_params* p, const BandMap& map, char* ws, const EstimateWs& L,
                          uint64_t* mask_bits, int32_t* row_ptr, float* lh, float* ll, hipStream_t st) {
-  const int N = p->seq_len / p->block;
+  const int N = n_blocks(p);
   const int strips = (N + kStripRows - 1) / kStripRows;
   const size_t lds = (size_t)kStripRows * (((N + 15) / 16) * 16 + 4) * sizeof(float);
   auto kern = select_kernel<MAXCH, DUMP>;
@@ -633,7 +637,7 @@ static int launch_select(const prism_params* p, const BandMap& map, char* ws, co
 static int run_compaction(const prism_params* p, const uint64_t* mask_bits, int32_t* row_ptr,
                           int32_t* col_idx, int64_t capacity, int32_t* info, bool count_rows,
                           hipStream_t st) {
-  const int N = p->seq_len / p->block;
+  const int N = n_blocks(p);
   const int R = p->n_q_heads * N;
   const int W = (N + 63) / 64;
   if (count_rows)
@@ -695,7 +699,7 @@ extern "C" int prism_estimate_bands(const prism_params* params, const prism_band
   char* ws = static_cast<char*>(workspace);
   rc = run_pool_and_scale(params, map, q_bf16, k_bf16, ws, L, nullptr, nullptr, nullptr, st);
   if (rc != PRISM_OK) return rc;
-  const int N = params->seq_len / params->block;
+  const int N = n_blocks(params);
   rc = (N <= 1024)
            ? launch_select<16, false>(params, map, ws, L, mask_bits, row_ptr, nullptr, nullptr, st)
            : launch_select<32, false>(params, map, ws, L, mask_bits, row_ptr, nullptr, nullptr, st);
@@ -766,7 +770,7 @@ static int dense_csr(const prism_params* params, bool causal, int32_t* row_ptr, 
   int rc = check_params(params);
   if (rc != PRISM_OK) return rc;
   if (!row_ptr || !col_idx) return PRISM_ERR_INVALID_ARG;
-  const int64_t N = params->seq_len / params->block;
+  const int64_t N = n_blocks(params);
   const int64_t need = (int64_t)params->n_q_heads * (causal ? N * (N + 1) / 2 : N * N);
   if (col_capacity < need) return PRISM_ERR_INVALID_ARG;
   const int R = params->n_q_heads * (int)N;

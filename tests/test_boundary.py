@@ -55,7 +55,7 @@ def test_workspace_queries(lib):
     (dict(n_q_heads=0), -1),
     (dict(head_dim=64), -2),
     (dict(block=32), -2),
-    (dict(seq_len=1000), -2),                        # L % B
+    (dict(seq_len=0), -1),
     (dict(seq_len=128 * 4096), -2),                  # N > 2048
 ])
 def test_bad_geometry_is_rejected(lib, kw, status):

@@ -234,3 +234,58 @@ def test_batch_folded_into_heads_equals_separate_calls():
         np.testing.assert_array_equal(mf[4 * b:4 * b + 4], ms)
         np.testing.assert_array_equal(of[4 * b:4 * b + 4], os_)
         np.testing.assert_array_equal(lf[4 * b:4 * b + 4], ls)
+
+
+def _ragged_inputs(L, h, hkv, B, name="c3_llama_32k"):
+    """Structured workload generated for whole blocks, truncated to L tokens."""
+    Lfull = -(-L // B) * B
+    w = wl.small_variant(wl.WORKLOADS[name], Lfull, h, hkv, B)
+    Qb, Kb, Vb = wl.generate(w)
+    return w, tuple(np.ascontiguousarray(x[:, :L]) for x in (Qb, Kb, Vb))
+
+
+@pytest.mark.parametrize("L,h,hkv,B,flags", [
+    (128 * 9 + 37, 4, 2, 128, 0),
+    (64 * 20 + 1, 2, 1, 64, 0),                               # a single token in the last block
+    (128 * 5 + 100, 4, 2, 128, pb.PRISM_FLAG_BIDIRECTIONAL),
+    (90, 2, 2, 128, 0),                                       # one ragged block in all
+])
+def test_ragged_last_block(L, h, hkv, B, flags):
+    """N = ceil(L / B): the last block is pooled over the tokens it holds, its missing keys
+    are invisible and its missing queries are not written."""
+    print(f"case L={L} h={h}/{hkv} B={B} flags={flags}", flush=True)
+    w, (Qb, Kb, Vb) = _ragged_inputs(L, h, hkv, B)
+    causal = not (flags & pb.PRISM_FLAG_BIDIRECTIONAL)
+    N = -(-L // B)
+    p = 0.9
+    Q, K, V = orc.bf16_to_f64(Qb), orc.bf16_to_f64(Kb), orc.bf16_to_f64(Vb)
+    sel = orc.prism_select(Q, K, w.d_high, w.d_low, B, p, causal=causal)
+    params = pb.make_params(h, hkv, L, B, w.d_high, w.d_low, p, flags)
+    assert params.n_blocks == N == sel.mask.shape[1]
+    qd, kd, vd = (pb.bf16_bits_to_device(x) for x in (Qb, Kb, Vb))
+    sc = gu.gpu_block_scores(params, qd, kd)
+    np.testing.assert_allclose(sc["pooled_q"], sel.q_pooled, rtol=2e-6, atol=2e-6)
+    np.testing.assert_allclose(sc["pooled_k"], sel.k_pooled, rtol=2e-6, atol=2e-6)
+    _check_logits(sc, sel, sel.valid)
+    res = gu.gpu_estimate(params, qd, kd)
+    _check_mask(res["mask"], sel, p, 0.08)
+    _check_csr(res)
+    # attention on the GPU's own lists, plus the dense lists
+    _, rp, ci, _ = res["dev"]
+    h_, L_ = params.n_q_heads, params.seq_len
+    guard = 64                                               # rows behind the output must stay untouched
+    out = torch.full((h_ * L_ + guard, 128), float("nan"), dtype=torch.bfloat16, device="cuda")
+    lse = torch.full((h_ * L_ + guard,), float("nan"), dtype=torch.float32, device="cuda")
+    ws = pb.alloc_workspace(pb.prism_sparse_attn_workspace_bytes(params))
+    pb.prism_sparse_attn(params, qd, kd, vd, rp, ci, int(res["info"][0]), out[:h_ * L_].view(h_, L_, 128),
+                         lse[:h_ * L_].view(h_, L_), ws)
+    torch.cuda.synchronize()
+    assert torch.isnan(out[h_ * L_:].float()).all() and torch.isnan(lse[h_ * L_:]).all()
+    _compare_rows(params, out[:h_ * L_].view(h_, L_, 128), lse[:h_ * L_].view(h_, L_), Q, K, V,
+                  res["mask"], causal)
+    _, rpd, cid, _ = pb.alloc_estimate_outputs(params)
+    pb.prism_dense_csr(params, rpd, cid, cid.numel())
+    out_d, lse_d = gu.gpu_sparse_attn(params, qd, kd, vd, rpd, cid, cid.numel())
+    ref_o, ref_l = (orc.dense_causal_attention(Q, K, V) if causal else orc.dense_full_attention(Q, K, V))
+    assert np.abs(gu.bf16_out_to_f64(out_d) - ref_o).max() <= OUT_TOL
+    assert np.abs(lse_d.cpu().numpy() - ref_l).max() <= LSE_TOL
