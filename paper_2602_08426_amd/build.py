@@ -16,6 +16,8 @@ HIPCC_FLAGS = [
     # no packed-fp32 VALU code generation
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-command-line-argument",
+    # queue pulls stay plain returning atomics whose result is waited for where it is used
+    "-mllvm", "-amdgpu-atomic-optimizer-strategy=None",
 ]
 
 

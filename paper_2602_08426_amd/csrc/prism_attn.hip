@@ -17,6 +17,8 @@
 // A operand.
 #include "prism_common.h"
 
+#include <type_traits>
+
 namespace prism {
 
 // =====================================================================================
@@ -56,14 +58,18 @@ __global__ __launch_bounds__(256) void vt_image_kernel(const uint16_t* __restric
 }
 
 // =====================================================================================
-// Sparse attention kernel.  One workgroup per (q-head, q-block); BLK/32 waves of 32 queries.
+// Sparse attention kernel.  One workgroup works on one (q-head, q-block) row at a time;
+// BLK/32 waves of 32 queries.
 // LDS: K tile [BLK][128] bf16 and V^T tile [128][BLK] bf16, 16-byte chunks XOR-swizzled by
 // row so that the 16-lane column reads are conflict-free.  Tiles are copied global -> LDS
 // asynchronously, without passing through registers.
-// Loop per listed kv block (V and the next K are fetched while the MFMAs of the other
-// operand run):
-//     K(j) in LDS | start V(j) copy | S^T = K Q^T | online softmax | wait V(j) | barrier
-//     start K(j+1) copy | O^T += V^T P^T | wait K(j+1) | barrier
+// Step per listed kv block (each tile buffer is refilled as soon as its last reader is done):
+//     K(j) in LDS | start V(j) copy | S^T = K Q^T | barrier | start K(j+1) copy
+//     online softmax | wait V(j) | barrier | O^T += V^T P^T | wait K(j+1) | barrier
+// The workgroups are persistent and the stream of rows is software-pipelined as well: the
+// queue position of the row after next, the descriptor of the next row and, during the last
+// PV of a row, the Q rows and the first K tile of the next row are fetched while the current
+// row computes, so a row switch costs no exposed memory round trip.
 // =====================================================================================
 template <int BLK>
 struct AttnCfg {
@@ -120,8 +126,6 @@ template <int BLK>
 __device__ __forceinline__ void async_load_vt_tile(__amdgpu_buffer_rsrc_t rs, int tile_off, char* lds,
                                                    int t) {
   using C = AttnCfg<BLK>;
-  // wave-uniform LDS base, re-materialised here so that the per-piece M0 values are formed
-  // with scalar adds instead of being kept live (and spilled) across the whole loop
   int wave_base = __builtin_amdgcn_readfirstlane(t & ~63);
   asm volatile("" : "+s"(wave_base));
 #pragma unroll
@@ -130,13 +134,53 @@ __device__ __forceinline__ void async_load_vt_tile(__amdgpu_buffer_rsrc_t rs, in
                                              vt_piece_offset<BLK>(i * C::kThreads + t), tile_off, 0, 0);
 }
 
-__device__ __forceinline__ void wait_async_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+// Waits on the vector-memory counter, written with the builtin (immediate: vmcnt in bits 3:0,
+// expcnt = 7 and lgkmcnt = 15 meaning "no wait") rather than inline asm, so that the compiler's
+// own wait-count bookkeeping sees them: it then knows which tile copies have landed and adds no
+// conservative vmcnt(0) of its own in front of the LDS reads of a finished tile.
+__device__ __forceinline__ void wait_async_loads() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0)
+  asm volatile("" ::: "memory");
+}
+// all but the 8 youngest vector-memory operations (one tile copy = 8 per thread) are complete
+__device__ __forceinline__ void wait_async_loads_but_last_tile() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_waitcnt(0x0F78);          // vmcnt(8)
+  asm volatile("" ::: "memory");
+}
+
+// Workgroup barrier of the tile loop: this wave's LDS accesses are complete, then s_barrier.
+// Unlike __syncthreads() it carries no memory fence, so the compiler adds no wait for the global
+// loads, stores and atomics in flight (the next tile copies, the previous row's output, the
+// queue pull); the tile copies are waited for explicitly with vmcnt where their data is needed.
+__device__ __forceinline__ void tile_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// Queue entry of one row, written by queue_fill_kernel:
+//   x = q-head, y = q-block u | (first valid key block << 16), z = index of that entry in
+//   col_idx, w = end of the row's list (z == w: the row has no valid entry).
+// A workgroup's pulls p = 0, 1, 2, ... from queue `my_queue` map to the table as
+//   round = p / g, member = p % g, slot = round * n_queues + my_queue, entry = slot * g + member;
+// the queue is exhausted once round * n_queues >= n_groups, and a slot >= n_groups is a hole
+// in the last deal round.
+enum { kItemEnd = 0, kItemHole = 1, kItemRow = 2 };
+
+__device__ __forceinline__ int item_kind(int pulled, int g, int n_queues, int my_queue, int n_groups,
+                                         int* entry) {
+  const int round = pulled / g, member = pulled - round * g;
+  if ((int64_t)round * n_queues >= n_groups) return kItemEnd;
+  const int slot = round * n_queues + my_queue;
+  if (slot >= n_groups) return kItemHole;
+  *entry = slot * g + member;
+  return kItemRow;
+}
 
 template <int BLK>
 __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ vt,
-    const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx, int64_t col_count,
-    const int32_t* __restrict__ order, int32_t* __restrict__ counter,
+    const int32_t* __restrict__ col_idx, const int4* __restrict__ items, int32_t* __restrict__ counter,
     uint16_t* __restrict__ out, float* __restrict__ lse, int h, int h_kv, int L, int N,
     int causal) {
   using C = AttnCfg<BLK>;
@@ -161,7 +205,7 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
   for (int st = 0; st < KT * 2; ++st)
     voff[st] = l32 * (BLK * 2) + (((2 * st + hf) ^ (l32 & (C::kVtCpr - 1))) << 4);
 
-  // Persistent workgroups pull work from queues ordered longest list first, so that heads
+  // Persistent workgroups pull rows from queues ordered longest list first, so that heads
   // of very different density keep every CU busy until the end.  The unit of the order is the
   // GQA group (kv head, q-block): its g rows are handed out back to back to workgroups of the
   // same XCD (workgroups are dealt round-robin to the 8 XCDs, and each XCD has its own L2), so
@@ -171,233 +215,292 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
   const int n_queues = gridDim.x < 8 ? 1 : 8;
   const int my_queue = blockIdx.x % n_queues;
   const int n_groups = h_kv * N;
-  for (;;) {
-  if (t == 0) next_item = atomicAdd(counter + my_queue, 1);
-  __syncthreads();
-  const int pulled = __builtin_amdgcn_readfirstlane(next_item);   // wave-uniform from here on
-  const int round = pulled / g, member = pulled - round * g;
-  if ((int64_t)round * n_queues >= n_groups) break;               // this deal round is past the end
-  const int slot = round * n_queues + my_queue;
-  if (slot >= n_groups) continue;                                  // hole in the last deal round
-  const int group_id = __builtin_amdgcn_readfirstlane(order[slot]);
-  const int kvh = group_id / N, u = group_id - kvh * N;
-  const int hq = kvh * g + member;
-  const int row_id = hq * N + u;
-
-  // list bounds as 32-bit scalars (CSR offsets are int32; col_count is clamped to that range)
-  const int cap = col_count > 0x7fffffff ? 0x7fffffff : (int)col_count;
-  int beg = __builtin_amdgcn_readfirstlane(row_ptr[row_id]);
-  int end = __builtin_amdgcn_readfirstlane(row_ptr[row_id + 1]);
-  beg = beg < 0 ? 0 : (beg > cap ? cap : beg);
-  end = end < beg ? beg : (end > cap ? cap : end);
-
-  // K and V^T of this kv head as buffer resources (tile v starts at byte v * kTileBytes).
-  // K is the caller's tensor: rows past L in a ragged last block are outside the resource and
-  // read as zeros.  The V^T image is padded to whole blocks.
+  const int vmax_nc = N - 1;
+  const int tail = L - (N - 1) * BLK;              // tokens in the last block (BLK unless ragged)
   const uint32_t head_bytes = (uint32_t)L * kHeadDim * 2;
   const uint32_t image_head_bytes = (uint32_t)N * C::kTileBytes;
-  const __amdgpu_buffer_rsrc_t krs = make_rsrc(k + (size_t)kvh * L * kHeadDim, head_bytes);
-  const __amdgpu_buffer_rsrc_t vrs = make_rsrc(vt + (size_t)kvh * N * BLK * kHeadDim, image_head_bytes);
 
-  // Q fragments (B operand of S^T = K Q^T): query row 32*wave + l32, dims 16*ks + 8*hf ..+7
-  const int qrow = u * BLK + wave * 32 + l32;       // >= L for the padding rows of a ragged last block
-  bf16x8 qf[8];
-  {
-    const uint16_t* qp = q + ((size_t)hq * L + min(qrow, L - 1)) * kHeadDim + hf * 8;
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16);
-  }
-
-  f32x16 oacc[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) oacc[i][r] = 0.f;
-  float m_run = -INFINITY;          // running max, in units of log2: s * sm_scale
-  float l_run = 0.f;                // this lane's share of the running sum
-
-  // find the first valid entry (v <= vmax) and start its K tile; vmax = u for causal
-  // attention (blocks beyond the diagonal are skipped), N - 1 otherwise
-  const int vmax = causal ? u : N - 1;
-  const int tail = L - (N - 1) * BLK;              // tokens in the last block (BLK unless ragged)
-  int it = beg;
-  int v = -1;
-  while (it < end) {
-    v = __builtin_amdgcn_readfirstlane(col_idx[it]);
-    if (v >= 0 && v <= vmax) break;
-    ++it;
-  }
-  // The list is walked one entry ahead of its use: col_idx[it + 1] is requested here and
-  // before the MFMA phases of every block, and read only after the waits that end the block,
-  // so the latency of the index load is never on the critical path of a block.
-  int ahead = it + 1 < end ? col_idx[it + 1] : -1;
-  if (it < end) async_load_k_tile<BLK>(krs, v * C::kTileBytes, lds_k, t);
-  wait_async_loads();
+  // The queue is pulled when a workgroup is about to become free (at the top of the last
+  // step of its row), so the g rows of a GQA group still start almost together on one XCD; the
+  // pull and the read of the next row's queue entry are hidden behind that last step.
+  int lane_zero;                                     // 0, but opaque to the compiler
+  asm volatile("v_mov_b32 %0, 0" : "=v"(lane_zero));
+  if (t == 0) next_item = atomicAdd(counter + my_queue, 1);
   __syncthreads();
+  int cur_x = 0, cur_y = 0, cur_z = 0, cur_w = 0;     // the current row's queue entry, wave-uniform
+  int kind_cur;
+  {
+    int e = 0;
+    kind_cur = item_kind(__builtin_amdgcn_readfirstlane(next_item), g, n_queues, my_queue, n_groups, &e);
+    if (kind_cur == kItemRow) {
+      const int4 it0 = items[e];
+      cur_x = it0.x; cur_y = it0.y; cur_z = it0.z; cur_w = it0.w;
+    }
+  }
+  __syncthreads();
+  // requests of the last step of a row (not re-initialised per row: overwriting a register that a
+  // load in flight will write would force a wait for every older memory operation)
+  int4 item_nxt = make_int4(0, 0, 0, 0);
+  int pulled_reg = 0;
 
-  while (it < end) {
-    // next valid entry (v_next <= vmax): normally the entry fetched one block ago; entries
-    // that must be skipped (negative or beyond vmax) take the slow path
-    int nx = it + 1;
-    int v_next = __builtin_amdgcn_readfirstlane(ahead);
-    if (nx < end && !(v_next >= 0 && v_next <= vmax)) {
-      ++nx;
-      while (nx < end) {
-        v_next = __builtin_amdgcn_readfirstlane(col_idx[nx]);
-        if (v_next >= 0 && v_next <= vmax) break;
+  while (kind_cur != kItemEnd) {
+    const int hq = cur_x;
+    const int u = cur_y & 0xffff;
+    int v = (cur_y >> 16) & 0xffff;
+    int it = cur_z;
+    const int end = cur_w;
+    const bool has_work = kind_cur == kItemRow && it < end;
+    const int kvh = hq / g;
+    const int qrow = u * BLK + wave * 32 + l32;       // >= L for the padding rows of a ragged last block
+    int kind_nxt = kItemEnd;
+
+    if (!has_work) {
+      // hole in the last deal round, or a row without a valid entry (o = 0, lse = -inf): no
+      // tile work; pull the next row right away
+      if (kind_cur == kItemRow && qrow < L) {
+        uint16_t* op = out + ((size_t)hq * L + qrow) * kHeadDim + hf * 64;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) *reinterpret_cast<uint4*>(op + c * 8) = make_uint4(0u, 0u, 0u, 0u);
+        if (lse != nullptr && hf == 0) lse[(size_t)hq * L + qrow] = -INFINITY;
+      }
+      if (t == 0) next_item = atomicAdd(counter + my_queue, 1);
+      __syncthreads();
+      int e = 0;
+      kind_cur = item_kind(__builtin_amdgcn_readfirstlane(next_item), g, n_queues, my_queue, n_groups, &e);
+      if (kind_cur == kItemRow) {
+        const int4 it0 = items[e];
+        cur_x = it0.x; cur_y = it0.y; cur_z = it0.z; cur_w = it0.w;
+      }
+      __syncthreads();
+      continue;
+    }
+
+    // K and V^T of this kv head as buffer resources (tile v starts at byte v * kTileBytes).
+    // K is the caller's tensor: rows past L in a ragged last block are outside the resource and
+    // read as zeros.  The V^T image is padded to whole blocks.
+    const __amdgpu_buffer_rsrc_t krs = make_rsrc(k + (size_t)kvh * L * kHeadDim, head_bytes);
+    const __amdgpu_buffer_rsrc_t vrs = make_rsrc(vt + (size_t)kvh * N * BLK * kHeadDim, image_head_bytes);
+    const int vmax = causal ? u : vmax_nc;
+
+    // Q fragments (B operand of S^T = K Q^T): query row 32*wave + l32, dims 16*ks + 8*hf ..+7
+    bf16x8 qf[8];
+    {
+      const uint16_t* qp = q + ((size_t)hq * L + min(qrow, L - 1)) * kHeadDim + hf * 8;
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16);
+    }
+    async_load_k_tile<BLK>(krs, v * C::kTileBytes, lds_k, t);
+    wait_async_loads();
+    tile_barrier();
+
+    f32x16 oacc[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) oacc[i][r] = 0.f;
+    float m_run = -INFINITY;          // running max, in units of log2: s * sm_scale
+    float l_run = 0.f;                // this lane's share of the running sum
+    int v_next = 0;
+
+    // One step = one listed kv block.  kLast distinguishes the last step of the row: an ordinary
+    // step starts the copy of the next K tile after its S^T phase, the last one pulls the queue.
+    auto step = [&](auto last_tag) __attribute__((always_inline)) {
+      constexpr bool kLast = decltype(last_tag)::value;
+      if (kLast && t == 0) pulled_reg = atomicAdd(counter + my_queue, 1);
+
+      // ---- V(j) -> LDS, in flight during S^T and the softmax ----
+      async_load_vt_tile<BLK>(vrs, v * C::kTileBytes, lds_v, t);
+
+      // ---- S^T = K Q^T ----
+      // Flat software pipeline over the KT*8 (tile, k-step) pairs: the LDS read of step
+      // i + kDepth is issued right after the MFMA of step i, in source order.
+      f32x16 sacc[KT];
+      const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      {
+        constexpr int kSteps = KT * 8;
+        bf16x8 fr[kDepth];
+#pragma unroll
+        for (int i = 0; i < kDepth; ++i)
+          fr[i] = *reinterpret_cast<const bf16x8*>(lds_k + (i % KT) * 8192 + koff[i / KT]);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < kSteps; ++i) {
+          const int kt = i % KT, ks = i / KT;          // consecutive MFMAs: independent accumulators
+          sacc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i % kDepth], qf[ks], ks == 0 ? zero16 : sacc[kt], 0, 0, 0);
+          if (i + kDepth < kSteps) {
+            const int j = i + kDepth;
+            fr[i % kDepth] = *reinterpret_cast<const bf16x8*>(lds_k + (j % KT) * 8192 + koff[j / KT]);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+
+      // every wave is done reading K(j): K(j+1) can start now and land during softmax + PV
+      tile_barrier();
+      if (!kLast) async_load_k_tile<BLK>(krs, v_next * C::kTileBytes, lds_k, t);
+
+      // ---- causal mask inside the diagonal block ----
+      if (causal && v == u) {
+        const int qloc = wave * 32 + l32;
+#pragma unroll
+        for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int kloc = kt * 32 + 8 * (r >> 2) + 4 * hf + (r & 3);
+            if (kloc > qloc) sacc[kt][r] = -INFINITY;
+          }
+      }
+
+      // ---- keys past the end of the sequence (ragged last block) ----
+      if (v == N - 1 && tail < BLK) {
+#pragma unroll
+        for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int kloc = kt * 32 + 8 * (r >> 2) + 4 * hf + (r & 3);
+            if (kloc >= tail) sacc[kt][r] = -INFINITY;
+          }
+      }
+
+      // ---- online softmax (per query = per lane pair l, l^32) ----
+      float mx = -INFINITY;
+#pragma unroll
+      for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[kt][r]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float m_new = fmaxf(m_run, mx * sm_scale);       // finite: every query sees a key
+      if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) { // some query's max moved: rescale
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+        l_run *= alpha;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) oacc[i][r] *= alpha;
+        m_run = m_new;
+      }
+      // p = 2^(s*scale - m) as bf16 pairs (the PV operand); the row sum adds the fp32 values with
+      // plain adds: the dot-product instructions that would add the rounded pairs run on the
+      // matrix pipe and stall behind the other workgroup's MFMAs (measured: 2.2x slower there).
+      float psum0 = 0.f, psum1 = 0.f;
+      bf16x8 pf[KT][2];
+#pragma unroll
+      for (int kt = 0; kt < KT; ++kt) {
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+#pragma unroll
+          for (int j = 0; j < 8; j += 2) {
+            const float p0 = __builtin_amdgcn_exp2f(fmaf(sacc[kt][8 * s + j], sm_scale, -m_new));
+            const float p1 = __builtin_amdgcn_exp2f(fmaf(sacc[kt][8 * s + j + 1], sm_scale, -m_new));
+            const f32x2 pp = {p0, p1};
+            const bf16x2 pb = __builtin_convertvector(pp, bf16x2);
+            pf[kt][s][j] = pb[0];
+            pf[kt][s][j + 1] = pb[1];
+            psum0 += p0;
+            psum1 += p1;
+          }
+        }
+      }
+      l_run += psum0 + psum1;
+
+      if (kLast) {
+        if (t == 0) next_item = pulled_reg;         // the queue position pulled at the top of the step
+        wait_async_loads();                          // this wave's share of V(j) has landed
+      } else {
+        wait_async_loads_but_last_tile();            // ... while the 8 younger loads of K(j+1) may still be in flight
+      }
+      tile_barrier();                                // V(j) complete
+
+      if (kLast) {
+        // the next row's queue entry, read through a per-lane (vector) address so that it arrives
+        // on the vector-memory counter and is waited for after the PV phase; a scalar load would be
+        // waited for by the very next LDS read
+        int e_nxt = 0;
+        kind_nxt = item_kind(__builtin_amdgcn_readfirstlane(next_item), g, n_queues, my_queue, n_groups, &e_nxt);
+        if (kind_nxt == kItemRow) item_nxt = items[e_nxt + lane_zero];
+      }
+
+      // ---- O^T += V^T P^T ----  (same flat pipeline over the 4*KT*2 (d-tile, k-step) pairs)
+      {
+        constexpr int kPer = KT * 2;                   // k-steps per d-tile
+        constexpr int kSteps = 4 * kPer;
+        bf16x8 fr[kDepth];
+#pragma unroll
+        for (int i = 0; i < kDepth; ++i)
+          fr[i] = *reinterpret_cast<const bf16x8*>(lds_v + (i % 4) * (32 * BLK * 2) + voff[i / 4]);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < kSteps; ++i) {
+          const int dt = i % 4, st = i / 4;            // consecutive MFMAs: independent accumulators
+          oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i % kDepth], pf[st >> 1][st & 1], oacc[dt], 0, 0, 0);
+          if (i + kDepth < kSteps) {
+            const int j = i + kDepth;
+            fr[i % kDepth] = *reinterpret_cast<const bf16x8*>(lds_v + (j % 4) * (32 * BLK * 2) + voff[j / 4]);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+
+      wait_async_loads();              // this wave's share of K(j+1) (or the next row's entry) has landed
+      tile_barrier();                  // K(j+1) complete; everyone is done reading V(j)
+    };
+
+    // The list is walked one entry ahead of its use: col_idx[it + 1] is requested here and
+    // before the MFMA phases of every block, and read only after the waits that end the block,
+    // so the latency of the index load is never on the critical path of a block.
+    int ahead = it + 1 < end ? col_idx[it + 1] : -1;
+    for (;;) {
+      // next valid entry (v_next <= vmax): normally the entry fetched one block ago; entries
+      // that must be skipped (negative or beyond vmax) take the slow path
+      int nx = it + 1;
+      v_next = __builtin_amdgcn_readfirstlane(ahead);
+      if (nx < end && !(v_next >= 0 && v_next <= vmax)) {
         ++nx;
-      }
-    }
-    ahead = nx + 1 < end ? col_idx[nx + 1] : -1;
-
-    // ---- V(j) -> LDS, in flight during S^T and the softmax ----
-    async_load_vt_tile<BLK>(vrs, v * C::kTileBytes, lds_v, t);
-
-    // ---- S^T = K Q^T ----
-    // Flat software pipeline over the KT*8 (tile, k-step) pairs: the LDS read of step
-    // i + kDepth is issued right after the MFMA of step i, in source order.
-    f32x16 sacc[KT];
-    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    {
-      constexpr int kSteps = KT * 8;
-      bf16x8 fr[kDepth];
-#pragma unroll
-      for (int i = 0; i < kDepth; ++i)
-        fr[i] = *reinterpret_cast<const bf16x8*>(lds_k + (i % KT) * 8192 + koff[i / KT]);
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int i = 0; i < kSteps; ++i) {
-        const int kt = i % KT, ks = i / KT;          // consecutive MFMAs: independent accumulators
-        sacc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i % kDepth], qf[ks], ks == 0 ? zero16 : sacc[kt], 0, 0, 0);
-        if (i + kDepth < kSteps) {
-          const int j = i + kDepth;
-          fr[i % kDepth] = *reinterpret_cast<const bf16x8*>(lds_k + (j % KT) * 8192 + koff[j / KT]);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-      }
-    }
-
-    // ---- causal mask inside the diagonal block ----
-    if (causal && v == u) {
-      const int qloc = wave * 32 + l32;
-#pragma unroll
-      for (int kt = 0; kt < KT; ++kt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int kloc = kt * 32 + 8 * (r >> 2) + 4 * hf + (r & 3);
-          if (kloc > qloc) sacc[kt][r] = -INFINITY;
-        }
-    }
-
-    // ---- keys past the end of the sequence (ragged last block) ----
-    if (v == N - 1 && tail < BLK) {
-#pragma unroll
-      for (int kt = 0; kt < KT; ++kt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int kloc = kt * 32 + 8 * (r >> 2) + 4 * hf + (r & 3);
-          if (kloc >= tail) sacc[kt][r] = -INFINITY;
-        }
-    }
-
-    // ---- online softmax (per query = per lane pair l, l^32) ----
-    float mx = -INFINITY;
-#pragma unroll
-    for (int kt = 0; kt < KT; ++kt)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[kt][r]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float m_new = fmaxf(m_run, mx * sm_scale);       // finite: every query sees a key
-    if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) { // some query's max moved: rescale
-      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-      l_run *= alpha;
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[i][r] *= alpha;
-      m_run = m_new;
-    }
-    // p = 2^(s*scale - m) as bf16 pairs (the PV operand); the row sum adds the fp32 values with
-    // plain adds: the dot-product instructions that would add the rounded pairs run on the
-    // matrix pipe and stall behind the other workgroup's MFMAs (measured: 2.2x slower there).
-    float psum0 = 0.f, psum1 = 0.f;
-    bf16x8 pf[KT][2];
-#pragma unroll
-    for (int kt = 0; kt < KT; ++kt) {
-#pragma unroll
-      for (int s = 0; s < 2; ++s) {
-#pragma unroll
-        for (int j = 0; j < 8; j += 2) {
-          const float p0 = __builtin_amdgcn_exp2f(fmaf(sacc[kt][8 * s + j], sm_scale, -m_new));
-          const float p1 = __builtin_amdgcn_exp2f(fmaf(sacc[kt][8 * s + j + 1], sm_scale, -m_new));
-          const f32x2 pp = {p0, p1};
-          const bf16x2 pb = __builtin_convertvector(pp, bf16x2);
-          pf[kt][s][j] = pb[0];
-          pf[kt][s][j + 1] = pb[1];
-          psum0 += p0;
-          psum1 += p1;
+        while (nx < end) {
+          v_next = __builtin_amdgcn_readfirstlane(col_idx[nx]);
+          if (v_next >= 0 && v_next <= vmax) break;
+          ++nx;
         }
       }
+      if (nx >= end) break;
+      ahead = nx + 1 < end ? col_idx[nx + 1] : -1;
+      step(std::false_type{});
+      it = nx;
+      v = v_next;
     }
-    l_run += psum0 + psum1;
+    step(std::true_type{});
 
-    wait_async_loads();              // this wave's share of V(j) has landed
-    __syncthreads();                 // V(j) complete; everyone is done reading K(j)
-
-    // ---- K(j+1) -> LDS, in flight during PV ----
-    if (nx < end) async_load_k_tile<BLK>(krs, v_next * C::kTileBytes, lds_k, t);
-
-    // ---- O^T += V^T P^T ----  (same flat pipeline over the 4*KT*2 (d-tile, k-step) pairs)
-    {
-      constexpr int kPer = KT * 2;                   // k-steps per d-tile
-      constexpr int kSteps = 4 * kPer;
-      bf16x8 fr[kDepth];
+    // ---- epilogue: O = O^T / l, bf16, [q][d] ----
+    const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+    const float inv_l = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+    uint16_t* op = out + ((size_t)hq * L + qrow) * kHeadDim;
+    if (qrow < L) {
 #pragma unroll
-      for (int i = 0; i < kDepth; ++i)
-        fr[i] = *reinterpret_cast<const bf16x8*>(lds_v + (i % 4) * (32 * BLK * 2) + voff[i / 4]);
-      __builtin_amdgcn_sched_barrier(0);
+      for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-      for (int i = 0; i < kSteps; ++i) {
-        const int dt = i % 4, st = i / 4;            // consecutive MFMAs: independent accumulators
-        oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i % kDepth], pf[st >> 1][st & 1], oacc[dt], 0, 0, 0);
-        if (i + kDepth < kSteps) {
-          const int j = i + kDepth;
-          fr[i % kDepth] = *reinterpret_cast<const bf16x8*>(lds_v + (j % 4) * (32 * BLK * 2) + voff[j / 4]);
+        for (int gq = 0; gq < 4; ++gq) {
+          const int d0 = dt * 32 + gq * 8 + hf * 4;
+          const f32x2 a = {oacc[dt][gq * 4 + 0] * inv_l, oacc[dt][gq * 4 + 1] * inv_l};
+          const f32x2 b = {oacc[dt][gq * 4 + 2] * inv_l, oacc[dt][gq * 4 + 3] * inv_l};
+          const bf16x2 ab = __builtin_convertvector(a, bf16x2);
+          const bf16x2 bb = __builtin_convertvector(b, bf16x2);
+          uint2 w;
+          w.x = *reinterpret_cast<const uint32_t*>(&ab);
+          w.y = *reinterpret_cast<const uint32_t*>(&bb);
+          *reinterpret_cast<uint2*>(op + d0) = w;
         }
-        __builtin_amdgcn_sched_barrier(0);
-      }
     }
+    if (lse != nullptr && hf == 0 && qrow < L)
+      lse[(size_t)hq * L + qrow] =
+          l_tot > 0.f ? (m_run + log2f(l_tot)) * 0.6931471805599453f : -INFINITY;
 
-    wait_async_loads();              // this wave's share of K(j+1) has landed
-    __syncthreads();                 // K(j+1) complete; everyone is done reading V(j)
-    it = nx;
-    v = v_next;
+    // ---- the row pulled in the last step becomes the current one ----
+    kind_cur = kind_nxt;
+    cur_x = __builtin_amdgcn_readfirstlane(item_nxt.x);
+    cur_y = __builtin_amdgcn_readfirstlane(item_nxt.y);
+    cur_z = __builtin_amdgcn_readfirstlane(item_nxt.z);
+    cur_w = __builtin_amdgcn_readfirstlane(item_nxt.w);
   }
-
-  // ---- epilogue: O = O^T / l, bf16, [q][d] ----
-  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
-  const float inv_l = l_tot > 0.f ? 1.0f / l_tot : 0.f;
-  uint16_t* op = out + ((size_t)hq * L + qrow) * kHeadDim;
-  if (qrow < L) {
-#pragma unroll
-  for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-    for (int gq = 0; gq < 4; ++gq) {
-      const int d0 = dt * 32 + gq * 8 + hf * 4;
-      const f32x2 a = {oacc[dt][gq * 4 + 0] * inv_l, oacc[dt][gq * 4 + 1] * inv_l};
-      const f32x2 b = {oacc[dt][gq * 4 + 2] * inv_l, oacc[dt][gq * 4 + 3] * inv_l};
-      const bf16x2 ab = __builtin_convertvector(a, bf16x2);
-      const bf16x2 bb = __builtin_convertvector(b, bf16x2);
-      uint2 w;
-      w.x = *reinterpret_cast<const uint32_t*>(&ab);
-      w.y = *reinterpret_cast<const uint32_t*>(&bb);
-      *reinterpret_cast<uint2*>(op + d0) = w;
-    }
-  }
-  if (lse != nullptr && hf == 0 && qrow < L)
-    lse[(size_t)hq * L + qrow] =
-        l_tot > 0.f ? (m_run + log2f(l_tot)) * 0.6931471805599453f : -INFINITY;
-  }  // persistent loop; the barrier at its top also orders next_item and the LDS tiles
 }
 
 // =====================================================================================
@@ -410,10 +513,11 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
 //   queue_reset_kernel : zero the histogram and the queue counters
 //   queue_hist_kernel  : hist[bin] over all groups (LDS-private histograms, integer atomics)
 //   queue_scan_kernel  : start[bin] = number of groups in earlier bins
-//   queue_fill_kernel  : order[start[bin] + k] = group  (order inside one bin is arbitrary)
+//   queue_fill_kernel  : the group gets position pos = start[bin] + k (order inside one bin is
+//                        arbitrary) and its g rows the queue entries items[pos*g .. pos*g+g-1]
 // =====================================================================================
 struct QueueCfg {
-  int n_groups, g, N, heads_per_phase, levels, n_bins;
+  int n_groups, g, N, heads_per_phase, levels, n_bins, causal, cap;
 };
 
 __global__ __launch_bounds__(256) void queue_reset_kernel(int32_t* __restrict__ hist, int nbins,
@@ -473,10 +577,14 @@ __global__ __launch_bounds__(1024) void queue_scan_kernel(int32_t* __restrict__ 
 }
 
 // Each workgroup ranks its 256 groups per bin in LDS and reserves one range per distinct bin
-// with a single global atomic, so groups of one bin do not serialise on one address.
+// with a single global atomic, so groups of one bin do not serialise on one address.  The
+// thread of a group then writes the queue entries of its g rows: list bounds clamped to
+// [0, cap], and the first entry that names a valid key block (0 <= v <= u for causal
+// attention, 0 <= v < N otherwise).
 __global__ __launch_bounds__(256) void queue_fill_kernel(const int32_t* __restrict__ row_ptr,
+                                                         const int32_t* __restrict__ col_idx,
                                                          QueueCfg c, int32_t* __restrict__ start,
-                                                         int32_t* __restrict__ order) {
+                                                         int4* __restrict__ items) {
   __shared__ int cnt[kMaxBlocks + 1];
   for (int i = threadIdx.x; i < c.n_bins; i += 256) cnt[i] = 0;
   __syncthreads();
@@ -494,7 +602,25 @@ __global__ __launch_bounds__(256) void queue_fill_kernel(const int32_t* __restri
   __syncthreads();
   if (gid < c.n_groups) {
     const int pos = cnt[bin] + rank;
-    if (pos >= 0 && pos < c.n_groups) order[pos] = gid;
+    if (pos >= 0 && pos < c.n_groups) {
+      const int kvh = gid / c.N, u = gid - kvh * c.N;
+      const int vmax = c.causal ? u : c.N - 1;
+      for (int j = 0; j < c.g; ++j) {
+        const int hq = kvh * c.g + j;
+        const int r = hq * c.N + u;
+        int beg = row_ptr[r], end = row_ptr[r + 1];
+        beg = beg < 0 ? 0 : (beg > c.cap ? c.cap : beg);
+        end = end < beg ? beg : (end > c.cap ? c.cap : end);
+        int it = beg, v = 0;
+        while (it < end) {
+          v = col_idx[it];
+          if (v >= 0 && v <= vmax) break;
+          ++it;
+        }
+        if (it >= end) v = 0;
+        items[(size_t)pos * c.g + j] = make_int4(hq, u | (v << 16), it, end);
+      }
+    }
   }
 }
 
@@ -502,16 +628,16 @@ __global__ __launch_bounds__(256) void queue_fill_kernel(const int32_t* __restri
 
 using namespace prism;
 
-// ---- workspace layout: [ V image | order[h_kv*N] | hist[bins] | 8 queue counters ] -------------------
+// ---- workspace layout: [ V image | items[h*N] (queue entries) | hist[bins] | 8 queue counters ] ------
 struct AttnWs {
-  size_t image, order, hist, counter, total;
+  size_t image, items, hist, counter, total;
 };
 static AttnWs attn_ws(const prism_params* p) {
   const size_t N = n_blocks(p);
   AttnWs w;
   size_t off = 0;
   w.image = off;   off = align_up(off + (size_t)p->n_kv_heads * N * p->block * kHeadDim * 2, 256);
-  w.order = off;   off = align_up(off + (size_t)p->n_kv_heads * N * sizeof(int32_t), 256);
+  w.items = off;   off = align_up(off + (size_t)p->n_q_heads * N * sizeof(int4), 256);
   w.hist = off;    off = align_up(off + (kMaxBlocks + 1) * sizeof(int32_t), 256);
   w.counter = off; off = align_up(off + 8 * sizeof(int32_t), 256);
   w.total = off;
@@ -580,7 +706,7 @@ extern "C" int prism_sparse_attn_pre(const prism_params* params, const void* q_b
   const int R = h * N;
   const AttnWs W = attn_ws(params);
   char* ws = static_cast<char*>(v_image);
-  int32_t* order = reinterpret_cast<int32_t*>(ws + W.order);
+  int4* items = reinterpret_cast<int4*>(ws + W.items);
   int32_t* hist = reinterpret_cast<int32_t*>(ws + W.hist);
   int32_t* counter = reinterpret_cast<int32_t*>(ws + W.counter);
   // resident workgroups per CU: 64 KB of LDS and 4 waves each at B = 128, half of that at B = 64
@@ -602,23 +728,25 @@ extern "C" int prism_sparse_attn_pre(const prism_params* params, const void* q_b
     qc.levels = 2;
   }
   qc.n_bins = ((h_kv + qc.heads_per_phase - 1) / qc.heads_per_phase) * qc.levels;
+  qc.causal = (params->flags & PRISM_FLAG_BIDIRECTIONAL) ? 0 : 1;
+  qc.cap = col_count > 0x7fffffff ? 0x7fffffff : (int)col_count;     // CSR offsets are int32
 
   hipLaunchKernelGGL(queue_reset_kernel, dim3((qc.n_bins + 255) / 256), dim3(256), 0, st, hist,
                      qc.n_bins, counter);
   hipLaunchKernelGGL(queue_hist_kernel, dim3(64), dim3(256), 0, st, row_ptr, qc, hist);
   hipLaunchKernelGGL(queue_scan_kernel, dim3(1), dim3(1024), 0, st, hist, qc.n_bins);
-  hipLaunchKernelGGL(queue_fill_kernel, dim3((qc.n_groups + 255) / 256), dim3(256), 0, st, row_ptr, qc,
-                     hist, order);
-  const int causal = (params->flags & PRISM_FLAG_BIDIRECTIONAL) ? 0 : 1;
+  hipLaunchKernelGGL(queue_fill_kernel, dim3((qc.n_groups + 255) / 256), dim3(256), 0, st, row_ptr,
+                     col_idx, qc, hist, items);
+  const int causal = qc.causal;
   if (params->block == 128)
     hipLaunchKernelGGL(sparse_attn_kernel<128>, dim3(grid), dim3(AttnCfg<128>::kThreads), 0, st,
                        (const uint16_t*)q_bf16, (const uint16_t*)k_bf16, (const uint16_t*)v_image,
-                       row_ptr, col_idx, col_count, order, counter, (uint16_t*)out_bf16, lse, h,
+                       col_idx, items, counter, (uint16_t*)out_bf16, lse, h,
                        h_kv, L, N, causal);
   else
     hipLaunchKernelGGL(sparse_attn_kernel<64>, dim3(grid), dim3(AttnCfg<64>::kThreads), 0, st,
                        (const uint16_t*)q_bf16, (const uint16_t*)k_bf16, (const uint16_t*)v_image,
-                       row_ptr, col_idx, col_count, order, counter, (uint16_t*)out_bf16, lse, h,
+                       col_idx, items, counter, (uint16_t*)out_bf16, lse, h,
                        h_kv, L, N, causal);
   return launch_status();
 }
