@@ -132,6 +132,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c4_llama_128k")
     ap.add_argument("--dense-reps", type=int, default=2)
+    ap.add_argument("--stream-reps", type=int, default=3,
+                    help="repetitions of the attention kernel with its arithmetic left out (memory side alone)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--gen-threads", type=int, default=16)
     ap.add_argument("--estimate-curve", action="store_true",
@@ -223,6 +225,24 @@ def main() -> int:
         del rp_d, ci_d, out_d
         log(f"dense causal (same kernel, all-ones lists) {ms_dense:.3f} ms")
 
+    # memory side alone: the same kernel with its arithmetic left out (tile copies, waits, queue)
+    ms_stream = None
+    if args.stream_reps > 0:
+        p_stream = pb.make_params(h, hkv, L, B, w.d_high, w.d_low, w.top_p, flags=pb.PRISM_FLAG_STREAM_ONLY)
+        out_s = torch.empty_like(q)
+        pb.prism_sparse_attn_pre(p_stream, q, k, v_image, row_ptr, col_idx, pairs, out_s, None)   # warm-up
+        torch.cuda.synchronize()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+               for _ in range(args.stream_reps)]
+        for a, b in evs:
+            a.record(stream)
+            pb.prism_sparse_attn_pre(p_stream, q, k, v_image, row_ptr, col_idx, pairs, out_s, None)
+            b.record(stream)
+        torch.cuda.synchronize()
+        ms_stream = float(np.mean([a.elapsed_time(b) for a, b in evs]))
+        del out_s
+        log(f"sparse attention, tile streaming only (no arithmetic) {ms_stream:.3f} ms")
+
     if args.calibrate_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)
         dst = torch.empty_like(src)
@@ -237,6 +257,10 @@ def main() -> int:
     density = nnz / pairs
     eff_tflops = flop_dense / (ms_step * 1e-3) / 1e12
     exec_tflops = flop_exec / (ms_attn * 1e-3) / 1e12
+    # bytes the attention kernel has to move when no tile is reused: K and V^T tile per listed
+    # block, Q rows in and O rows out once per (head, q-block)
+    attn_bytes = nnz * 2 * B * d * 2 + 2 * Qb.nbytes
+    attn_gbs = attn_bytes / (ms_attn * 1e-3) / 1e9
     est_bytes = (Qb.nbytes + Kb.nbytes)
     est_gbs = est_bytes / (ms_est * 1e-3) / 1e9
 
@@ -251,6 +275,7 @@ def main() -> int:
         "detail": {
             "ms_estimate": round(ms_est, 4), "ms_v_image": round(ms_vimg, 4),
             "ms_sparse_attn": round(ms_attn, 4),
+            "ms_sparse_attn_stream_only": None if ms_stream is None else round(ms_stream, 4),
             "ms_dense_same_kernel": None if ms_dense is None else round(ms_dense, 3),
             "speedup_vs_dense": None if ms_dense is None else round(ms_dense / ms_step, 3),
             "estimate_over_dense": None if ms_dense is None else round(ms_est / ms_dense, 5),
@@ -260,10 +285,18 @@ def main() -> int:
             "estimate_gbs": round(est_gbs, 1), "estimate_frac_hbm_peak": round(est_gbs / PEAK_HBM_GBS, 4),
             "paper_context": "paper reports up to 5.1x over FlashAttention-2 at 128K on one H100 (different hardware)",
         },
-        "roofline": {"kernel": "sparse_attn_kernel<128>", "bound": "mfma", "achieved": round(exec_tflops, 2),
+        "roofline": {"kernel": f"sparse_attn_kernel<{B}, false>", "bound": "mfma", "achieved": round(exec_tflops, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(exec_tflops / PEAK_BF16_TFLOPS, 4),
                      "traffic": profiled_traffic(w.name, "sparse_attn_kernel"),
                      "flops_per_launch": flop_exec, "avg_launch_ms": round(ms_attn, 4)},
+        # the same kernel against the memory roof: without tile reuse it has 128 flop per byte,
+        # below the machine's ridge (2500 TFLOP/s / 8 TB/s = 312 flop/B)
+        "roofline_sparse_attn_memory": {"kernel": f"sparse_attn_kernel<{B}, false>", "bound": "hbm",
+                                        "achieved": round(attn_gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                                        "frac": round(attn_gbs / PEAK_HBM_GBS, 4),
+                                        "traffic": profiled_traffic(w.name, "sparse_attn_kernel"),
+                                        "bytes_per_launch": attn_bytes, "avg_launch_ms": round(ms_attn, 4),
+                                        "stream_only_ms": None if ms_stream is None else round(ms_stream, 4)},
         "roofline_estimate": {"kernel": "prism_estimate (5 kernels; pool_energy_kernel carries the bytes)",
                               "bound": "hbm", "achieved": round(est_gbs, 1), "peak": PEAK_HBM_GBS,
                               "unit": "GB/s", "frac": round(est_gbs / PEAK_HBM_GBS, 4),

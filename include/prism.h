@@ -51,6 +51,10 @@ typedef enum prism_status {
                                           listed block */
 #define PRISM_FLAG_FORCE_DIAGONAL 4u   /* extra, not in the paper: block u of row u is always selected */
 #define PRISM_FLAG_FORCE_SINK     8u   /* extra, not in the paper: block 0 is always selected */
+#define PRISM_FLAG_STREAM_ONLY 0x40000000u /* measurement aid for prism_sparse_attn(_pre): run the
+                                          kernel's K / V^T tile copies, waits and scheduling without
+                                          its arithmetic; the outputs are then meaningless.  Shows how
+                                          long the memory side of a call takes on its own. */
 
 /* Problem description shared by all calls (plain data, host memory). */
 typedef struct prism_params {

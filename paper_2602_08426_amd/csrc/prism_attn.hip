@@ -177,12 +177,15 @@ __device__ __forceinline__ int item_kind(int pulled, int g, int n_queues, int my
   return kItemRow;
 }
 
-template <int BLK>
+// kStreamOnly (PRISM_FLAG_STREAM_ONLY): the same tile copies, waits, barriers and queue traffic
+// with the arithmetic left out; it measures how long the memory side of a call takes alone.
+template <int BLK, bool kStreamOnly>
 __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ vt,
     const int32_t* __restrict__ col_idx, const int4* __restrict__ items, int32_t* __restrict__ counter,
     uint16_t* __restrict__ out, float* __restrict__ lse, int h, int h_kv, int L, int N,
     int causal) {
+#if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the kernel's signature
   using C = AttnCfg<BLK>;
   constexpr int KT = BLK / 32;                       // 32-key tiles per kv block
   __shared__ __attribute__((aligned(16))) char lds_k[C::kTileBytes];
@@ -311,10 +314,11 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
       // ---- V(j) -> LDS, in flight during S^T and the softmax ----
       async_load_vt_tile<BLK>(vrs, v * C::kTileBytes, lds_v, t);
 
+      f32x16 sacc[KT];
+      if (!kStreamOnly) {
       // ---- S^T = K Q^T ----
       // Flat software pipeline over the KT*8 (tile, k-step) pairs: the LDS read of step
       // i + kDepth is issued right after the MFMA of step i, in source order.
-      f32x16 sacc[KT];
       const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
       {
         constexpr int kSteps = KT * 8;
@@ -335,10 +339,14 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
         }
       }
 
+      }
+
       // every wave is done reading K(j): K(j+1) can start now and land during softmax + PV
       tile_barrier();
       if (!kLast) async_load_k_tile<BLK>(krs, v_next * C::kTileBytes, lds_k, t);
 
+      bf16x8 pf[KT][2];
+      if (!kStreamOnly) {
       // ---- causal mask inside the diagonal block ----
       if (causal && v == u) {
         const int qloc = wave * 32 + l32;
@@ -383,7 +391,6 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
       // plain adds: the dot-product instructions that would add the rounded pairs run on the
       // matrix pipe and stall behind the other workgroup's MFMAs (measured: 2.2x slower there).
       float psum0 = 0.f, psum1 = 0.f;
-      bf16x8 pf[KT][2];
 #pragma unroll
       for (int kt = 0; kt < KT; ++kt) {
 #pragma unroll
@@ -403,6 +410,8 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
       }
       l_run += psum0 + psum1;
 
+      }
+
       if (kLast) {
         if (t == 0) next_item = pulled_reg;         // the queue position pulled at the top of the step
         wait_async_loads();                          // this wave's share of V(j) has landed
@@ -420,6 +429,7 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
         if (kind_nxt == kItemRow) item_nxt = items[e_nxt + lane_zero];
       }
 
+      if (!kStreamOnly) {
       // ---- O^T += V^T P^T ----  (same flat pipeline over the 4*KT*2 (d-tile, k-step) pairs)
       {
         constexpr int kPer = KT * 2;                   // k-steps per d-tile
@@ -439,6 +449,8 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
           }
           __builtin_amdgcn_sched_barrier(0);
         }
+      }
+
       }
 
       wait_async_loads();              // this wave's share of K(j+1) (or the next row's entry) has landed
@@ -501,6 +513,7 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
     cur_z = __builtin_amdgcn_readfirstlane(item_nxt.z);
     cur_w = __builtin_amdgcn_readfirstlane(item_nxt.w);
   }
+#endif
 }
 
 // =====================================================================================
@@ -738,16 +751,29 @@ extern "C" int prism_sparse_attn_pre(const prism_params* params, const void* q_b
   hipLaunchKernelGGL(queue_fill_kernel, dim3((qc.n_groups + 255) / 256), dim3(256), 0, st, row_ptr,
                      col_idx, qc, hist, items);
   const int causal = qc.causal;
-  if (params->block == 128)
-    hipLaunchKernelGGL(sparse_attn_kernel<128>, dim3(grid), dim3(AttnCfg<128>::kThreads), 0, st,
-                       (const uint16_t*)q_bf16, (const uint16_t*)k_bf16, (const uint16_t*)v_image,
-                       col_idx, items, counter, (uint16_t*)out_bf16, lse, h,
-                       h_kv, L, N, causal);
-  else
-    hipLaunchKernelGGL(sparse_attn_kernel<64>, dim3(grid), dim3(AttnCfg<64>::kThreads), 0, st,
-                       (const uint16_t*)q_bf16, (const uint16_t*)k_bf16, (const uint16_t*)v_image,
-                       col_idx, items, counter, (uint16_t*)out_bf16, lse, h,
-                       h_kv, L, N, causal);
+  const bool stream_only = (params->flags & PRISM_FLAG_STREAM_ONLY) != 0;
+  const dim3 grid3(grid);
+  const uint16_t* qp = (const uint16_t*)q_bf16;
+  const uint16_t* kp = (const uint16_t*)k_bf16;
+  const uint16_t* vp = (const uint16_t*)v_image;
+  uint16_t* op = (uint16_t*)out_bf16;
+  if (params->block == 128) {
+    const dim3 block3(AttnCfg<128>::kThreads);
+    if (stream_only)
+      hipLaunchKernelGGL((sparse_attn_kernel<128, true>), grid3, block3, 0, st, qp, kp, vp, col_idx, items,
+                         counter, op, lse, h, h_kv, L, N, causal);
+    else
+      hipLaunchKernelGGL((sparse_attn_kernel<128, false>), grid3, block3, 0, st, qp, kp, vp, col_idx, items,
+                         counter, op, lse, h, h_kv, L, N, causal);
+  } else {
+    const dim3 block3(AttnCfg<64>::kThreads);
+    if (stream_only)
+      hipLaunchKernelGGL((sparse_attn_kernel<64, true>), grid3, block3, 0, st, qp, kp, vp, col_idx, items,
+                         counter, op, lse, h, h_kv, L, N, causal);
+    else
+      hipLaunchKernelGGL((sparse_attn_kernel<64, false>), grid3, block3, 0, st, qp, kp, vp, col_idx, items,
+                         counter, op, lse, h, h_kv, L, N, causal);
+  }
   return launch_status();
 }
 
