@@ -289,3 +289,32 @@ def test_ragged_last_block(L, h, hkv, B, flags):
     ref_o, ref_l = (orc.dense_causal_attention(Q, K, V) if causal else orc.dense_full_attention(Q, K, V))
     assert np.abs(gu.bf16_out_to_f64(out_d) - ref_o).max() <= OUT_TOL
     assert np.abs(lse_d.cpu().numpy() - ref_l).max() <= LSE_TOL
+
+
+def test_stream_only_flag_runs_and_leaves_later_calls_exact():
+    """PRISM_FLAG_STREAM_ONLY is a measurement aid: the call must complete (same tile copies and
+    queue traffic, no arithmetic) and a following ordinary call through the same workspace must
+    give bitwise the result it gave before."""
+    rng = np.random.default_rng(21)
+    h, hkv, L, B = 4, 2, 128 * 9, 128
+    Qb = wl.f32_to_bf16_bits(rng.standard_normal((h, L, 128)).astype(np.float32))
+    Kb = wl.f32_to_bf16_bits(rng.standard_normal((hkv, L, 128)).astype(np.float32))
+    Vb = wl.f32_to_bf16_bits(rng.standard_normal((hkv, L, 128)).astype(np.float32))
+    N = L // B
+    mask = np.tril(rng.random((h, N, N)) < 0.5)
+    rp, ci = orc.mask_to_csr(mask)
+    rp_d, ci_d, cnt = gu.csr_to_device(rp, ci)
+    qd, kd, vd = (pb.bf16_bits_to_device(x) for x in (Qb, Kb, Vb))
+    params = pb.make_params(h, hkv, L, B)
+    ws = pb.alloc_workspace(pb.prism_sparse_attn_workspace_bytes(params))
+    out0 = torch.empty_like(qd)
+    pb.prism_sparse_attn(params, qd, kd, vd, rp_d, ci_d, cnt, out0, None, ws)
+    torch.cuda.synchronize()
+    p_stream = pb.make_params(h, hkv, L, B, flags=pb.PRISM_FLAG_STREAM_ONLY)
+    scratch = torch.empty_like(qd)
+    pb.prism_sparse_attn(p_stream, qd, kd, vd, rp_d, ci_d, cnt, scratch, None, ws)
+    torch.cuda.synchronize()
+    out1 = torch.empty_like(qd)
+    pb.prism_sparse_attn(params, qd, kd, vd, rp_d, ci_d, cnt, out1, None, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(out0.view(torch.int16), out1.view(torch.int16))
