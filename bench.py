@@ -132,6 +132,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c4_llama_128k")
     ap.add_argument("--dense-reps", type=int, default=2)
+    ap.add_argument("--graph-reps", type=int, default=10,
+                    help="replays of the step captured in a HIP graph (0 = skip)")
     ap.add_argument("--stream-reps", type=int, default=3,
                     help="repetitions of the attention kernel with its arithmetic left out (memory side alone)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -205,6 +207,29 @@ def main() -> int:
     ms_attn = float(np.mean([e[2].elapsed_time(e[3]) for e in events]))
     log(f"step {ms_step:.3f} ms  (estimate {ms_est:.3f}, v_image {ms_vimg:.3f}, sparse attention {ms_attn:.3f})")
 
+    # the same step replayed from a HIP graph (launch overhead of the ~11 kernels taken out; matters
+    # for the short workloads only)
+    ms_graph = None
+    if args.graph_reps > 0:
+        side = torch.cuda.Stream()
+        side.wait_stream(stream)
+        with torch.cuda.stream(side):
+            step()
+        stream.wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.graph_reps):
+            graph.replay()
+        torch.cuda.synchronize()
+        ms_graph = (time.perf_counter() - t0) * 1e3 / args.graph_reps
+        del graph
+        log(f"step replayed from a HIP graph {ms_graph:.3f} ms")
+
     # dense baseline: the same attention kernel over the all-ones causal lists
     ms_dense = None
     if args.dense_reps > 0:
@@ -275,6 +300,7 @@ def main() -> int:
         "detail": {
             "ms_estimate": round(ms_est, 4), "ms_v_image": round(ms_vimg, 4),
             "ms_sparse_attn": round(ms_attn, 4),
+            "ms_per_step_hip_graph": None if ms_graph is None else round(ms_graph, 4),
             "ms_sparse_attn_stream_only": None if ms_stream is None else round(ms_stream, 4),
             "ms_dense_same_kernel": None if ms_dense is None else round(ms_dense, 3),
             "speedup_vs_dense": None if ms_dense is None else round(ms_dense / ms_step, 3),

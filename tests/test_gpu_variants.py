@@ -318,3 +318,56 @@ def test_stream_only_flag_runs_and_leaves_later_calls_exact():
     pb.prism_sparse_attn(params, qd, kd, vd, rp_d, ci_d, cnt, out1, None, ws)
     torch.cuda.synchronize()
     assert torch.equal(out0.view(torch.int16), out1.view(torch.int16))
+
+
+def test_hip_graph_replays_match_eager_calls():
+    """No entry point allocates, synchronises or records a memset, so a caller can capture
+    estimate -> V image -> attention in a HIP graph.  Every replay (with eager work and
+    synchronisations between them, and new input values in the captured buffers) must give
+    bitwise what the eager calls give on the same inputs."""
+    w = wl.small_variant(wl.WORKLOADS["c2_llama_8k"], 2048, 8, 2)
+    params = gu.params_for(w)
+    inputs = []
+    for seed in (w.seed, w.seed + 1, w.seed + 2):
+        Qb, Kb, Vb = wl.generate(dataclasses.replace(w, seed=seed))
+        inputs.append(tuple(pb.bf16_bits_to_device(x) for x in (Qb, Kb, Vb)))
+    q, k, v = (torch.empty_like(x) for x in inputs[0])
+    mask_bits, row_ptr, col_idx, info = pb.alloc_estimate_outputs(params)
+    cap = col_idx.numel()
+    ws_e = pb.alloc_workspace(pb.prism_estimate_workspace_bytes(params))
+    ws_a = pb.alloc_workspace(pb.prism_sparse_attn_workspace_bytes(params))
+    out = torch.empty_like(q)
+    lse = torch.empty((w.n_q_heads, w.seq_len), dtype=torch.float32, device="cuda")
+
+    def run():
+        pb.prism_estimate(params, q, k, mask_bits, row_ptr, col_idx, cap, info, ws_e)
+        pb.prism_v_image(params, v, ws_a)
+        pb.prism_sparse_attn_pre(params, q, k, ws_a, row_ptr, col_idx, cap, out, lse)
+
+    eager = []
+    for qi, ki, vi in inputs:
+        q.copy_(qi); k.copy_(ki); v.copy_(vi)
+        run()
+        torch.cuda.synchronize()
+        eager.append((out.clone(), lse.clone(), mask_bits.clone(), int(info[0].item())))
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run()                                   # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run()
+    for rep in range(2):
+        for (qi, ki, vi), (o_ref, l_ref, m_ref, nnz_ref) in zip(inputs, eager):
+            q.copy_(qi); k.copy_(ki); v.copy_(vi)
+            out.zero_(); lse.zero_(); mask_bits.zero_()        # eager work between the replays
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert int(info[0].item()) == nnz_ref
+            assert torch.equal(mask_bits, m_ref)
+            assert torch.equal(out.view(torch.int16), o_ref.view(torch.int16))
+            assert torch.equal(lse, l_ref)
