@@ -135,6 +135,44 @@ int prism_estimate_bands(const prism_params* params, const prism_bands* bands /*
                          int32_t* info,
                          void* workspace, size_t workspace_bytes, void* stream);
 
+/* ------------------------------------------------------------------------------------
+ * Estimation fused with the producer of the post-RoPE tensors.
+ *
+ * q_in / k_in hold the vectors BEFORE the rotary embedding.  Feature pair j = dims (2j, 2j+1)
+ * of token n is rotated by the angle (position_offset + n) * theta_j, theta_j = base^(-2j/d)
+ * (Sec. 3.1 "Spectral Structure of RoPE"):
+ *      x' = x cos(a) - y sin(a),   y' = x sin(a) + y cos(a),
+ * rounded to bf16 and written to q_out / k_out (same layouts; q_out may be q_in and k_out may be
+ * k_in: the rotation is then done in place).  The same pass pools the rounded values, so the
+ * masks and lists are exactly those prism_estimate_bands(q_out, k_out) would give, without
+ * reading the tensors a second time.  With yarn_native_len != 0 the frequencies follow the
+ * NTK-by-parts map of App. "Compatibility with YaRN":
+ *      theta'_j = (1 - gamma_j) theta_j / yarn_scale + gamma_j theta_j,
+ *      gamma_j = clamp((r_j - yarn_alpha) / (yarn_beta - yarn_alpha), 0, 1),
+ *      r_j = yarn_native_len * theta_j / (2 pi).
+ * The angle is formed and reduced in double precision; cos and sin are evaluated in fp32.
+ * `bands` may be NULL (the bands of params->d_high / d_low).  Outputs, workspace and errors as
+ * for prism_estimate; additionally PRISM_ERR_INVALID_ARG for base <= 1, a negative position
+ * offset, yarn_scale < 1 or yarn_beta <= yarn_alpha.
+ * ---------------------------------------------------------------------------------- */
+typedef struct prism_rope {
+  double  base;              /* b                                                        */
+  int32_t position_offset;   /* position of token 0                                      */
+  int32_t yarn_native_len;   /* L of r_j; 0 = plain RoPE (the yarn_* fields are ignored) */
+  double  yarn_scale;        /* s >= 1                                                   */
+  double  yarn_alpha;        /* 1 in the paper                                           */
+  double  yarn_beta;         /* 32 in the paper                                          */
+} prism_rope;
+
+int prism_rope_estimate(const prism_params* params, const prism_rope* rope /* host */,
+                        const prism_bands* bands /* host, may be NULL */,
+                        const void* q_in_bf16, const void* k_in_bf16,
+                        void* q_out_bf16, void* k_out_bf16,
+                        uint64_t* mask_bits, int32_t* row_ptr,
+                        int32_t* col_idx, int64_t col_capacity,
+                        int32_t* info,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
 /* Same computation as prism_estimate up to the block scores, for inspection at small
  * sizes: writes the pooled vectors, the two scales sqrt(d_z)*tau_z and the dual-band
  * logits (Sec. 3.4, step "Dual-Band Scoring").  Any output pointer may be NULL.

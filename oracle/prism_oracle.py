@@ -39,6 +39,9 @@ Readings taken where the paper is silent (all listed in the design notes):
   - force_diagonal / force_sink are optional extras (not in the paper): after the
     union, block u (resp. block 0) of every row is switched on.
 
+rope_frequencies / apply_rope restate Sec. 3.1 and the YaRN appendix; they are pinned by
+the zone boundaries the appendix prints, rotation invariants and the Dirichlet closed form.
+
 Pins (tests/test_oracle_*.py): Dirichlet-kernel closed form for pooled RoPE
 content (Eq. "attenuation"), printed cutoff dimensions, 1/sqrt(B) residual,
 tau = 1 when a band is the full head, brute-force top-p on tiny rows, naive
@@ -63,6 +66,62 @@ def bf16_to_f64(bits: np.ndarray) -> np.ndarray:
     if b.dtype != np.uint16:
         raise TypeError("expected uint16 bf16 bit patterns")
     return (b.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+
+
+def f64_to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    """Round finite fp64 values to bf16 (round to nearest, ties to even) and return the bit
+    patterns.  Done directly on the fp64 value: the upper 16 bits of the fp32 pattern of the
+    nearest bf16, found by comparing with the two neighbouring bf16 values."""
+    x = np.asarray(x, dtype=np.float64)
+    f = x.astype(np.float32)                                    # only used to locate a neighbour
+    lo_bits = f.view(np.uint32) & np.uint32(0xFFFF0000)         # truncation toward zero
+    lo = lo_bits.view(np.float32).astype(np.float64)
+    # fp32 rounding may have crossed a bf16 boundary away from zero; step back if so
+    over = np.abs(lo) > np.abs(x)
+    lo_bits = np.where(over, lo_bits - np.uint32(0x10000), lo_bits).astype(np.uint32)
+    lo = lo_bits.view(np.float32).astype(np.float64)
+    hi_bits = (lo_bits + np.uint32(0x10000)).astype(np.uint32)
+    hi = hi_bits.view(np.float32).astype(np.float64)
+    d_lo, d_hi = np.abs(x - lo), np.abs(hi - x)
+    even_lo = ((lo_bits >> np.uint32(16)) & np.uint32(1)) == 0
+    take_hi = (d_hi < d_lo) | ((d_hi == d_lo) & ~even_lo)
+    return (np.where(take_hi, hi_bits, lo_bits) >> np.uint32(16)).astype(np.uint16)
+
+
+# --------------------------------------------------------------------------- #
+# Rotary position embedding (Sec. 3.1 "Spectral Structure of RoPE") and the YaRN
+# frequency map (App. "Compatibility with YaRN") — used to check the library's fused
+# RoPE + pooling producer
+# --------------------------------------------------------------------------- #
+def rope_frequencies(d: int, base: float,
+                     yarn: Optional[Tuple[int, float, float, float]] = None) -> np.ndarray:
+    """theta_j = base^(-2j/d) for feature pair j = 0 .. d/2-1 (Sec. 3.1).  With
+    yarn = (L, s, alpha, beta): theta'_j = (1 - gamma_j) theta_j / s + gamma_j theta_j where
+    gamma_j is 1 for r_j > beta, 0 for r_j < alpha and (r_j - alpha) / (beta - alpha) between,
+    r_j = L theta_j / (2 pi) (App. "Compatibility with YaRN", NTK-by-parts interpolation)."""
+    j = np.arange(d // 2, dtype=np.float64)
+    theta = np.power(float(base), -2.0 * j / d)
+    if yarn is None:
+        return theta
+    L, s, alpha, beta = yarn
+    r = L * theta / (2.0 * np.pi)
+    gamma = np.where(r > beta, 1.0, np.where(r < alpha, 0.0, (r - alpha) / (beta - alpha)))
+    return (1.0 - gamma) * theta / s + gamma * theta
+
+
+def apply_rope(X: np.ndarray, theta: np.ndarray, position_offset: int = 0) -> np.ndarray:
+    """X [..., L, d] -> rotated copy: feature pair j = dims (2j, 2j+1) of the token at position
+    n = position_offset + (index along L), read as the complex number x + i y, is multiplied by
+    exp(i n theta_j) (Sec. 3.1: x_n^(j) = x_nope^(j) e^{i n theta_j})."""
+    X = np.asarray(X, dtype=np.float64)
+    L, d = X.shape[-2], X.shape[-1]
+    n = position_offset + np.arange(L, dtype=np.float64)
+    z = X[..., 0::2] + 1j * X[..., 1::2]
+    z = z * np.exp(1j * n[:, None] * np.asarray(theta, dtype=np.float64)[None, :])
+    out = np.empty_like(X)
+    out[..., 0::2] = z.real
+    out[..., 1::2] = z.imag
+    return out
 
 
 # --------------------------------------------------------------------------- #

@@ -55,8 +55,14 @@ class prism_bands(ctypes.Structure):
     _fields_ = [("high", prism_band), ("low", prism_band)]
 
 
+class prism_rope(ctypes.Structure):
+    _fields_ = [("base", ctypes.c_double), ("position_offset", ctypes.c_int32),
+                ("yarn_native_len", ctypes.c_int32), ("yarn_scale", ctypes.c_double),
+                ("yarn_alpha", ctypes.c_double), ("yarn_beta", ctypes.c_double)]
+
+
 EXPORTS = ("prism_version", "prism_status_string", "prism_estimate_workspace_bytes",
-           "prism_estimate", "prism_estimate_bands", "prism_block_scores",
+           "prism_estimate", "prism_estimate_bands", "prism_rope_estimate", "prism_block_scores",
            "prism_block_scores_bands", "prism_mask_to_csr", "prism_causal_csr", "prism_dense_csr",
            "prism_sparse_attn_workspace_bytes", "prism_sparse_attn", "prism_v_image",
            "prism_sparse_attn_pre")
@@ -80,6 +86,8 @@ def _load() -> ctypes.CDLL:
     lib.prism_estimate_workspace_bytes.argtypes = [P, ctypes.POINTER(sz)]
     lib.prism_estimate.argtypes = [P, vp, vp, vp, vp, vp, i64, vp, vp, sz, vp]
     lib.prism_estimate_bands.argtypes = [P, PB, vp, vp, vp, vp, vp, i64, vp, vp, sz, vp]
+    lib.prism_rope_estimate.argtypes = [P, ctypes.POINTER(prism_rope), PB, vp, vp, vp, vp, vp, vp, vp,
+                                        i64, vp, vp, sz, vp]
     lib.prism_block_scores.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.prism_block_scores_bands.argtypes = [P, PB, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.prism_dense_csr.argtypes = [P, vp, vp, i64, vp]
@@ -187,6 +195,23 @@ def prism_estimate_bands(params: prism_params, bands: prism_bands, q: torch.Tens
                                         _ptr(mask_bits), _ptr(row_ptr), _ptr(col_idx), col_capacity,
                                         _ptr(info), _ptr(workspace), workspace.numel(), _stream()),
            "prism_estimate_bands")
+
+
+def make_rope(base: float, position_offset: int = 0, yarn_native_len: int = 0, yarn_scale: float = 1.0,
+              yarn_alpha: float = 1.0, yarn_beta: float = 32.0) -> prism_rope:
+    return prism_rope(base, position_offset, yarn_native_len, yarn_scale, yarn_alpha, yarn_beta)
+
+
+def prism_rope_estimate(params: prism_params, rope: prism_rope, bands: Optional[prism_bands],
+                        q_in: torch.Tensor, k_in: torch.Tensor, q_out: torch.Tensor, k_out: torch.Tensor,
+                        mask_bits: torch.Tensor, row_ptr: torch.Tensor, col_idx: torch.Tensor,
+                        col_capacity: int, info: torch.Tensor, workspace: torch.Tensor) -> None:
+    _check(_load().prism_rope_estimate(ctypes.byref(params), ctypes.byref(rope),
+                                       ctypes.byref(bands) if bands is not None else None,
+                                       _ptr(q_in), _ptr(k_in), _ptr(q_out), _ptr(k_out), _ptr(mask_bits),
+                                       _ptr(row_ptr), _ptr(col_idx), col_capacity, _ptr(info),
+                                       _ptr(workspace), workspace.numel(), _stream()),
+           "prism_rope_estimate")
 
 
 def prism_block_scores(params: prism_params, q: torch.Tensor, k: torch.Tensor,

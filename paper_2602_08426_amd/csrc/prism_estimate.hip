@@ -34,17 +34,50 @@ struct BandVectors {
 // and the three sums of squares (all dims, high band, low band) in
 // energy[(head*N + block)*4 + {0,1,2}].  Heads 0..h-1 are Q heads, h..h+h_kv-1 are K heads.
 // =====================================================================================
-template <int BLK>
+// With kRope the kernel is also the producer of the post-RoPE tensors: q / k hold the vectors
+// BEFORE the rotation, every feature pair (2j, 2j+1) of token n is rotated by the angle
+// (position_offset + n) * theta_j (Sec. 3.1 "Spectral Structure of RoPE"), rounded to bf16, written
+// to q_out / k_out, and the rounded values are what is pooled, so the statistics are bit for bit
+// those of pooling the written tensors; the separate 2*(h + h_kv)*L*d bytes read of the pooling
+// pass is saved.
+struct RopeArgs {
+  double ln_base;           // theta_j = exp(-(2j/d) ln b)
+  double yarn_scale;        // s of the NTK-by-parts map (App. "Compatibility with YaRN"); <= 0: plain RoPE
+  double yarn_alpha, yarn_beta;
+  double yarn_native_len;   // L of r_j = L theta_j / (2 pi)
+  int position_offset;
+};
+
+// theta'_j of feature pair j: plain RoPE, or (1 - gamma_j) theta_j / s + gamma_j theta_j with
+// gamma_j = clamp((r_j - alpha) / (beta - alpha), 0, 1), r_j = L theta_j / (2 pi).
+__device__ __forceinline__ double rope_theta(const RopeArgs& r, int j) {
+  const double theta = exp(-(2.0 * j / kHeadDim) * r.ln_base);
+  if (!(r.yarn_scale > 0.0)) return theta;
+  const double rj = r.yarn_native_len * theta * 0.15915494309189535;          // / (2 pi)
+  double gamma = (rj - r.yarn_alpha) / (r.yarn_beta - r.yarn_alpha);
+  gamma = gamma < 0.0 ? 0.0 : (gamma > 1.0 ? 1.0 : gamma);
+  return (1.0 - gamma) * theta / r.yarn_scale + gamma * theta;
+}
+
+// cos and sin of position * theta: the product and its reduction to [-pi, pi] in fp64 (the angle
+// reaches 1e5 rad at 128K tokens, far beyond what fp32 resolves), the functions in fp32.
+__device__ __forceinline__ void rope_cos_sin(double angle, float* c, float* s) {
+  const double n = rint(angle * 0.15915494309189535);
+  const double a = fma(-n, 6.283185307179586, angle) - n * 2.4492935982947064e-16;   // 2 pi = hi + lo
+  sincosf((float)a, s, c);
+}
+
+template <int BLK, bool kRope>
 __global__ __launch_bounds__(256) void pool_energy_kernel(
-    const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, int h, int L, int N,
+    const uint16_t* q, const uint16_t* k, int h, int L, int N,
     BandMap map, BandVectors bv, float* __restrict__ energy,
-    float* __restrict__ pooled_q_f32, float* __restrict__ pooled_k_f32) {
+    float* __restrict__ pooled_q_f32, float* __restrict__ pooled_k_f32,
+    RopeArgs rope, uint16_t* q_out, uint16_t* k_out) {      // q_out / k_out may alias q / k
   __shared__ float part[16][kHeadDim + 4];
   __shared__ float esum[2][4];
   const int blk = blockIdx.x, head = blockIdx.y, t = threadIdx.x;
-  const uint16_t* src = (head < h) ? q + (size_t)head * L * kHeadDim
-                                   : k + (size_t)(head - h) * L * kHeadDim;
-  src += (size_t)blk * BLK * kHeadDim;
+  const size_t head_off = (head < h) ? (size_t)head * L * kHeadDim : (size_t)(head - h) * L * kHeadDim;
+  const uint16_t* src = ((head < h) ? q : k) + head_off + (size_t)blk * BLK * kHeadDim;
   const int c = t & 15, rg = t >> 4;
 
   const int cnt = min(BLK, L - blk * BLK);          // tokens in this block (ragged last block)
@@ -54,6 +87,37 @@ __global__ __launch_bounds__(256) void pool_energy_kernel(
     const int row = rg + it * 16;
     v[it] = row < cnt ? *reinterpret_cast<const uint4*>(src + (size_t)row * kHeadDim + c * 8)
                       : make_uint4(0u, 0u, 0u, 0u);
+  }
+  if (kRope) {
+    // This thread holds feature pairs 4c .. 4c+3 of tokens rg, rg + 16, ...: one accurate
+    // cos / sin per pair for its first token, then a rotation by 16 theta per further token (the
+    // fp32 recurrence runs over at most BLK/16 - 1 = 7 steps).
+    uint16_t* dst = ((head < h) ? q_out : k_out) + head_off + (size_t)blk * BLK * kHeadDim;
+    const int pos0 = rope.position_offset + blk * BLK + rg;
+    float cs[4], sn[4], dc[4], ds[4];
+#pragma unroll
+    for (int pj = 0; pj < 4; ++pj) {
+      const double theta = rope_theta(rope, 4 * c + pj);
+      rope_cos_sin((double)pos0 * theta, &cs[pj], &sn[pj]);
+      rope_cos_sin(16.0 * theta, &dc[pj], &ds[pj]);
+    }
+#pragma unroll
+    for (int it = 0; it < BLK / 16; ++it) {
+      const int row = rg + it * 16;
+      uint32_t w[4] = {v[it].x, v[it].y, v[it].z, v[it].w};
+#pragma unroll
+      for (int pj = 0; pj < 4; ++pj) {
+        const float x = __uint_as_float(w[pj] << 16), y = __uint_as_float(w[pj] & 0xFFFF0000u);
+        const float xr = x * cs[pj] - y * sn[pj];
+        const float yr = x * sn[pj] + y * cs[pj];
+        w[pj] = float_to_bf16_bits(xr) | (float_to_bf16_bits(yr) << 16);
+        const float cn = cs[pj] * dc[pj] - sn[pj] * ds[pj];
+        sn[pj] = sn[pj] * dc[pj] + cs[pj] * ds[pj];
+        cs[pj] = cn;
+      }
+      v[it] = make_uint4(w[0], w[1], w[2], w[3]);
+      if (row < cnt) *reinterpret_cast<uint4*>(dst + (size_t)row * kHeadDim + c * 8) = v[it];
+    }
   }
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -592,20 +656,33 @@ static BandVectors band_vectors(char* ws, const EstimateWs& L) {
 
 static int run_pool_and_scale(const prism_params* p, const BandMap& map, const void* q, const void* k,
                               char* ws, const EstimateWs& L, float* pooled_q, float* pooled_k,
-                              float* scales, hipStream_t st) {
+                              float* scales, hipStream_t st, const RopeArgs* rope = nullptr,
+                              void* q_out = nullptr, void* k_out = nullptr) {
   const int N = n_blocks(p);
   const dim3 grid(N, p->n_q_heads + p->n_kv_heads);
   const BandVectors bv = band_vectors(ws, L);
   float* energy = reinterpret_cast<float*>(ws + L.energy);
   float* inv = reinterpret_cast<float*>(ws + L.inv_scale);
-  if (p->block == 128)
-    hipLaunchKernelGGL(pool_energy_kernel<128>, grid, dim3(256), 0, st, (const uint16_t*)q,
-                       (const uint16_t*)k, p->n_q_heads, p->seq_len, N, map, bv, energy, pooled_q,
-                       pooled_k);
-  else
-    hipLaunchKernelGGL(pool_energy_kernel<64>, grid, dim3(256), 0, st, (const uint16_t*)q,
-                       (const uint16_t*)k, p->n_q_heads, p->seq_len, N, map, bv, energy, pooled_q,
-                       pooled_k);
+  const uint16_t* qp = (const uint16_t*)q;
+  const uint16_t* kp = (const uint16_t*)k;
+  const RopeArgs no_rope = {};
+  if (rope == nullptr) {
+    if (p->block == 128)
+      hipLaunchKernelGGL((pool_energy_kernel<128, false>), grid, dim3(256), 0, st, qp, kp, p->n_q_heads,
+                         p->seq_len, N, map, bv, energy, pooled_q, pooled_k, no_rope, nullptr, nullptr);
+    else
+      hipLaunchKernelGGL((pool_energy_kernel<64, false>), grid, dim3(256), 0, st, qp, kp, p->n_q_heads,
+                         p->seq_len, N, map, bv, energy, pooled_q, pooled_k, no_rope, nullptr, nullptr);
+  } else {
+    if (p->block == 128)
+      hipLaunchKernelGGL((pool_energy_kernel<128, true>), grid, dim3(256), 0, st, qp, kp, p->n_q_heads,
+                         p->seq_len, N, map, bv, energy, pooled_q, pooled_k, *rope, (uint16_t*)q_out,
+                         (uint16_t*)k_out);
+    else
+      hipLaunchKernelGGL((pool_energy_kernel<64, true>), grid, dim3(256), 0, st, qp, kp, p->n_q_heads,
+                         p->seq_len, N, map, bv, energy, pooled_q, pooled_k, *rope, (uint16_t*)q_out,
+                         (uint16_t*)k_out);
+  }
   hipLaunchKernelGGL(scale_kernel, dim3(p->n_q_heads), dim3(64), 0, st, energy, p->n_q_heads,
                      p->n_kv_heads, N, map.dz[0], map.dz[1],
                      (p->flags & PRISM_FLAG_NO_CALIBRATION) ? 0 : 1, inv, scales);
@@ -718,6 +795,60 @@ extern "C" int prism_estimate(const prism_params* params, const void* q_bf16, co
   const prism_bands bands = default_bands(params);
   return prism_estimate_bands(params, &bands, q_bf16, k_bf16, mask_bits, row_ptr, col_idx,
                               col_capacity, info, workspace, workspace_bytes, stream);
+}
+
+extern "C" int prism_rope_estimate(const prism_params* params, const prism_rope* rope,
+                                   const prism_bands* bands, const void* q_in_bf16,
+                                   const void* k_in_bf16, void* q_out_bf16, void* k_out_bf16,
+                                   uint64_t* mask_bits, int32_t* row_ptr, int32_t* col_idx,
+                                   int64_t col_capacity, int32_t* info, void* workspace,
+                                   size_t workspace_bytes, void* stream) {
+  int rc = check_params(params);
+  if (rc != PRISM_OK) return rc;
+  prism_bands def;
+  if (bands == nullptr) {
+    rc = check_bands(params);
+    if (rc != PRISM_OK) return rc;
+    def = default_bands(params);
+    bands = &def;
+  }
+  BandMap map;
+  rc = make_band_map(params, bands, &map);
+  if (rc != PRISM_OK) return rc;
+  if (!rope || !q_in_bf16 || !k_in_bf16 || !q_out_bf16 || !k_out_bf16 || !mask_bits || !row_ptr ||
+      !col_idx || !info || col_capacity < 0)
+    return PRISM_ERR_INVALID_ARG;
+  if (!(rope->base > 1.0) || rope->position_offset < 0 ||
+      (int64_t)rope->position_offset + params->seq_len > ((int64_t)1 << 30))
+    return PRISM_ERR_INVALID_ARG;
+  RopeArgs ra;
+  ra.ln_base = log(rope->base);
+  ra.position_offset = rope->position_offset;
+  ra.yarn_scale = 0.0;
+  ra.yarn_alpha = ra.yarn_beta = ra.yarn_native_len = 0.0;
+  if (rope->yarn_native_len != 0) {
+    if (rope->yarn_native_len < 0 || !(rope->yarn_scale >= 1.0) || !(rope->yarn_alpha >= 0.0) ||
+        !(rope->yarn_beta > rope->yarn_alpha))
+      return PRISM_ERR_INVALID_ARG;
+    ra.yarn_scale = rope->yarn_scale;
+    ra.yarn_alpha = rope->yarn_alpha;
+    ra.yarn_beta = rope->yarn_beta;
+    ra.yarn_native_len = (double)rope->yarn_native_len;
+  }
+  const EstimateWs L = estimate_ws(params);
+  rc = check_ws(workspace, workspace_bytes, L.total);
+  if (rc != PRISM_OK) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  char* ws = static_cast<char*>(workspace);
+  rc = run_pool_and_scale(params, map, q_in_bf16, k_in_bf16, ws, L, nullptr, nullptr, nullptr, st, &ra,
+                          q_out_bf16, k_out_bf16);
+  if (rc != PRISM_OK) return rc;
+  const int N = n_blocks(params);
+  rc = (N <= 1024)
+           ? launch_select<16, false>(params, map, ws, L, mask_bits, row_ptr, nullptr, nullptr, st)
+           : launch_select<32, false>(params, map, ws, L, mask_bits, row_ptr, nullptr, nullptr, st);
+  if (rc != PRISM_OK) return rc;
+  return run_compaction(params, mask_bits, row_ptr, col_idx, col_capacity, info, false, st);
 }
 
 extern "C" int prism_block_scores_bands(const prism_params* params, const prism_bands* bands,

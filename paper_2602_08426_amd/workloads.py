@@ -20,7 +20,7 @@ from __future__ import annotations
 
 from concurrent.futures import ThreadPoolExecutor
 from dataclasses import dataclass, field
-from typing import Dict, List, Tuple
+from typing import Dict, List, Optional, Tuple
 
 import numpy as np
 
@@ -44,15 +44,24 @@ def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
 # --------------------------------------------------------------------------- #
 # RoPE (input generator side)
 # --------------------------------------------------------------------------- #
-def rope_frequencies(head_dim: int, base: float) -> np.ndarray:
-    """theta_j = base^(-2j/d), j = 0 .. d/2-1 (fp64)."""
+def rope_frequencies(head_dim: int, base: float, yarn=None) -> np.ndarray:
+    """theta_j = base^(-2j/d), j = 0 .. d/2-1 (fp64).  yarn = (native_len, scale, alpha, beta)
+    stretches the low frequencies the way a YaRN-extended checkpoint does (NTK-by-parts: pairs that
+    turn fewer than alpha times over native_len are slowed by `scale`, pairs that turn more than
+    beta times are kept, linear blend between)."""
     j = np.arange(head_dim // 2, dtype=np.float64)
-    return np.power(float(base), -2.0 * j / head_dim)
+    theta = np.power(float(base), -2.0 * j / head_dim)
+    if yarn is not None:
+        native_len, scale, alpha, beta = yarn
+        turns = native_len * theta / (2.0 * np.pi)
+        keep = np.clip((turns - alpha) / (beta - alpha), 0.0, 1.0)
+        theta = (1.0 - keep) * theta / scale + keep * theta
+    return theta
 
 
-def rope_tables(positions: np.ndarray, head_dim: int, base: float) -> Tuple[np.ndarray, np.ndarray]:
+def rope_tables(positions: np.ndarray, head_dim: int, base: float, yarn=None) -> Tuple[np.ndarray, np.ndarray]:
     """cos/sin of n*theta_j as fp32 [len(positions), d/2]; angles formed in fp64."""
-    ang = positions.astype(np.float64)[:, None] * rope_frequencies(head_dim, base)[None, :]
+    ang = positions.astype(np.float64)[:, None] * rope_frequencies(head_dim, base, yarn)[None, :]
     return np.cos(ang).astype(np.float32), np.sin(ang).astype(np.float32)
 
 
@@ -65,9 +74,9 @@ def apply_rope(x: np.ndarray, cos: np.ndarray, sin: np.ndarray) -> np.ndarray:
     return out
 
 
-def rotate_vector(g: np.ndarray, shift: float, head_dim: int, base: float) -> np.ndarray:
+def rotate_vector(g: np.ndarray, shift: float, head_dim: int, base: float, yarn=None) -> np.ndarray:
     """R_shift g: rotate a single content vector by `shift` positions (fp64)."""
-    th = rope_frequencies(head_dim, base) * float(shift)
+    th = rope_frequencies(head_dim, base, yarn) * float(shift)
     c, s = np.cos(th), np.sin(th)
     out = np.empty(head_dim, dtype=np.float64)
     out[0::2] = g[0::2] * c - g[1::2] * s
@@ -94,6 +103,7 @@ class Workload:
     d_low: int = 96
     k_lognormal_sigma: float = 0.0   # heavy-tailed per-token key scales (0 = off)
     amp_scale: float = 1.0           # multiplies the planted q-side amplitudes (density knob)
+    yarn: Optional[Tuple[int, float, float, float]] = None   # (native_len, scale, alpha, beta): YaRN-style frequencies
 
     @property
     def n_blocks(self) -> int:
@@ -231,12 +241,15 @@ def describe(w: Workload) -> List[dict]:
             for i, p in enumerate(hp)]
 
 
-def generate(w: Workload, n_threads: int = 8) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+def generate(w: Workload, n_threads: int = 8, rotate: bool = True) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
     """Return (Q, K, V) as bf16 bit patterns (uint16), shapes
-    [n_q_heads, L, d], [n_kv_heads, L, d], [n_kv_heads, L, d]."""
+    [n_q_heads, L, d], [n_kv_heads, L, d], [n_kv_heads, L, d].  rotate=False returns Q and K as
+    they are BEFORE the rotary embedding (rounded to bf16), for callers that apply it themselves."""
     L, d, B = w.seq_len, w.head_dim, w.block
     head_plans, kv_plans, g_vecs, m_vecs = _plan(w)
-    cos, sin = rope_tables(np.arange(L), d, w.rope_base)
+    cos, sin = rope_tables(np.arange(L), d, w.rope_base, w.yarn)
+    if not rotate:
+        cos, sin = np.ones_like(cos), np.zeros_like(sin)
     root = np.random.SeedSequence([w.seed, 0xDA7A])
     seeds = root.spawn(w.n_q_heads + 2 * w.n_kv_heads)
 
@@ -252,7 +265,7 @@ def generate(w: Workload, n_threads: int = 8) -> Tuple[np.ndarray, np.ndarray, n
         const = hp.vert_amp * m_vecs[kvh]
         for o in hp.slash_offsets:
             const = const + (hp.slash_amp / np.sqrt(len(hp.slash_offsets))) * \
-                rotate_vector(g_vecs[kvh], -o, d, w.rope_base)
+                rotate_vector(g_vecs[kvh], -o, d, w.rope_base, w.yarn)
         x += const.astype(np.float32)[None, :]
         _add_block_topics(x, rng, B, d, _Q_TOPIC_AMP)
         Q[hq] = f32_to_bf16_bits(apply_rope(x, cos, sin))

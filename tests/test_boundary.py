@@ -127,6 +127,24 @@ def test_null_pointers_and_workspace_are_rejected(lib):
     assert lib.prism_estimate(None, fake, fake, fake, fake, fake, 10, fake, fake, 1 << 30, None) == -1
 
 
+@pytest.mark.parametrize("kw", [
+    dict(base=1.0), dict(base=float("nan")), dict(base=1e4, position_offset=-1),
+    dict(base=1e4, position_offset=(1 << 30)),
+    dict(base=1e6, yarn_native_len=32768, yarn_scale=0.5),
+    dict(base=1e6, yarn_native_len=32768, yarn_scale=4.0, yarn_alpha=32.0, yarn_beta=32.0),
+    dict(base=1e6, yarn_native_len=-5, yarn_scale=4.0),
+])
+def test_bad_rope_descriptors_are_rejected_before_launch(lib, kw):
+    p = pb.make_params(4, 2, 1024, 128)
+    fake = ctypes.c_void_p(256)
+    rope = pb.make_rope(**kw)
+    call = lambda r, qi=fake: lib.prism_rope_estimate(ctypes.byref(p), r, None, qi, fake, fake, fake, fake, fake,
+                                                      fake, 10, fake, fake, 1 << 30, None)
+    assert call(ctypes.byref(rope)) == -1
+    assert call(None) == -1                                           # no descriptor at all
+    assert call(ctypes.byref(pb.make_rope(1e4)), None) == -1          # null input with a good descriptor
+
+
 def test_mask_pack_roundtrip():
     import numpy as np
     from tests.gpu_util import pack_mask, unpack_mask
