@@ -51,3 +51,27 @@ def test_all_baseline_configs_present():
     assert (c4.n_q_heads, c4.n_kv_heads, c4.seq_len, c4.block, c4.n_blocks) == (32, 8, 131072, 128, 1024)
     c5 = wl.WORKLOADS["c5_qwen_64k"]
     assert (c5.n_q_heads, c5.n_kv_heads, c5.top_p, c5.rope_base) == (28, 4, 0.93, 1.0e6)
+
+
+def test_generator_and_oracle_agree_on_the_rope_convention():
+    """Two independent implementations (the generator's tables, the oracle's complex rotation) of the
+    same convention: pairs (2j, 2j+1), angle n * theta_j, plain and YaRN-scaled frequencies."""
+    import dataclasses
+
+    from oracle import prism_oracle as orc
+    yarn = (32768, 4.0, 1.0, 32.0)
+    np.testing.assert_allclose(wl.rope_frequencies(128, 1.0e6, yarn), orc.rope_frequencies(128, 1.0e6, yarn=yarn),
+                               rtol=1e-14)
+    for y in (None, yarn):
+        w = dataclasses.replace(wl.small_variant(wl.WORKLOADS["c5_qwen_64k"], 512, 2, 1), yarn=y)
+        q_pre, k_pre, v0 = wl.generate(w, n_threads=1, rotate=False)
+        q_rot, k_rot, v1 = wl.generate(w, n_threads=1)
+        np.testing.assert_array_equal(v0, v1)
+        theta = orc.rope_frequencies(w.head_dim, w.rope_base, yarn=y)
+        for pre, rot in ((q_pre, q_rot), (k_pre, k_rot)):
+            # the generator rotates its fp32 content before rounding; rotating the rounded pre-RoPE
+            # tensor instead differs by the rounding of the content (2^-9 relative per element)
+            ref = orc.apply_rope(orc.bf16_to_f64(pre), theta)
+            got = orc.bf16_to_f64(rot)
+            scale = np.abs(orc.bf16_to_f64(pre)).max()
+            assert np.abs(got - ref).max() < 2.0 ** -6 * scale
