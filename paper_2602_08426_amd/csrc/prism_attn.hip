@@ -161,19 +161,15 @@ __device__ __forceinline__ void tile_barrier() {
 // Queue entry of one row, written by queue_fill_kernel:
 //   x = q-head, y = q-block u | (first valid key block << 16), z = index of that entry in
 //   col_idx, w = end of the row's list (z == w: the row has no valid entry).
-// A workgroup's pulls p = 0, 1, 2, ... from queue `my_queue` map to the table as
-//   round = p / g, member = p % g, slot = round * n_queues + my_queue, entry = slot * g + member;
-// the queue is exhausted once round * n_queues >= n_groups, and a slot >= n_groups is a hole
-// in the last deal round.
-enum { kItemEnd = 0, kItemHole = 1, kItemRow = 2 };
+// Every queue (one per XCD) owns a contiguous segment of the table: `plan` = { start[8], len[8],
+// pull counters[8] }; a workgroup's pulls p = 0, 1, 2, ... from queue x are the entries
+// start[x] + p while p < len[x].
+enum { kItemEnd = 0, kItemRow = 2 };
+constexpr int kPlanStart = 0, kPlanLen = 8, kPlanCounter = 16, kPlanInts = 24;
 
-__device__ __forceinline__ int item_kind(int pulled, int g, int n_queues, int my_queue, int n_groups,
-                                         int* entry) {
-  const int round = pulled / g, member = pulled - round * g;
-  if ((int64_t)round * n_queues >= n_groups) return kItemEnd;
-  const int slot = round * n_queues + my_queue;
-  if (slot >= n_groups) return kItemHole;
-  *entry = slot * g + member;
+__device__ __forceinline__ int item_kind(int pulled, int seg_start, int seg_len, int* entry) {
+  if (pulled >= seg_len) return kItemEnd;
+  *entry = seg_start + pulled;
   return kItemRow;
 }
 
@@ -182,7 +178,7 @@ __device__ __forceinline__ int item_kind(int pulled, int g, int n_queues, int my
 template <int BLK, bool kStreamOnly>
 __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ vt,
-    const int32_t* __restrict__ col_idx, const int4* __restrict__ items, int32_t* __restrict__ counter,
+    const int32_t* __restrict__ col_idx, const int4* __restrict__ items, int32_t* __restrict__ plan,
     uint16_t* __restrict__ out, float* __restrict__ lse, int h, int h_kv, int L, int N,
     int causal) {
 #if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the kernel's signature
@@ -190,7 +186,7 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
   constexpr int KT = BLK / 32;                       // 32-key tiles per kv block
   __shared__ __attribute__((aligned(16))) char lds_k[C::kTileBytes];
   __shared__ __attribute__((aligned(16))) char lds_v[C::kTileBytes];
-  __shared__ int next_item;
+  __shared__ int next_item, next_queue;
 
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int l32 = lane & 31, hf = lane >> 5;
@@ -208,24 +204,28 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
   for (int st = 0; st < KT * 2; ++st)
     voff[st] = l32 * (BLK * 2) + (((2 * st + hf) ^ (l32 & (C::kVtCpr - 1))) << 4);
 
-  // Persistent workgroups pull rows from queues ordered longest list first, so that heads
-  // of very different density keep every CU busy until the end.  The unit of the order is the
-  // GQA group (kv head, q-block): its g rows are handed out back to back to workgroups of the
-  // same XCD (workgroups are dealt round-robin to the 8 XCDs, and each XCD has its own L2), so
-  // that the K/V tiles the rows of a group share are fetched from HBM once.  Groups are dealt
-  // to the XCD queues round-robin in sorted order, which keeps the queues balanced.
-  // Every workgroup leaves the loop as soon as its queue is exhausted.
+  // Persistent workgroups pull rows from per-XCD queues (workgroups are dealt round-robin to the
+  // 8 XCDs, and each XCD has its own L2).  A queue runs through neighbouring q-blocks of one
+  // q-head at a time, so the 64 workgroups of an XCD work on neighbouring rows of one head: such
+  // rows list many of the same key blocks (stripes, sinks, local windows; all of them for dense
+  // lists) at about the same position of their lists, and the tile one of them fetches is still
+  // in the XCD's L2 when the others ask for it.
+  // A workgroup whose queue is exhausted goes on with rows of another XCD's queue, so the XCDs
+  // finish together although the lists of one may take longer per block than those of another;
+  // it leaves the loop once it has seen every queue exhausted.
   const int n_queues = gridDim.x < 8 ? 1 : 8;
-  const int my_queue = blockIdx.x % n_queues;
-  const int n_groups = h_kv * N;
+  int my_queue = blockIdx.x % n_queues;
+  int seg_start = plan[kPlanStart + my_queue];
+  int seg_len = plan[kPlanLen + my_queue];
+  int32_t* counter = plan + kPlanCounter;
   const int vmax_nc = N - 1;
   const int tail = L - (N - 1) * BLK;              // tokens in the last block (BLK unless ragged)
   const uint32_t head_bytes = (uint32_t)L * kHeadDim * 2;
   const uint32_t image_head_bytes = (uint32_t)N * C::kTileBytes;
 
   // The queue is pulled when a workgroup is about to become free (at the top of the last
-  // step of its row), so the g rows of a GQA group still start almost together on one XCD; the
-  // pull and the read of the next row's queue entry are hidden behind that last step.
+  // step of its row), so neighbouring rows of the queue start close together; the pull and the
+  // read of the next row's queue entry are hidden behind that last step.
   int lane_zero;                                     // 0, but opaque to the compiler
   asm volatile("v_mov_b32 %0, 0" : "=v"(lane_zero));
   if (t == 0) next_item = atomicAdd(counter + my_queue, 1);
@@ -234,7 +234,7 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
   int kind_cur;
   {
     int e = 0;
-    kind_cur = item_kind(__builtin_amdgcn_readfirstlane(next_item), g, n_queues, my_queue, n_groups, &e);
+    kind_cur = item_kind(__builtin_amdgcn_readfirstlane(next_item), seg_start, seg_len, &e);
     if (kind_cur == kItemRow) {
       const int4 it0 = items[e];
       cur_x = it0.x; cur_y = it0.y; cur_z = it0.z; cur_w = it0.w;
@@ -246,7 +246,43 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
   int4 item_nxt = make_int4(0, 0, 0, 0);
   int pulled_reg = 0;
 
-  while (kind_cur != kItemEnd) {
+  for (;;) {
+    if (kind_cur == kItemEnd) {
+      // Own queue exhausted: look (one coherent read of the 8 pull counters, no atomic) for a
+      // queue that still has rows, nearest first round the ring, and pull from it.  A counter
+      // only grows, so a queue seen exhausted stays so; the atomic pull decides who gets a row.
+      if (wave == 0) {
+        int pulls = 0x7fffffff, len = 0;
+        if (lane < n_queues) {
+          pulls = __hip_atomic_load(counter + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          len = plan[kPlanLen + lane];
+        }
+        const unsigned long long open = __ballot(pulls < len);
+        int pick = -1;
+        for (int s = 1; s < n_queues && pick < 0; ++s) {
+          const int x = my_queue + s < n_queues ? my_queue + s : my_queue + s - n_queues;
+          if ((open >> x) & 1ull) pick = x;
+        }
+        if (lane == 0) {
+          next_queue = pick;
+          if (pick >= 0) next_item = atomicAdd(counter + pick, 1);
+        }
+      }
+      __syncthreads();
+      const int pick = __builtin_amdgcn_readfirstlane(next_queue);
+      if (pick < 0) break;
+      my_queue = pick;
+      seg_start = plan[kPlanStart + my_queue];
+      seg_len = plan[kPlanLen + my_queue];
+      int e = 0;
+      kind_cur = item_kind(__builtin_amdgcn_readfirstlane(next_item), seg_start, seg_len, &e);
+      if (kind_cur == kItemRow) {
+        const int4 it0 = items[e];
+        cur_x = it0.x; cur_y = it0.y; cur_z = it0.z; cur_w = it0.w;
+      }
+      __syncthreads();
+      continue;
+    }
     const int hq = cur_x;
     const int u = cur_y & 0xffff;
     int v = (cur_y >> 16) & 0xffff;
@@ -258,8 +294,7 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
     int kind_nxt = kItemEnd;
 
     if (!has_work) {
-      // hole in the last deal round, or a row without a valid entry (o = 0, lse = -inf): no
-      // tile work; pull the next row right away
+      // a row without a valid entry (o = 0, lse = -inf): no tile work; pull the next row right away
       if (kind_cur == kItemRow && qrow < L) {
         uint16_t* op = out + ((size_t)hq * L + qrow) * kHeadDim + hf * 64;
 #pragma unroll
@@ -269,7 +304,7 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
       if (t == 0) next_item = atomicAdd(counter + my_queue, 1);
       __syncthreads();
       int e = 0;
-      kind_cur = item_kind(__builtin_amdgcn_readfirstlane(next_item), g, n_queues, my_queue, n_groups, &e);
+      kind_cur = item_kind(__builtin_amdgcn_readfirstlane(next_item), seg_start, seg_len, &e);
       if (kind_cur == kItemRow) {
         const int4 it0 = items[e];
         cur_x = it0.x; cur_y = it0.y; cur_z = it0.z; cur_w = it0.w;
@@ -425,7 +460,7 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
         // on the vector-memory counter and is waited for after the PV phase; a scalar load would be
         // waited for by the very next LDS read
         int e_nxt = 0;
-        kind_nxt = item_kind(__builtin_amdgcn_readfirstlane(next_item), g, n_queues, my_queue, n_groups, &e_nxt);
+        kind_nxt = item_kind(__builtin_amdgcn_readfirstlane(next_item), seg_start, seg_len, &e_nxt);
         if (kind_nxt == kItemRow) item_nxt = items[e_nxt + lane_zero];
       }
 
@@ -517,142 +552,252 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
 }
 
 // =====================================================================================
-// Work queue: GQA groups (kv head, q-block) in the order  (phase ascending, longest list
-// descending), by a counting sort.
-//   phase  = kv head / heads_per_phase: the kv heads are taken a few at a time so that the K
-//            and V^T of the heads in flight fit the 256 MB memory-side cache (at 128K tokens a
-//            kv head is 67 MB of K + V^T and all eight do not fit);
-//   length = the longest list among the g rows of the group, quantised to `levels` steps.
-//   queue_reset_kernel : zero the histogram and the queue counters
-//   queue_hist_kernel  : hist[bin] over all groups (LDS-private histograms, integer atomics)
-//   queue_scan_kernel  : start[bin] = number of groups in earlier bins
-//   queue_fill_kernel  : the group gets position pos = start[bin] + k (order inside one bin is
-//                        arbitrary) and its g rows the queue entries items[pos*g .. pos*g+g-1]
+// Work queues.  The rows (q-head, q-block) are put in the order
+//     (phase, length class, q-head, q-block descending)
+// and every (phase, class) group of that order is cut into one contiguous part per queue, the
+// parts of a group holding equal work (listed blocks + one per row).  A queue is the sequence of
+// its parts.  So each XCD walks neighbouring q-blocks of one q-head at a time, all XCDs go
+// through the long rows of a phase first and its short rows last (no long row is started at the
+// end of the call), and the queues hold equal work.
+//   phase = kv head / heads_per_phase: the kv heads are taken a few at a time so that the K and
+//       V^T of the heads in flight fit the 256 MB memory-side cache (at 128K tokens a kv head is
+//       67 MB of K + V^T and all eight do not fit).
+//   class: list length in (512, ..], (256, 512], (128, 256], ... (1, 2], [0, 1].
+//   queue_count_kernel  (one workgroup per q-head): rows and work of the head per class.
+//   queue_rank_kernel   (one workgroup per q-head): every row's rank in its group and its part,
+//       and the number of rows of every (group, part).
+//   queue_fill_kernel   (one thread per row): the row's position in its queue and its entry.
 // =====================================================================================
-struct QueueCfg {
-  int n_groups, g, N, heads_per_phase, levels, n_bins, causal, cap;
+struct PlanCfg {
+  int h, g, N, heads_per_phase, n_phases, n_queues, cap, causal;
 };
+constexpr int kClasses = 11;
+constexpr int kMaxGroups = 512;           // (phase, class) groups held in LDS by queue_fill_kernel
 
-__global__ __launch_bounds__(256) void queue_reset_kernel(int32_t* __restrict__ hist, int nbins,
-                                                          int32_t* __restrict__ counters) {
-  const int i = blockIdx.x * 256 + threadIdx.x;
-  if (i < nbins) hist[i] = 0;
-  if (i < 8) counters[i] = 0;
+// class 0: more than 512 listed blocks, class c = 1 .. 9: (2^(9-c), 2^(10-c)], class 10: 0 or 1
+__device__ __forceinline__ int length_class(int len) {
+  if (len <= 1) return kClasses - 1;
+  const int k = 31 - __builtin_clz(len - 1);           // len in (2^k, 2^(k+1)]
+  return k > 9 ? 0 : 9 - k;
 }
 
-__device__ __forceinline__ int group_bin(const int32_t* __restrict__ row_ptr, int gid, const QueueCfg& c) {
-  const int kvh = gid / c.N, u = gid - kvh * c.N;
-  int m = 0;
-  for (int j = 0; j < c.g; ++j) {
-    const int r = (kvh * c.g + j) * c.N + u;
-    const int n = row_ptr[r + 1] - row_ptr[r];
-    m = max(m, n < 0 ? 0 : (n > c.N ? c.N : n));
+// list bounds of row r clamped to [0, cap] (and end >= begin)
+__device__ __forceinline__ void row_bounds(const int32_t* __restrict__ row_ptr, int r, int cap, int* beg,
+                                           int* end) {
+  int b = row_ptr[r], e = row_ptr[r + 1];
+  b = b < 0 ? 0 : (b > cap ? cap : b);
+  e = e < b ? b : (e > cap ? cap : e);
+  *beg = b;
+  *end = e;
+}
+
+// bins = { rows[h][kClasses], work[h][kClasses] }; parts[n_phases][kClasses][8] is cleared here.
+__global__ __launch_bounds__(256) void queue_count_kernel(const int32_t* __restrict__ row_ptr, PlanCfg c,
+                                                          int32_t* __restrict__ bins,
+                                                          int32_t* __restrict__ parts) {
+  __shared__ int s_rows[kClasses], s_work[kClasses];
+  const int t = threadIdx.x, hq = blockIdx.x;
+  if (t < kClasses) {
+    s_rows[t] = 0;
+    s_work[t] = 0;
   }
-  const int q = (int)(((int64_t)m * (c.levels - 1)) / c.N);          // 0 .. levels-1
-  return (kvh / c.heads_per_phase) * c.levels + (c.levels - 1 - q);
-}
-
-__global__ __launch_bounds__(256) void queue_hist_kernel(const int32_t* __restrict__ row_ptr,
-                                                         QueueCfg c, int32_t* __restrict__ hist) {
-  __shared__ int lh[kMaxBlocks + 1];
-  for (int i = threadIdx.x; i < c.n_bins; i += 256) lh[i] = 0;
+  for (int i = hq * 256 + t; i < c.n_phases * kClasses * 8; i += c.h * 256) parts[i] = 0;
   __syncthreads();
-  for (int gid = blockIdx.x * 256 + threadIdx.x; gid < c.n_groups; gid += gridDim.x * 256)
-    atomicAdd(&lh[group_bin(row_ptr, gid, c)], 1);
-  __syncthreads();
-  for (int i = threadIdx.x; i < c.n_bins; i += 256)
-    if (lh[i] != 0) atomicAdd(&hist[i], lh[i]);
-}
-
-// single workgroup: exclusive prefix sum over the bins, in place
-__global__ __launch_bounds__(1024) void queue_scan_kernel(int32_t* __restrict__ hist, int nb) {
-  __shared__ int wave_tot[16];
-  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  const int per = (nb + 1023) / 1024;
-  const int lo = min(nb, t * per), hi = min(nb, lo + per);
-  int s = 0;
-  for (int i = lo; i < hi; ++i) s += hist[i];
-  int inc = s;
-#pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    const int y = __shfl_up(inc, off, 64);
-    if (lane >= off) inc += y;
+  for (int u = t; u < c.N; u += 256) {
+    int beg, end;
+    row_bounds(row_ptr, hq * c.N + u, c.cap, &beg, &end);
+    const int cls = length_class(end - beg);
+    atomicAdd(&s_rows[cls], 1);
+    atomicAdd(&s_work[cls], end - beg + 1);
   }
-  if (lane == 63) wave_tot[wave] = inc;
   __syncthreads();
-  int run = inc - s;
-  for (int w = 0; w < wave; ++w) run += wave_tot[w];
-  for (int i = lo; i < hi; ++i) {
-    const int c = hist[i];
-    hist[i] = run;
-    run += c;
+  if (t < kClasses) {
+    bins[hq * kClasses + t] = s_rows[t];
+    bins[(c.h + hq) * kClasses + t] = s_work[t];
   }
 }
 
-// Each workgroup ranks its 256 groups per bin in LDS and reserves one range per distinct bin
-// with a single global atomic, so groups of one bin do not serialise on one address.  The
-// thread of a group then writes the queue entries of its g rows: list bounds clamped to
-// [0, cap], and the first entry that names a valid key block (0 <= v <= u for causal
-// attention, 0 <= v < N otherwise).
-__global__ __launch_bounds__(256) void queue_fill_kernel(const int32_t* __restrict__ row_ptr,
-                                                         const int32_t* __restrict__ col_idx,
-                                                         QueueCfg c, int32_t* __restrict__ start,
-                                                         int4* __restrict__ items) {
-  __shared__ int cnt[kMaxBlocks + 1];
-  for (int i = threadIdx.x; i < c.n_bins; i += 256) cnt[i] = 0;
-  __syncthreads();
-  const int gid = blockIdx.x * 256 + threadIdx.x;
-  int bin = 0, rank = 0;
-  if (gid < c.n_groups) {
-    bin = group_bin(row_ptr, gid, c);
-    rank = atomicAdd(&cnt[bin], 1);
+// row_rank[r] = rank of row r inside its (phase, class) group; row_part[r] = group * 8 + part.
+__global__ __launch_bounds__(256) void queue_rank_kernel(const int32_t* __restrict__ row_ptr, PlanCfg c,
+                                                         const int32_t* __restrict__ bins,
+                                                         int32_t* __restrict__ parts,
+                                                         int32_t* __restrict__ row_rank,
+                                                         int32_t* __restrict__ row_part) {
+  __shared__ int s_rows_before[kClasses];            // rows of the group in earlier heads
+  __shared__ long long s_work_before[kClasses], s_work_total[kClasses];
+  __shared__ int s_parts[kClasses * 8];
+  __shared__ long long s_wave_total[kClasses][4];
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6, hq = blockIdx.x;
+  const int phase = (hq / c.g) / c.heads_per_phase;
+  if (t < kClasses) {
+    s_rows_before[t] = 0;
+    s_work_before[t] = 0;
+    s_work_total[t] = 0;
   }
   __syncthreads();
-  for (int i = threadIdx.x; i < c.n_bins; i += 256) {
-    const int k = cnt[i];
-    if (k != 0) cnt[i] = atomicAdd(&start[i], k);  // count -> first position of this workgroup's range
-  }
-  __syncthreads();
-  if (gid < c.n_groups) {
-    const int pos = cnt[bin] + rank;
-    if (pos >= 0 && pos < c.n_groups) {
-      const int kvh = gid / c.N, u = gid - kvh * c.N;
-      const int vmax = c.causal ? u : c.N - 1;
-      for (int j = 0; j < c.g; ++j) {
-        const int hq = kvh * c.g + j;
-        const int r = hq * c.N + u;
-        int beg = row_ptr[r], end = row_ptr[r + 1];
-        beg = beg < 0 ? 0 : (beg > c.cap ? c.cap : beg);
-        end = end < beg ? beg : (end > c.cap ? c.cap : end);
-        int it = beg, v = 0;
-        while (it < end) {
-          v = col_idx[it];
-          if (v >= 0 && v <= vmax) break;
-          ++it;
-        }
-        if (it >= end) v = 0;
-        items[(size_t)pos * c.g + j] = make_int4(hq, u | (v << 16), it, end);
+  {
+    const int h0 = phase * c.heads_per_phase * c.g;
+    const int h1 = min(c.h, h0 + c.heads_per_phase * c.g);
+    for (int i = t; i < (h1 - h0) * kClasses; i += 256) {
+      const int hh = h0 + i / kClasses, k = i % kClasses;
+      const int w = bins[(c.h + hh) * kClasses + k];
+      if (hh < hq) {
+        atomicAdd(&s_rows_before[k], bins[hh * kClasses + k]);
+        atomicAdd(reinterpret_cast<unsigned long long*>(&s_work_before[k]), (unsigned long long)w);
       }
+      atomicAdd(reinterpret_cast<unsigned long long*>(&s_work_total[k]), (unsigned long long)w);
     }
   }
+  for (int i = t; i < kClasses * 8; i += 256) s_parts[i] = 0;
+
+  // Thread t owns the rows i = t*per .. t*per + per - 1 of the head's order (q-block N-1-i).
+  // Per class, rows and work of a thread travel through the scan as one number: work * 2^16 + rows
+  // (a head has at most 2048 rows).
+  const int per = (c.N + 255) / 256;
+  long long mine[kClasses];
+#pragma unroll
+  for (int k = 0; k < kClasses; ++k) mine[k] = 0;
+  for (int j = 0; j < per; ++j) {
+    const int i = t * per + j;
+    if (i >= c.N) break;
+    int beg, end;
+    row_bounds(row_ptr, hq * c.N + (c.N - 1 - i), c.cap, &beg, &end);
+    const int cls = length_class(end - beg);
+    const long long add = ((long long)(end - beg + 1) << 16) + 1;
+#pragma unroll
+    for (int k = 0; k < kClasses; ++k) mine[k] += k == cls ? add : 0;
+  }
+  long long before[kClasses];                        // exclusive prefix over the threads
+#pragma unroll
+  for (int k = 0; k < kClasses; ++k) {
+    long long incl = mine[k];
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const long long y = __shfl_up(incl, off, 64);
+      if (lane >= off) incl += y;
+    }
+    if (lane == 63) s_wave_total[k][wave] = incl;
+    before[k] = incl - mine[k];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < kClasses; ++k)
+    for (int w = 0; w < wave; ++w) before[k] += s_wave_total[k][w];
+
+  for (int j = 0; j < per; ++j) {
+    const int i = t * per + j;
+    if (i >= c.N) break;
+    const int r = hq * c.N + (c.N - 1 - i);
+    int beg, end;
+    row_bounds(row_ptr, r, c.cap, &beg, &end);
+    const int cls = length_class(end - beg);
+    const long long add = ((long long)(end - beg + 1) << 16) + 1;
+    long long upto = 0;                              // this row included
+#pragma unroll
+    for (int k = 0; k < kClasses; ++k)
+      if (k == cls) {
+        before[k] += add;
+        upto = before[k];
+      }
+    const int rank = (int)(upto & 0xffff) - 1;
+    const long long w_incl = (upto >> 16) + s_work_before[cls];
+    int x = 0;
+    if (c.n_queues > 1) {
+      x = (int)(((w_incl - 1) * c.n_queues) / s_work_total[cls]);
+      x = x < 0 ? 0 : (x > c.n_queues - 1 ? c.n_queues - 1 : x);
+    }
+    row_rank[r] = s_rows_before[cls] + rank;
+    row_part[r] = (phase * kClasses + cls) * 8 + x;
+    atomicAdd(&s_parts[cls * 8 + x], 1);
+  }
+  __syncthreads();
+  for (int i = t; i < kClasses * 8; i += 256)
+    if (s_parts[i] > 0) atomicAdd(&parts[phase * kClasses * 8 + i], s_parts[i]);
+}
+
+// The thread of a row writes the row's queue entry: list bounds clamped to [0, cap], and the
+// first entry that names a valid key block (0 <= v <= u for causal attention, 0 <= v < N
+// otherwise).  Queue x holds, group after group, the rows of its part of the group; workgroup 0
+// also writes the plan (segment starts and lengths, cleared pull counters).
+__global__ __launch_bounds__(256) void queue_fill_kernel(const int32_t* __restrict__ row_ptr,
+                                                         const int32_t* __restrict__ col_idx, PlanCfg c,
+                                                         const int32_t* __restrict__ parts,
+                                                         const int32_t* __restrict__ row_rank,
+                                                         const int32_t* __restrict__ row_part,
+                                                         int32_t* __restrict__ plan,
+                                                         int4* __restrict__ items) {
+  __shared__ int s_parts[kMaxGroups * 8];            // rows of (group, part)
+  __shared__ int s_before[kMaxGroups * 8];           // rows of the same part in earlier groups
+  __shared__ int s_start[8];
+  const int t = threadIdx.x;
+  const int n_groups = c.n_phases * kClasses;
+  for (int i = t; i < n_groups * 8; i += 256) s_parts[i] = parts[i];
+  __syncthreads();
+  if (t < 8) {
+    int run = 0;
+    for (int gq = 0; gq < n_groups; ++gq) {
+      s_before[gq * 8 + t] = run;
+      run += s_parts[gq * 8 + t];
+    }
+    s_start[t] = run;                                // length of queue t, turned into its start below
+  }
+  __syncthreads();
+  if (t == 0) {
+    int start = 0;
+    for (int x = 0; x < 8; ++x) {
+      const int len = s_start[x];
+      s_start[x] = start;
+      if (blockIdx.x == 0) {
+        plan[kPlanStart + x] = start;
+        plan[kPlanLen + x] = len;
+        plan[kPlanCounter + x] = 0;
+      }
+      start += len;
+    }
+  }
+  __syncthreads();
+
+  const int r = blockIdx.x * 256 + t;
+  if (r >= c.h * c.N) return;
+  const int hq = r / c.N, u = r - hq * c.N;
+  const int gp = row_part[r], x = gp & 7;
+  int in_earlier_parts = 0;
+  for (int y = 0; y < x; ++y) in_earlier_parts += s_parts[(gp & ~7) + y];
+  const int entry = s_start[x] + s_before[gp] + row_rank[r] - in_earlier_parts;
+  int beg, end;
+  row_bounds(row_ptr, r, c.cap, &beg, &end);
+  const int vmax = c.causal ? u : c.N - 1;
+  int it = beg, v = 0;
+  while (it < end) {
+    v = col_idx[it];
+    if (v >= 0 && v <= vmax) break;
+    ++it;
+  }
+  if (it >= end) v = 0;
+  if (entry >= 0 && entry < c.h * c.N) items[entry] = make_int4(hq, u | (v << 16), it, end);
 }
 
 }  // namespace prism
 
 using namespace prism;
 
-// ---- workspace layout: [ V image | items[h*N] (queue entries) | hist[bins] | 8 queue counters ] ------
+// ---- workspace layout: [ V image | items[h*N] (queue entries) | row_rank[h*N] | row_part[h*N] |
+//                            bins[2*h*kClasses] | parts[h_kv*kClasses*8] | plan[24] ] ----
 struct AttnWs {
-  size_t image, items, hist, counter, total;
+  size_t image, items, row_rank, row_part, bins, parts, plan, total;
 };
 static AttnWs attn_ws(const prism_params* p) {
   const size_t N = n_blocks(p);
+  const size_t rows = (size_t)p->n_q_heads * N;
   AttnWs w;
   size_t off = 0;
-  w.image = off;   off = align_up(off + (size_t)p->n_kv_heads * N * p->block * kHeadDim * 2, 256);
-  w.items = off;   off = align_up(off + (size_t)p->n_q_heads * N * sizeof(int4), 256);
-  w.hist = off;    off = align_up(off + (kMaxBlocks + 1) * sizeof(int32_t), 256);
-  w.counter = off; off = align_up(off + 8 * sizeof(int32_t), 256);
+  w.image = off;    off = align_up(off + (size_t)p->n_kv_heads * N * p->block * kHeadDim * 2, 256);
+  w.items = off;    off = align_up(off + rows * sizeof(int4), 256);
+  w.row_rank = off; off = align_up(off + rows * sizeof(int32_t), 256);
+  w.row_part = off; off = align_up(off + rows * sizeof(int32_t), 256);
+  w.bins = off;     off = align_up(off + (size_t)2 * p->n_q_heads * kClasses * sizeof(int32_t), 256);
+  w.parts = off;    off = align_up(off + (size_t)p->n_kv_heads * kClasses * 8 * sizeof(int32_t), 256);
+  w.plan = off;     off = align_up(off + kPlanInts * sizeof(int32_t), 256);
   w.total = off;
   return w;
 }
@@ -720,37 +865,39 @@ extern "C" int prism_sparse_attn_pre(const prism_params* params, const void* q_b
   const AttnWs W = attn_ws(params);
   char* ws = static_cast<char*>(v_image);
   int4* items = reinterpret_cast<int4*>(ws + W.items);
-  int32_t* hist = reinterpret_cast<int32_t*>(ws + W.hist);
-  int32_t* counter = reinterpret_cast<int32_t*>(ws + W.counter);
+  int32_t* row_rank = reinterpret_cast<int32_t*>(ws + W.row_rank);
+  int32_t* row_part = reinterpret_cast<int32_t*>(ws + W.row_part);
+  int32_t* bins = reinterpret_cast<int32_t*>(ws + W.bins);
+  int32_t* parts = reinterpret_cast<int32_t*>(ws + W.parts);
+  int32_t* plan = reinterpret_cast<int32_t*>(ws + W.plan);
   // resident workgroups per CU: 64 KB of LDS and 4 waves each at B = 128, half of that at B = 64
   const int grid = persistent_grid(R, params->block == 128 ? 2 : 4);
   if (grid <= 0) return PRISM_ERR_HIP;
 
-  // queue order: kv heads in phases that fit the memory-side cache, longest lists first
-  QueueCfg qc;
-  qc.n_groups = h_kv * N;
-  qc.g = h / h_kv;
-  qc.N = N;
+  // queue plan: kv heads in phases that fit the memory-side cache
+  PlanCfg pc;
+  pc.h = h;
+  pc.g = h / h_kv;
+  pc.N = N;
+  pc.n_queues = grid < 8 ? 1 : 8;
   const size_t head_bytes = (size_t)L * kHeadDim * 2 * 2;                 // K + V^T of one kv head
   const size_t cache_budget = (size_t)160 << 20;
-  qc.heads_per_phase = (int)(cache_budget / head_bytes) < 1 ? 1 : (int)(cache_budget / head_bytes);
-  const int n_phases = (h_kv + qc.heads_per_phase - 1) / qc.heads_per_phase;
-  qc.levels = (N + 1) < (kMaxBlocks + 1) / n_phases ? (N + 1) : (kMaxBlocks + 1) / n_phases;
-  if (qc.levels < 2) {                                                     // more phases than bins
-    qc.heads_per_phase = (h_kv + (kMaxBlocks + 1) / 2 - 1) / ((kMaxBlocks + 1) / 2);
-    qc.levels = 2;
+  pc.heads_per_phase = (int)(cache_budget / head_bytes) < 1 ? 1 : (int)(cache_budget / head_bytes);
+  pc.n_phases = (h_kv + pc.heads_per_phase - 1) / pc.heads_per_phase;
+  if (pc.n_phases * kClasses > kMaxGroups) {                               // very many kv heads: larger phases
+    pc.n_phases = kMaxGroups / kClasses;
+    pc.heads_per_phase = (h_kv + pc.n_phases - 1) / pc.n_phases;
+    pc.n_phases = (h_kv + pc.heads_per_phase - 1) / pc.heads_per_phase;
   }
-  qc.n_bins = ((h_kv + qc.heads_per_phase - 1) / qc.heads_per_phase) * qc.levels;
-  qc.causal = (params->flags & PRISM_FLAG_BIDIRECTIONAL) ? 0 : 1;
-  qc.cap = col_count > 0x7fffffff ? 0x7fffffff : (int)col_count;     // CSR offsets are int32
+  pc.cap = col_count > 0x7fffffff ? 0x7fffffff : (int)col_count;     // CSR offsets are int32
+  pc.causal = (params->flags & PRISM_FLAG_BIDIRECTIONAL) ? 0 : 1;
 
-  hipLaunchKernelGGL(queue_reset_kernel, dim3((qc.n_bins + 255) / 256), dim3(256), 0, st, hist,
-                     qc.n_bins, counter);
-  hipLaunchKernelGGL(queue_hist_kernel, dim3(64), dim3(256), 0, st, row_ptr, qc, hist);
-  hipLaunchKernelGGL(queue_scan_kernel, dim3(1), dim3(1024), 0, st, hist, qc.n_bins);
-  hipLaunchKernelGGL(queue_fill_kernel, dim3((qc.n_groups + 255) / 256), dim3(256), 0, st, row_ptr,
-                     col_idx, qc, hist, items);
-  const int causal = qc.causal;
+  hipLaunchKernelGGL(queue_count_kernel, dim3(h), dim3(256), 0, st, row_ptr, pc, bins, parts);
+  hipLaunchKernelGGL(queue_rank_kernel, dim3(h), dim3(256), 0, st, row_ptr, pc, bins, parts, row_rank,
+                     row_part);
+  hipLaunchKernelGGL(queue_fill_kernel, dim3((R + 255) / 256), dim3(256), 0, st, row_ptr, col_idx, pc,
+                     parts, row_rank, row_part, plan, items);
+  const int causal = pc.causal;
   const bool stream_only = (params->flags & PRISM_FLAG_STREAM_ONLY) != 0;
   const dim3 grid3(grid);
   const uint16_t* qp = (const uint16_t*)q_bf16;
@@ -761,18 +908,18 @@ extern "C" int prism_sparse_attn_pre(const prism_params* params, const void* q_b
     const dim3 block3(AttnCfg<128>::kThreads);
     if (stream_only)
       hipLaunchKernelGGL((sparse_attn_kernel<128, true>), grid3, block3, 0, st, qp, kp, vp, col_idx, items,
-                         counter, op, lse, h, h_kv, L, N, causal);
+                         plan, op, lse, h, h_kv, L, N, causal);
     else
       hipLaunchKernelGGL((sparse_attn_kernel<128, false>), grid3, block3, 0, st, qp, kp, vp, col_idx, items,
-                         counter, op, lse, h, h_kv, L, N, causal);
+                         plan, op, lse, h, h_kv, L, N, causal);
   } else {
     const dim3 block3(AttnCfg<64>::kThreads);
     if (stream_only)
       hipLaunchKernelGGL((sparse_attn_kernel<64, true>), grid3, block3, 0, st, qp, kp, vp, col_idx, items,
-                         counter, op, lse, h, h_kv, L, N, causal);
+                         plan, op, lse, h, h_kv, L, N, causal);
     else
       hipLaunchKernelGGL((sparse_attn_kernel<64, false>), grid3, block3, 0, st, qp, kp, vp, col_idx, items,
-                         counter, op, lse, h, h_kv, L, N, causal);
+                         plan, op, lse, h, h_kv, L, N, causal);
   }
   return launch_status();
 }
