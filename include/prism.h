@@ -228,7 +228,8 @@ int prism_dense_csr(const prism_params* params, int32_t* row_ptr, int32_t* col_i
  *   out_bf16         : [n_q_heads, L, d] bf16, fully overwritten.
  *   lse              : [n_q_heads, L] float natural-log sum-exp of the scaled scores, or NULL.
  * workspace: prism_sparse_attn_workspace_bytes() bytes (a transposed copy of V plus the
- *            kernel's work queue: rows sorted by list length).
+ *            kernel's work queues: one entry per row, ordered by list-length class and
+ *            q-head and dealt to the eight XCDs in parts of equal work).
  * top_p, d_high, d_low and the other flags of `params` are ignored here.
  * ---------------------------------------------------------------------------------- */
 int prism_sparse_attn_workspace_bytes(const prism_params* params, size_t* bytes /* host, out */);

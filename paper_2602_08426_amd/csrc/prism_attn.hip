@@ -66,10 +66,9 @@ __global__ __launch_bounds__(256) void vt_image_kernel(const uint16_t* __restric
 // Step per listed kv block (each tile buffer is refilled as soon as its last reader is done):
 //     K(j) in LDS | start V(j) copy | S^T = K Q^T | barrier | start K(j+1) copy
 //     online softmax | wait V(j) | barrier | O^T += V^T P^T | wait K(j+1) | barrier
-// The workgroups are persistent and the stream of rows is software-pipelined as well: the
-// queue position of the row after next, the descriptor of the next row and, during the last
-// PV of a row, the Q rows and the first K tile of the next row are fetched while the current
-// row computes, so a row switch costs no exposed memory round trip.
+// The workgroups are persistent: a workgroup pulls its next row from its XCD's queue at the top
+// of the last step of the current row and reads that row's queue entry during the last PV, so
+// a row switch exposes only the load of the Q rows and of the first K tile.
 // =====================================================================================
 template <int BLK>
 struct AttnCfg {
