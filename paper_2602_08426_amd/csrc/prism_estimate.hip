@@ -20,10 +20,26 @@ struct BandMap {
   int32_t dpad[2];           // dz rounded up to a multiple of 32
 };
 
-// Band vectors of all heads and blocks: [z][term]([head][N][128] bf16), term = hi, mid, lo.
+// Band vectors of all heads and blocks: [z][term], term = hi, mid, lo, each bf16.
+//   q-heads (read once per strip of 16 q-blocks): [h][N][128], plain rows;
+//   kv heads (read by every strip of the g q-heads): behind them, in the order the score GEMM
+//   reads them: per head ceil(N/16) tiles of 16 blocks; per tile 4 k-steps of 32 band dims; per
+//   (tile, k-step) the 64 lanes' 16-byte MFMA operand pieces back to back (lane =
+//   16 * (dim / 8 % 4) + block % 16).  One operand fetch of a wave is then one contiguous KB
+//   instead of 16 rows of 64 bytes (a fetch of 16 rows costs the address path four times as
+//   long).  Blocks N .. 16*ceil(N/16)-1 of a head's last tile are zero.
 struct BandVectors {
   uint16_t* v[2][3];
 };
+constexpr int kBandTileElems = 16 * kHeadDim;          // one tile of 16 blocks
+
+// element offset of (kv head, block, band position) behind the q-heads' h*N*128 elements
+__device__ __forceinline__ size_t kv_band_offset(int h, int N, int kvh, int blk, int pz) {
+  const int n_tiles = (N + 15) >> 4;
+  const int tile = blk >> 4, r = blk & 15, ks = pz >> 5, piece = (pz >> 3) & 3, j = pz & 7;
+  return (size_t)h * N * kHeadDim + ((size_t)kvh * n_tiles + tile) * kBandTileElems + ks * 512 +
+         (piece * 16 + r) * 8 + j;
+}
 
 // =====================================================================================
 // Mean pooling (Eq. "mean-pooling") and band energies (Sec. 3.4, RMS definition).
@@ -147,19 +163,43 @@ __global__ __launch_bounds__(256) void pool_energy_kernel(
     const float rem2 = rem1 - bf16_bits_to_float(mid);
     const uint32_t lo = float_to_bf16_bits(rem2);
     const size_t o = ((size_t)head * N + blk) * kHeadDim + t;
-    const size_t vec = ((size_t)head * N + blk) * kHeadDim;
+    if (head < h) {
+      const size_t vec = ((size_t)head * N + blk) * kHeadDim;
 #pragma unroll
-    for (int z = 0; z < 2; ++z) {
-      const int pz = map.pos[z][t];
-      if (pz >= 0) {
-        bv.v[z][0][vec + pz] = (uint16_t)hi;
-        bv.v[z][1][vec + pz] = (uint16_t)mid;
-        bv.v[z][2][vec + pz] = (uint16_t)lo;
+      for (int z = 0; z < 2; ++z) {
+        const int pz = map.pos[z][t];
+        if (pz >= 0) {
+          bv.v[z][0][vec + pz] = (uint16_t)hi;
+          bv.v[z][1][vec + pz] = (uint16_t)mid;
+          bv.v[z][2][vec + pz] = (uint16_t)lo;
+        }
+        if (t >= map.dz[z] && t < map.dpad[z]) {           // zero padding of the last k-step
+          bv.v[z][0][vec + t] = 0;
+          bv.v[z][1][vec + t] = 0;
+          bv.v[z][2][vec + t] = 0;
+        }
       }
-      if (t >= map.dz[z] && t < map.dpad[z]) {           // zero padding of the last k-step
-        bv.v[z][0][vec + t] = 0;
-        bv.v[z][1][vec + t] = 0;
-        bv.v[z][2][vec + t] = 0;
+    } else {
+      // the workgroup of a head's last block also clears the blocks that pad the last tile
+      const int blk_end = blk == N - 1 ? ((N + 15) >> 4) * 16 : blk + 1;
+#pragma unroll
+      for (int z = 0; z < 2; ++z) {
+        const int pz = map.pos[z][t];
+        if (pz >= 0) {
+          const size_t e = kv_band_offset(h, N, head - h, blk, pz);
+          bv.v[z][0][e] = (uint16_t)hi;
+          bv.v[z][1][e] = (uint16_t)mid;
+          bv.v[z][2][e] = (uint16_t)lo;
+        }
+        for (int b = blk; b < blk_end; ++b) {
+          // zero padding of the last k-step (dims dz .. dpad-1), and whole padding blocks
+          if (t < map.dpad[z] && (b > blk || t >= map.dz[z])) {
+            const size_t e = kv_band_offset(h, N, head - h, b, t);
+            bv.v[z][0][e] = 0;
+            bv.v[z][1][e] = 0;
+            bv.v[z][2][e] = 0;
+          }
+        }
       }
     }
     if (head < h) {
@@ -402,14 +442,13 @@ __global__ __launch_bounds__(256) void select_kernel(
       // B fragments of the next tile are fetched while the MFMAs of the current one run
       bf16x8 bh[4], bm[4], bl[4];
       auto load_b = [&](int ct) {
-        const int brow = min(ct * 16 + (lane & 15), N - 1);
-        const size_t boff = ((size_t)kvh * N + brow) * kHeadDim + (lane >> 4) * 8;
+        const size_t boff = kv_band_offset(h, N, kvh - h, ct * 16, 0) + lane * 8;
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
           if (ks < ksteps) {
-            bh[ks] = *reinterpret_cast<const bf16x8*>(pooled_hi + boff + ks * 32);
-            bm[ks] = *reinterpret_cast<const bf16x8*>(pooled_mid + boff + ks * 32);
-            bl[ks] = *reinterpret_cast<const bf16x8*>(pooled_lo + boff + ks * 32);
+            bh[ks] = *reinterpret_cast<const bf16x8*>(pooled_hi + boff + ks * 512);
+            bm[ks] = *reinterpret_cast<const bf16x8*>(pooled_mid + boff + ks * 512);
+            bl[ks] = *reinterpret_cast<const bf16x8*>(pooled_lo + boff + ks * 512);
           }
         }
       };
@@ -639,7 +678,8 @@ static EstimateWs estimate_ws(const prism_params* p) {
   for (int z = 0; z < 2; ++z)
     for (int term = 0; term < 3; ++term) {
       w.band[z][term] = off;
-      off = align_up(off + heads * N * kHeadDim * 2, 256);
+      // q-heads: N rows each; kv heads: whole tiles of 16 blocks
+      off = align_up(off + ((size_t)p->n_q_heads * N + (size_t)p->n_kv_heads * ((N + 15) / 16 * 16)) * kHeadDim * 2, 256);
     }
   w.energy = off;    off = align_up(off + heads * N * 4 * sizeof(float), 256);
   w.inv_scale = off; off = align_up(off + (size_t)p->n_q_heads * 2 * sizeof(float), 256);
