@@ -93,6 +93,14 @@ __device__ __forceinline__ double wave_sum(double x) {
   for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off, 64);
   return x;
 }
+__device__ __forceinline__ uint32_t wave_min_u32(uint32_t x) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    const uint32_t y = (uint32_t)__shfl_xor((int)x, off, 64);
+    x = y < x ? y : x;
+  }
+  return x;
+}
 __device__ __forceinline__ int wave_sum(int x) {
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off, 64);

@@ -294,6 +294,13 @@ constexpr int kStripRows = 16;
 // (dependent DPP chains) overlap.  Selected bits are OR-ed into the rows' LDS bit words.
 constexpr int kRowsPerWave = 4;
 
+// lane `i` of (lo, hi) := the wave-uniform 64-bit word w
+__device__ __forceinline__ void put_word(uint64_t w, int i, int lane, int& lo, int& hi) {
+  const bool mine = lane == i;
+  lo = mine ? (int)(uint32_t)w : lo;
+  hi = mine ? (int)(uint32_t)(w >> 32) : hi;
+}
+
 template <int NCH>
 __device__ __forceinline__ void select_rows(const float* __restrict__ logits, int ld, int n0, int nstep,
                                             int nrows, float top_p, int lane,
@@ -324,65 +331,133 @@ __device__ __forceinline__ void select_rows(const float* __restrict__ logits, in
 
   uint32_t tstar[kRowsPerWave];
   float gstar[kRowsPerWave];
+  bool one_tie[kRowsPerWave];                        // exactly one element has the key T*
 #pragma unroll
   for (int k = 0; k < kRowsPerWave; ++k) {
     tstar[k] = 0;
     gstar[k] = 0.f;
+    one_tie[k] = false;
   }
   if (!all) {
     // per row: largest key T with mass{key > T} >= target; T* = T + 1 is then the smallest key
     // whose strictly-larger mass is < target (and T* is some element's key).  Keys are bit
     // patterns of values in [0, 1], i.e. <= 0x3F800000: bit 30 is never set.
+    // The search is a bisection on the key bits.  Beside the mass above a candidate it counts
+    // the elements above it, which tells how many elements are left between the bounds: at
+    // bit b the answer lies in [T, T + 2^(b+1) - 1], n_lo elements are above T and n_hi above
+    // T + 2^(b+1).  When n_lo - n_hi = 1 the one element in between is T* and the search of
+    // that row stops (typically after 12-16 of the 30 bits; rows whose cut falls among equal
+    // elements run to the last bit).
     uint32_t T[kRowsPerWave];
+    int n_lo[kRowsPerWave], n_hi[kRowsPerWave];
+    float g_hi[kRowsPerWave];
+    bool open[kRowsPerWave];
 #pragma unroll
-    for (int k = 0; k < kRowsPerWave; ++k) T[k] = 0;
+    for (int k = 0; k < kRowsPerWave; ++k) {
+      T[k] = 0;
+      n_hi[k] = 0;
+      g_hi[k] = 0.f;
+      int n = 0;
+#pragma unroll
+      for (int i = 0; i < NCH; ++i) n += __popcll(__builtin_amdgcn_ballot_w64(__float_as_uint(e[k][i]) > 0u));
+      n_lo[k] = n;
+      open[k] = n > 1;
+    }
     for (int bit = 29; bit >= 0; --bit) {
+      if (!(open[0] || open[1] || open[2] || open[3])) break;
       float gp[kRowsPerWave];
+      int np[kRowsPerWave];
 #pragma unroll
       for (int k = 0; k < kRowsPerWave; ++k) {
-        const uint32_t cand = T[k] | (1u << bit);
         gp[k] = 0.f;
+        np[k] = 0;
+        if (open[k]) {
+          const uint32_t cand = T[k] | (1u << bit);
 #pragma unroll
-        for (int i = 0; i < NCH; ++i) gp[k] += (__float_as_uint(e[k][i]) > cand) ? e[k][i] : 0.f;
+          for (int i = 0; i < NCH; ++i) {
+            const bool above = __float_as_uint(e[k][i]) > cand;
+            gp[k] += above ? e[k][i] : 0.f;
+            np[k] += __popcll(__builtin_amdgcn_ballot_w64(above));
+          }
+        }
       }
 #pragma unroll
-      for (int k = 0; k < kRowsPerWave; ++k)
-        if (!(wave_sum(gp[k]) < target[k])) T[k] |= (1u << bit);
+      for (int k = 0; k < kRowsPerWave; ++k) {
+        if (open[k]) {
+          const float g = wave_sum(gp[k]);
+          if (!(g < target[k])) {
+            T[k] |= (1u << bit);
+            n_lo[k] = np[k];
+          } else {
+            n_hi[k] = np[k];
+            g_hi[k] = g;
+          }
+          open[k] = n_lo[k] - n_hi[k] > 1;
+        }
+      }
     }
 #pragma unroll
     for (int k = 0; k < kRowsPerWave; ++k) {
-      tstar[k] = T[k] + 1;
-      float gp = 0.f;
+      if (n_lo[k] - n_hi[k] == 1) {
+        // the one element above T and not above the upper bound
+        uint32_t mn = 0xFFFFFFFFu;
 #pragma unroll
-      for (int i = 0; i < NCH; ++i) gp += (__float_as_uint(e[k][i]) > tstar[k]) ? e[k][i] : 0.f;
-      gstar[k] = wave_sum(gp);
+        for (int i = 0; i < NCH; ++i) {
+          const uint32_t key = __float_as_uint(e[k][i]);
+          mn = key > T[k] ? min(mn, key) : mn;
+        }
+        tstar[k] = wave_min_u32(mn);
+        gstar[k] = g_hi[k];
+        one_tie[k] = true;
+      } else {
+        // the search ran to the last bit (equal elements at the cut), or the row is empty
+        tstar[k] = T[k] + 1;
+        float gp = 0.f;
+#pragma unroll
+        for (int i = 0; i < NCH; ++i) gp += (__float_as_uint(e[k][i]) > tstar[k]) ? e[k][i] : 0.f;
+        gstar[k] = wave_sum(gp);
+      }
     }
   }
   // elements above T* are selected; elements equal to T* in ascending block order while the
-  // mass before them stays < target (stable descending order, exclusive cumulative mass < p)
+  // mass before them stays < target (stable descending order, exclusive cumulative mass < p).
+  // Lane i collects word i of the row's bits (columns 64*i .. 64*i + 63) and ORs it into LDS.
 #pragma unroll
   for (int k = 0; k < kRowsPerWave; ++k) {
     if (k >= nrows) break;
     const int n = n0 + k * nstep;
-    const float tie_val = __uint_as_float(tstar[k]);
-    int tie_base = 0;
+    int word_lo = 0, word_hi = 0;
+    if (all) {
 #pragma unroll
-    for (int i = 0; i < NCH; ++i) {
-      const int idx = i * 64 + lane;
-      bool sel;
-      if (all) {
-        sel = idx < n;
-      } else {
+      for (int i = 0; i < NCH; ++i) {
+        const uint64_t bal = __builtin_amdgcn_ballot_w64(i * 64 + lane < n);
+        put_word(bal, i, lane, word_lo, word_hi);
+      }
+    } else if (one_tie[k]) {
+      // the mass above the one element at T* is < target, so it is selected: everything >= T*
+      // (columns past the row's end hold 0 < T*)
+#pragma unroll
+      for (int i = 0; i < NCH; ++i) {
+        const uint64_t bal = __builtin_amdgcn_ballot_w64(__float_as_uint(e[k][i]) >= tstar[k]);
+        put_word(bal, i, lane, word_lo, word_hi);
+      }
+    } else {
+      const float tie_val = __uint_as_float(tstar[k]);
+      int tie_base = 0;
+#pragma unroll
+      for (int i = 0; i < NCH; ++i) {
         const uint32_t key = __float_as_uint(e[k][i]);
         const bool tie = key == tstar[k];
-        const uint64_t tb = __ballot(tie);
+        const uint64_t tb = __builtin_amdgcn_ballot_w64(tie);
         const int rank = tie_base + __popcll(tb & ((1ull << lane) - 1ull));
-        sel = (key > tstar[k]) || (tie && (gstar[k] + (float)rank * tie_val < target[k]));
+        const bool sel = (key > tstar[k]) || (tie && (gstar[k] + (float)rank * tie_val < target[k]));
         tie_base += __popcll(tb);
+        const uint64_t bal = __builtin_amdgcn_ballot_w64(sel);
+        put_word(bal, i, lane, word_lo, word_hi);
       }
-      const uint64_t bal = __ballot(sel);
-      if (lane == 0) bits[k * bits_ld + i] |= bal;
     }
+    if (lane < NCH)
+      bits[k * bits_ld + lane] |= ((uint64_t)(uint32_t)word_hi << 32) | (uint64_t)(uint32_t)word_lo;
   }
 }
 
