@@ -149,6 +149,19 @@ __device__ __forceinline__ void wait_async_loads_but_last_tile() {
   asm volatile("" ::: "memory");
 }
 
+// max / sum of a value with the lane 32 away (the two lanes that share a query), on the
+// v_permlane32_swap cross-lane path: an LDS shuffle here would queue behind the tile traffic
+// on the critical path of every step.
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float other_half_max(float x) {
+  const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float other_half_sum(float x) {
+  const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
 // Workgroup barrier of the tile loop: this wave's LDS accesses are complete, then s_barrier.
 // Unlike __syncthreads() it carries no memory fence, so the compiler adds no wait for the global
 // loads, stores and atomics in flight (the next tile copies, the previous row's output, the
@@ -410,7 +423,7 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
       for (int kt = 0; kt < KT; ++kt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[kt][r]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      mx = other_half_max(mx);
       const float m_new = fmaxf(m_run, mx * sm_scale);       // finite: every query sees a key
       if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) { // some query's max moved: rescale
         const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
@@ -517,7 +530,7 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
     step(std::true_type{});
 
     // ---- epilogue: O = O^T / l, bf16, [q][d] ----
-    const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+    const float l_tot = other_half_sum(l_run);
     const float inv_l = l_tot > 0.f ? 1.0f / l_tot : 0.f;
     uint16_t* op = out + ((size_t)hq * L + qrow) * kHeadDim;
     if (qrow < L) {
