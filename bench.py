@@ -322,7 +322,10 @@ def main() -> int:
                                         "frac": round(attn_gbs / PEAK_HBM_GBS, 4),
                                         "traffic": profiled_traffic(w.name, "sparse_attn_kernel"),
                                         "bytes_per_launch": attn_bytes, "avg_launch_ms": round(ms_attn, 4),
-                                        "stream_only_ms": None if ms_stream is None else round(ms_stream, 4)},
+                                        "stream_only_ms": None if ms_stream is None else round(ms_stream, 4),
+                                        "note": "algorithmic bytes (64 KB per listed block pair + Q in + O out); "
+                                                "tiles that rows share are served by L2, so this can exceed the HBM "
+                                                "peak: `traffic` is what left the L2s"},
         "roofline_estimate": {"kernel": "prism_estimate (5 kernels; pool_energy_kernel carries the bytes)",
                               "bound": "hbm", "achieved": round(est_gbs, 1), "peak": PEAK_HBM_GBS,
                               "unit": "GB/s", "frac": round(est_gbs / PEAK_HBM_GBS, 4),
