@@ -129,6 +129,10 @@ WORKLOADS: Dict[str, Workload] = {
     # Qwen2.5-7B-shaped layer (28 q / 4 kv heads, base 1e6), 64K, heavy-tailed K norms.
     "c5_qwen_64k": Workload("c5_qwen_64k", 28, 4, 65536, 128, 1.0e6, 0.93, 1004, "mixed",
                             k_lognormal_sigma=0.75, amp_scale=0.55),
+    # The 128K layer at block 64 (N = 2048, the largest block count the library takes): the
+    # block-size study of the paper's appendix; same tokens as c4, not a headline configuration.
+    "c4_llama_128k_b64": Workload("c4_llama_128k_b64", 32, 8, 131072, 64, 5.0e5, 0.95, 1003, "mixed",
+                                  amp_scale=0.6),
 }
 
 

@@ -182,7 +182,7 @@ def test_attention_is_deterministic_across_runs():
         assert torch.equal(a.view(torch.int16), b.view(torch.int16)) and torch.equal(la, lb)
 
 
-FULL = [("c3_llama_32k", 300), ("c5_qwen_64k", 300), ("c4_llama_128k", 900)]
+FULL = [("c3_llama_32k", 300), ("c5_qwen_64k", 300), ("c4_llama_128k", 900), ("c4_llama_128k_b64", 900)]
 
 
 @pytest.mark.timeout(1200)

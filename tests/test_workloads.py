@@ -46,7 +46,9 @@ def test_generate_is_deterministic_and_shaped():
 
 def test_all_baseline_configs_present():
     names = ["c1_2k_slash", "c2_llama_8k", "c3_llama_32k", "c4_llama_128k", "c5_qwen_64k"]
-    assert list(wl.WORKLOADS) == names
+    assert list(wl.WORKLOADS)[:5] == names
+    b64 = wl.WORKLOADS["c4_llama_128k_b64"]                # the 128K layer at block 64 (N = 2048)
+    assert (b64.seq_len, b64.block, b64.n_blocks, b64.seed) == (131072, 64, 2048, 1003)
     c4 = wl.WORKLOADS["c4_llama_128k"]
     assert (c4.n_q_heads, c4.n_kv_heads, c4.seq_len, c4.block, c4.n_blocks) == (32, 8, 131072, 128, 1024)
     c5 = wl.WORKLOADS["c5_qwen_64k"]
