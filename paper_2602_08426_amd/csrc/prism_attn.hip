@@ -34,10 +34,10 @@ __global__ __launch_bounds__(256) void vt_image_kernel(const uint16_t* __restric
   const int cnt = min(BLK, L - blk * BLK);
   for (int idx = t; idx < BLK * 16; idx += 256) {
     const int row = idx >> 4, c = idx & 15;
-    const uint4 x = row < cnt ? *reinterpret_cast<const uint4*>(src + (size_t)row * kHeadDim + c * 8)
-                              : make_uint4(0u, 0u, 0u, 0u);
+    u32x4 x = {0u, 0u, 0u, 0u};                       // V is read once: streaming (non-temporal) loads
+    if (row < cnt) x = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + (size_t)row * kHeadDim + c * 8));
     uint32_t* dst = reinterpret_cast<uint32_t*>(&tile[row][c * 8]);   // 4-byte aligned: row stride 260 B
-    dst[0] = x.x; dst[1] = x.y; dst[2] = x.z; dst[3] = x.w;
+    dst[0] = x[0]; dst[1] = x[1]; dst[2] = x[2]; dst[3] = x[3];
   }
   __syncthreads();
   constexpr int CPR = BLK / 8;                       // 16-byte chunks per image row

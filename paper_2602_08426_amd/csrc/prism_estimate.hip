@@ -101,8 +101,13 @@ __global__ __launch_bounds__(256) void pool_energy_kernel(
 #pragma unroll
   for (int it = 0; it < BLK / 16; ++it) {
     const int row = rg + it * 16;
-    v[it] = row < cnt ? *reinterpret_cast<const uint4*>(src + (size_t)row * kHeadDim + c * 8)
-                      : make_uint4(0u, 0u, 0u, 0u);
+    // streaming read (non-temporal): every token row is read once per call
+    if (row < cnt) {
+      const u32x4 x = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + (size_t)row * kHeadDim + c * 8));
+      v[it] = make_uint4(x[0], x[1], x[2], x[3]);
+    } else {
+      v[it] = make_uint4(0u, 0u, 0u, 0u);
+    }
   }
   if (kRope) {
     // This thread holds feature pairs 4c .. 4c+3 of tokens rg, rg + 16, ...: one accurate
