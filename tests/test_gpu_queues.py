@@ -16,7 +16,6 @@ import pytest
 import torch
 
 from paper_2602_08426_amd import binding as pb
-from paper_2602_08426_amd import workloads as wl
 
 pytestmark = pytest.mark.gpu
 
