@@ -40,7 +40,9 @@ typedef enum prism_status {
   PRISM_ERR_INVALID_ARG = -1,     /* null pointer, inconsistent sizes, p outside (0,1], ... */
   PRISM_ERR_UNSUPPORTED = -2,     /* head_dim != 128, block not in {64,128}, more than 2048 blocks, ... */
   PRISM_ERR_WORKSPACE = -3,       /* workspace missing, misaligned or too small */
-  PRISM_ERR_HIP = -4              /* a HIP runtime call failed (launch error) */
+  PRISM_ERR_HIP = -4,             /* a HIP runtime call failed (launch error) */
+  PRISM_ERR_TOO_LARGE = -5        /* prism_estimate_static: the problem needs more scratch than the
+                                     library's static array holds */
 } prism_status;
 
 /* flags */
@@ -134,6 +136,23 @@ int prism_estimate_bands(const prism_params* params, const prism_bands* bands /*
                          int32_t* col_idx, int64_t col_capacity,
                          int32_t* info,
                          void* workspace, size_t workspace_bytes, void* stream);
+
+/* prism_estimate for callers that cannot allocate device memory or pass a workspace (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): same
+ * arguments, outputs and results as prism_estimate, bit for bit, but the scratch is a
+ * 16 MiB device array inside the library (one copy per GPU, held until the process ends;
+ * its address is looked up on the first call on each device, which allocates nothing).
+ * Returns PRISM_ERR_TOO_LARGE, with nothing enqueued, when
+ * prism_estimate_workspace_bytes(params) exceeds 16 MiB (16 777 216 bytes; the Llama-shaped
+ * layer fits up to 32K tokens at B = 128).  The call allocates nothing.  All calls on one GPU
+ * share that GPU's array: calls that overlap there (different streams or threads) race and
+ * must be serialised by the caller; calls in a row on one stream are fine, nothing needs
+ * clearing between them. */
+int prism_estimate_static(const prism_params* params,
+                          const void* q_bf16, const void* k_bf16,
+                          uint64_t* mask_bits, int32_t* row_ptr,
+                          int32_t* col_idx, int64_t col_capacity,
+                          int32_t* info, void* stream);
 
 /* ------------------------------------------------------------------------------------
  * Estimation fused with the producer of the post-RoPE tensors.

@@ -62,7 +62,7 @@ class prism_rope(ctypes.Structure):
 
 
 EXPORTS = ("prism_version", "prism_status_string", "prism_estimate_workspace_bytes",
-           "prism_estimate", "prism_estimate_bands", "prism_rope_estimate", "prism_block_scores",
+           "prism_estimate", "prism_estimate_static", "prism_estimate_bands", "prism_rope_estimate", "prism_block_scores",
            "prism_block_scores_bands", "prism_mask_to_csr", "prism_causal_csr", "prism_dense_csr",
            "prism_sparse_attn_workspace_bytes", "prism_sparse_attn", "prism_v_image",
            "prism_sparse_attn_pre")
@@ -85,6 +85,7 @@ def _load() -> ctypes.CDLL:
     lib.prism_status_string.argtypes = [ctypes.c_int]
     lib.prism_estimate_workspace_bytes.argtypes = [P, ctypes.POINTER(sz)]
     lib.prism_estimate.argtypes = [P, vp, vp, vp, vp, vp, i64, vp, vp, sz, vp]
+    lib.prism_estimate_static.argtypes = [P, vp, vp, vp, vp, vp, i64, vp, vp]
     lib.prism_estimate_bands.argtypes = [P, PB, vp, vp, vp, vp, vp, i64, vp, vp, sz, vp]
     lib.prism_rope_estimate.argtypes = [P, ctypes.POINTER(prism_rope), PB, vp, vp, vp, vp, vp, vp, vp,
                                         i64, vp, vp, sz, vp]
@@ -186,6 +187,14 @@ def prism_estimate(params: prism_params, q: torch.Tensor, k: torch.Tensor, mask_
     _check(_load().prism_estimate(ctypes.byref(params), _ptr(q), _ptr(k), _ptr(mask_bits),
                                   _ptr(row_ptr), _ptr(col_idx), col_capacity, _ptr(info),
                                   _ptr(workspace), workspace.numel(), _stream()), "prism_estimate")
+
+
+def prism_estimate_static(params: prism_params, q: torch.Tensor, k: torch.Tensor,
+                          mask_bits: torch.Tensor, row_ptr: torch.Tensor, col_idx: torch.Tensor,
+                          col_capacity: int, info: torch.Tensor) -> None:
+    _check(_load().prism_estimate_static(ctypes.byref(params), _ptr(q), _ptr(k), _ptr(mask_bits),
+                                         _ptr(row_ptr), _ptr(col_idx), col_capacity, _ptr(info),
+                                         _stream()), "prism_estimate_static")
 
 
 def prism_estimate_bands(params: prism_params, bands: prism_bands, q: torch.Tensor, k: torch.Tensor,

@@ -8,6 +8,8 @@
 //   scan/fill kernels  : bit rows -> CSR index lists
 #include "prism_common.h"
 
+#include <mutex>
+
 namespace prism {
 
 // The two bands as maps from head dims to band positions.  A band is a list of slices of
@@ -865,6 +867,7 @@ extern "C" const char* prism_status_string(int status) {
     case PRISM_ERR_UNSUPPORTED: return "unsupported configuration";
     case PRISM_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case PRISM_ERR_HIP: return "HIP runtime error";
+    case PRISM_ERR_TOO_LARGE: return "problem exceeds the library's static scratch (prism_estimate_static)";
     default: return "unknown status";
   }
 }
@@ -915,6 +918,52 @@ extern "C" int prism_estimate(const prism_params* params, const void* q_bf16, co
   const prism_bands bands = default_bands(params);
   return prism_estimate_bands(params, &bands, q_bf16, k_bf16, mask_bits, row_ptr, col_idx,
                               col_capacity, info, workspace, workspace_bytes, stream);
+}
+
+// ---- the estimate for callers that cannot allocate -----------------------------------
+// The scratch of prism_estimate lives in one file-scope device array instead of a caller
+// workspace.  `scratch` below is only the host-side handle of that array: the address of the
+// copy a given GPU holds is asked from the runtime once per device and kept; kernels and
+// everything else on the host side use that address.
+constexpr size_t kStaticScratchBytes = (size_t)16 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices];
+static std::mutex g_scratch_mutex;
+
+static int static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return PRISM_ERR_HIP;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) {
+      (void)hipGetLastError();
+      return PRISM_ERR_HIP;
+    }
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return PRISM_OK;
+}
+
+extern "C" int prism_estimate_static(const prism_params* params, const void* q_bf16,
+                                     const void* k_bf16, uint64_t* mask_bits, int32_t* row_ptr,
+                                     int32_t* col_idx, int64_t col_capacity, int32_t* info,
+                                     void* stream) {
+  int rc = check_params(params);
+  if (rc != PRISM_OK) return rc;
+  rc = check_bands(params);
+  if (rc != PRISM_OK) return rc;
+  if (estimate_ws(params).total > kStaticScratchBytes) return PRISM_ERR_TOO_LARGE;
+  void* ws = nullptr;
+  rc = static_scratch(&ws);
+  if (rc != PRISM_OK) return rc;
+  // every part of the scratch that a kernel reads is written earlier in the same call, so the
+  // previous call's contents need no clearing
+  return prism_estimate(params, q_bf16, k_bf16, mask_bits, row_ptr, col_idx, col_capacity, info, ws,
+                        kStaticScratchBytes, stream);
 }
 
 extern "C" int prism_rope_estimate(const prism_params* params, const prism_rope* rope,
