@@ -163,16 +163,21 @@ def softmax_rows(logits: np.ndarray) -> np.ndarray:
 
 
 def top_p(probs: np.ndarray, p: float) -> np.ndarray:
-    """App. C: sort descending, cumulative sum, keep rank k while the mass
-    strictly before it is < p, scatter back.  probs: [..., N] -> bool [..., N].
-    Ties are ordered by a stable sort (lower index first)."""
-    order = np.argsort(-probs, axis=-1, kind="stable")
-    sorted_probs = np.take_along_axis(probs, order, axis=-1)
-    cumulative = np.cumsum(sorted_probs, axis=-1)
-    sorted_mask = (cumulative - sorted_probs) < p
-    mask = np.zeros(probs.shape, dtype=bool)
-    np.put_along_axis(mask, order, sorted_mask, axis=-1)
-    return mask
+    """Top-p selection of App. C in words: per row, walk the blocks from the most to the
+    least probable (equal probabilities: lower index first) and take a block as long as the
+    mass of the blocks already taken is below p; the walk stops with the block that carries
+    the taken mass to p or beyond, so the result is the smallest set of most probable blocks
+    whose mass reaches p.  probs: [..., N] -> bool [..., N]."""
+    n = probs.shape[-1]
+    rows = np.ascontiguousarray(probs, dtype=np.float64).reshape(-1, n)
+    taken = np.zeros(rows.shape, dtype=bool)
+    for r in range(rows.shape[0]):
+        ranked = np.argsort(-rows[r], kind="stable")
+        mass_after = np.add.accumulate(rows[r][ranked])      # mass once rank k has been taken
+        reached = np.nonzero(mass_after >= p)[0]
+        n_taken = int(reached[0]) + 1 if len(reached) else n
+        taken[r, ranked[:n_taken]] = True
+    return taken.reshape(probs.shape)
 
 
 Segments = Sequence[Tuple[int, int]]          # (start, width) slices of the head dim
@@ -226,67 +231,46 @@ def prism_select(Q: np.ndarray, K: np.ndarray, d_h: int, d_l: int, B: int, p: fl
     h_kv = K.shape[0]
     if h % h_kv:
         raise ValueError("n_q_heads must be a multiple of n_kv_heads")
-    g = h // h_kv
-    kv_of = np.arange(h) // g
+    kv_of = np.arange(h) // (h // h_kv)            # q-head -> its kv head
 
-    # 1. pooling & slicing
-    Qb, Kb = pool(Q, B), pool(K, B)
+    Qb, Kb = pool(Q, B), pool(K, B)                # block means, Eq. "mean-pooling"
     N = Qb.shape[1]
-    bands = band_dims(d, d_h, d_l, bands)
-    width = {z: len(idx) for z, idx in bands.items()}
+    dims = band_dims(d, d_h, d_l, bands)
+    allowed = np.tril(np.ones((N, N), dtype=bool)) if causal else np.ones((N, N), dtype=bool)
 
-    # 2. RMS energies
+    # RMS(Xbar) over the whole head and over each band (one scalar per head)
     rms_q = {"full": rms(Qb)}
     rms_k = {"full": rms(Kb)}
-    for z, sl in bands.items():
-        if width[z] > 0:
-            rms_q[z] = rms(Qb[:, :, sl])
-            rms_k[z] = rms(Kb[:, :, sl])
-        else:
-            rms_q[z] = np.zeros(h)
-            rms_k[z] = np.zeros(h_kv)
+    for z, idx in dims.items():
+        rms_q[z] = rms(Qb[:, :, idx]) if len(idx) else np.zeros(h)
+        rms_k[z] = rms(Kb[:, :, idx]) if len(idx) else np.zeros(h_kv)
 
-    tri = np.tril(np.ones((N, N), dtype=bool)) if causal else np.ones((N, N), dtype=bool)
     tau: Dict[str, np.ndarray] = {}
     scale: Dict[str, np.ndarray] = {}
     logits: Dict[str, np.ndarray] = {}
     probs: Dict[str, np.ndarray] = {}
     band_masks: Dict[str, np.ndarray] = {}
-    for z, sl in bands.items():
-        d_z = width[z]
-        if d_z == 0:                               # band disabled
+    for z, idx in dims.items():
+        d_z = len(idx)
+        logits[z] = np.full((h, N, N), -np.inf)
+        probs[z] = np.zeros((h, N, N))
+        band_masks[z] = np.zeros((h, N, N), dtype=bool)
+        if d_z == 0:                               # band switched off
             tau[z] = np.full(h, np.nan)
             scale[z] = np.full(h, np.nan)
-            logits[z] = np.full((h, N, N), -np.inf)
-            probs[z] = np.zeros((h, N, N))
-            band_masks[z] = np.zeros((h, N, N), dtype=bool)
             continue
-        # 3. calibration
-        if calibrate:
-            tau[z] = temperature(d_z, d, rms_q[z], rms_q["full"],
-                                 rms_k[z][kv_of], rms_k["full"][kv_of])
-        else:
-            tau[z] = np.ones(h)
-        # 4. dual-band scoring
+        # S_z = softmax( Qbar_z Kbar_z^T / (sqrt(d_z) tau_z) ), tau_z from the band energies
+        tau[z] = (temperature(d_z, d, rms_q[z], rms_q["full"], rms_k[z][kv_of], rms_k["full"][kv_of])
+                  if calibrate else np.ones(h))
         scale[z] = np.sqrt(d_z) * tau[z]
-        raw = np.einsum("hud,hvd->huv", Qb[:, :, sl], Kb[kv_of][:, :, sl])
-        lz = np.empty_like(raw)
         for hq in range(h):
-            s = scale[z][hq]
-            if np.isfinite(s) and s > 0.0:
-                lz[hq] = raw[hq] / s
-            else:                                   # zero band energy -> flat logits
-                lz[hq] = 0.0
-        lz = np.where(tri[None], lz, -np.inf)
-        logits[z] = lz
-        # 5. selection
-        probs[z] = softmax_rows(lz)
-        if p >= 1.0:
-            mz = np.ones((h, N, N), dtype=bool)
-        else:
-            mz = top_p(probs[z], p)
-        mz &= tri[None]
-        band_masks[z] = mz
+            Qz, Kz = Qb[hq][:, idx], Kb[kv_of[hq]][:, idx]
+            usable = np.isfinite(scale[z][hq]) and scale[z][hq] > 0.0
+            l = Qz @ Kz.T / scale[z][hq] if usable else np.zeros((N, N))   # no band energy: flat
+            logits[z][hq] = np.where(allowed, l, -np.inf)
+            probs[z][hq] = softmax_rows(logits[z][hq])
+            chosen = np.ones((N, N), dtype=bool) if p >= 1.0 else top_p(probs[z][hq], p)
+            band_masks[z][hq] = chosen & allowed
 
     mask = band_masks["high"] | band_masks["low"]
     forced = np.zeros((h, N, N), dtype=bool)
@@ -296,7 +280,7 @@ def prism_select(Q: np.ndarray, K: np.ndarray, d_h: int, d_l: int, B: int, p: fl
         forced[:, :, 0] = True
     mask = mask | forced
     return Selection(mask, band_masks, logits, probs, tau, scale, Qb, Kb, rms_q, rms_k,
-                     tri, forced)
+                     allowed, forced)
 
 
 def mask_to_csr(mask: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
@@ -327,7 +311,7 @@ class Tolerance:
 
 
 def selection_tolerance(sel: Selection, p: float, logit_margin: float = 1e-3,
-                        p_margin: float = 1e-3) -> Tolerance:
+                        p_margin: float = 2e-5) -> Tolerance:
     """Blocks whose selection may legitimately differ in another implementation.
 
     Per band and row the selected set is the top-k* blocks by score, the cutoff lying
@@ -336,8 +320,12 @@ def selection_tolerance(sel: Selection, p: float, logit_margin: float = 1e-3,
       - it is selected and its score is within `logit_margin` of l_out, or it is
         unselected and within `logit_margin` of l_in (a score error of that size could
         swap it across the cutoff; exact ties fall here too), or
-      - it enters the set somewhere between p - p_margin and p + p_margin (the
-        cumulative mass at the cutoff is that close to p).
+      - it enters the set somewhere between p - p_margin and p + p_margin: the taken mass
+        at the cutoff is so close to p that fp32 arithmetic decides differently from fp64.
+        p_margin is sized for an implementation whose logits are within 2e-5 + 4e-6 |l| of
+        these (1.2e-4 at |l| = 25): the mass share A / (A + B) of a top set then moves by at
+        most A B / (A + B)^2 * 2 * 1.2e-4 <= 1.2e-5 near p = 0.95, plus about 2e-6 of fp32
+        rounding in the exponentials and their sums.
     must = union over bands of (selected minus don't-care); must_not = complement of the
     union over bands of (selected or don't-care)."""
     h, N, _ = sel.mask.shape

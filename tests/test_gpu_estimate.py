@@ -2,7 +2,7 @@
 
 Bar: integer outputs (CSR vs the bit mask, caller-mask compaction, causal lists) bit-exact;
 block masks exact outside the oracle's don't-care set (scores within 1e-3 of the selection
-cutoff, or cumulative mass within 1e-3 of p); pooled vectors / scales / logits within
+cutoff, or taken mass within 2e-5 of p, the fp32-vs-fp64 slack the oracle derives); pooled vectors / scales / logits within
 fp32-accumulation tolerances far below that margin.
 """
 import numpy as np
@@ -22,7 +22,7 @@ def _inputs(w):
     return Qb, Kb, Vb, pb.bf16_bits_to_device(Qb), pb.bf16_bits_to_device(Kb)
 
 
-def _check_mask(w, gpu_mask, sel, p, max_dont_care=0.02):
+def _check_mask(w, gpu_mask, sel, p, max_dont_care=0.005):
     tol = orc.selection_tolerance(sel, p)
     missing = tol.must & ~gpu_mask
     extra = tol.must_not & gpu_mask
@@ -102,7 +102,7 @@ def test_parameter_variants(over, okw):
                            kw["p"], calibrate=kw["calibrate"])
     params = gu.params_for(w, **over)
     res = gu.gpu_estimate(params, qd, kd)
-    _check_mask(w, res["mask"], sel, kw["p"], max_dont_care=0.05)
+    _check_mask(w, res["mask"], sel, kw["p"], max_dont_care=0.02)
     _check_csr(res, w.n_q_heads, w.n_blocks)
     if kw["p"] >= 1.0:
         np.testing.assert_array_equal(res["mask"], np.tril(np.ones((50, 50), bool))[None].repeat(4, 0))
@@ -116,6 +116,37 @@ def test_many_blocks_path_n_2048():
     res = gu.gpu_estimate(gu.params_for(w), qd, kd)
     _check_mask(w, res["mask"], sel, w.top_p)
     _check_csr(res, 1, w.n_blocks)
+
+
+@pytest.mark.parametrize("N,B", [(100, 128), (200, 128), (500, 128), (1000, 128), (2000, 64)])
+def test_exact_selection_on_separated_rows(N, B):
+    """Rows whose block probabilities are distinct and well apart: every token of a block carries
+    the same seeded vector, so the block logits are spread like independent normals.  On every
+    row where the oracle finds no block near the cutoff (empty don't-care set, checked on the
+    CPU) the GPU mask must equal the oracle's bit for bit: the same count, the block that carries
+    the mass across p included, no +-1.  N = 100 .. 2000 walks through all five register
+    layouts of the selection (2, 4, 8, 16 and 32 columns per lane)."""
+    rng = np.random.default_rng(7000 + N)
+    h, hkv, L = 2, 1, N * B
+    def blocks(nh, scale):
+        x = (rng.standard_normal((nh, N, 1, 128)) * scale).astype(np.float32)
+        return wl.f32_to_bf16_bits(np.broadcast_to(x, (nh, N, B, 128)).reshape(nh, L, 128))
+    Qb, Kb = blocks(h, 1.0), blocks(hkv, 1.5)
+    qd, kd = pb.bf16_bits_to_device(Qb), pb.bf16_bits_to_device(Kb)
+    p = 0.9
+    sel = orc.prism_select(orc.bf16_to_f64(Qb), orc.bf16_to_f64(Kb), 64, 96, B, p)
+    tol = orc.selection_tolerance(sel, p)
+    dont_care = (~tol.must) & (~tol.must_not) & tol.valid[None]
+    clean = ~dont_care.any(axis=-1)                       # [h, N] rows without any doubtful block
+    assert clean.mean() > 0.6, clean.mean()
+    res = gu.gpu_estimate(pb.make_params(h, hkv, L, B, top_p=p), qd, kd)
+    diff = (res["mask"] != sel.mask).any(axis=-1)
+    assert not (diff & clean).any(), f"{(diff & clean).sum()} clean rows differ, first {np.argwhere(diff & clean)[:5]}"
+    np.testing.assert_array_equal(res["mask"].sum(-1)[clean], sel.mask.sum(-1)[clean])
+    lens = sel.mask.sum(-1)[clean]
+    print(f"  N={N}: {clean.sum()} of {clean.size} rows clean, selected counts {lens.min()}..{lens.max()}", flush=True)
+    assert lens.max() > 2 * 64 * (N > 128)                # long lists really occur
+    _check_mask(None, res["mask"], sel, p, max_dont_care=0.02)
 
 
 def test_degenerate_inputs_zero_and_constant():
