@@ -48,6 +48,53 @@ def profiled_traffic(workload: str, kernel: str):
     return None
 
 
+PEAK_PROBES = (("mfma_32x32x16_bf16_only", (1, 2)), ("mfma_plus_lds_read_1_to_1", (2,)),
+               ("mfma_plus_lds_read_1_to_2", (1, 2)), ("lds_read_b128_only", (2,)),
+               ("valu_fma_f32", (1,)), ("valu_exp_f32", (1,)), ("mfma_plus_4fma_1exp_same_wave", (1, 2)),
+               ("stream_read_16B", (16, 128, 1024, 8192)))
+
+
+def measure_peaks(which=None):
+    """Achievable peaks of this GPU from the probe loops of libprism_peaks.so (bench-only library
+    built beside libprism.so): rows of {probe, arg, ms, rate, unit, shader_mhz, cycles_per_op}."""
+    import ctypes
+    path = os.path.join(ROOT, "paper_2602_08426_amd", "libprism_peaks.so")
+    if not os.path.exists(path):
+        raise FileNotFoundError(f"{path} not found: run __graft_entry__.build() first")
+    lib = ctypes.CDLL(path)
+    lib.prism_peaks_name.restype = ctypes.c_char_p
+    lib.prism_peaks_measure.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_double)]
+    index = {lib.prism_peaks_name(i).decode(): i for i in range(lib.prism_peaks_count())}
+    rows = []
+    for name, args in PEAK_PROBES:
+        if which is not None and name not in which:
+            continue
+        for arg in args:
+            out = (ctypes.c_double * 4)()
+            if lib.prism_peaks_measure(index[name], arg, out) != 0:
+                raise RuntimeError(f"peak probe {name}({arg}) failed")
+            ms, work = out[0], out[1]
+            if name.startswith("mfma"):
+                rate, unit = work / ms / 1e9, "TFLOP/s"
+            elif name.startswith("valu"):
+                rate, unit = work * 64 / ms / 1e9, "Tlane-op/s"
+            else:
+                rate, unit = work / ms / 1e6, "GB/s"
+            rows.append({"probe": name, "arg": arg, "ms": round(ms, 4), "rate": round(rate, 1), "unit": unit,
+                         "shader_mhz": round(out[2], 0), "cycles_per_op": round(out[3], 2)})
+            log(f"peak {name}({arg}): {rate:.1f} {unit}, {out[2]:.0f} MHz, {out[3]:.2f} cycles/op")
+    return rows
+
+
+def peaks_main() -> int:
+    rows = measure_peaks()
+    print(json.dumps({"metric": "achievable peaks of this GPU (probe loops of libprism_peaks.so)",
+                      "published": {"bf16_mfma_tflops": PEAK_BF16_TFLOPS, "hbm_gbs": PEAK_HBM_GBS},
+                      "arg_meaning": "workgroups per CU for the on-chip probes, footprint in MiB for stream_read_16B",
+                      "rows": rows}), flush=True)
+    return 0
+
+
 def cpu_baseline(w, Qb, Kb, Vb, mask, flop_dense: float, budget_rows: int = 48):
     """Time the oracle (as it stands) on a bounded sample and scale to the whole workload:
     selection on one kv group, block-masked attention on a seeded sample of (head, q-block)
@@ -141,6 +188,10 @@ def main() -> int:
     ap.add_argument("--estimate-curve", action="store_true",
                     help="instead of the step benchmark: prism_estimate time vs sequence length for "
                          "B = 128 and B = 64 (the block-size study of the paper's App. E), one JSON line")
+    ap.add_argument("--peaks", action="store_true",
+                    help="instead of the step benchmark: run the machine-peak probes (MFMA-only loop, MFMA with "
+                         "LDS operand reads, LDS reads, VALU, streaming reads over several footprints), one JSON line")
+    ap.add_argument("--no-peaks", action="store_true", help="skip the two peak probes of the default run")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (known HBM traffic) for counter calibration")
     args = ap.parse_args()
@@ -161,6 +212,8 @@ def main() -> int:
     pb._load()                                   # fails loudly if libprism.so is missing
     if args.estimate_curve:
         return estimate_curve(args)
+    if args.peaks:
+        return peaks_main()
     w = wl.WORKLOADS[args.workload]
     h, hkv, L, B, N, d = w.n_q_heads, w.n_kv_heads, w.seq_len, w.block, w.n_blocks, w.head_dim
 

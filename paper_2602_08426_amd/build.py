@@ -10,6 +10,9 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libprism.so")
 SOURCES = ["prism_estimate.hip", "prism_attn.hip"]
+# bench-only probes of the machine's achievable peaks (bench.py --peaks); not part of libprism
+PEAKS_LIB_PATH = os.path.join(HERE, "libprism_peaks.so")
+PEAKS_SOURCES = ["prism_peaks.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -21,11 +24,10 @@ HIPCC_FLAGS = [
 ]
 
 
-def build_library(verbose: bool = False, extra_flags: list[str] | None = None) -> str:
-    """Compile every HIP source into paper_2602_08426_amd/libprism.so and return its path."""
+def _compile(sources: list[str], out_path: str, verbose: bool, extra_flags: list[str] | None) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     cmd = [hipcc, *HIPCC_FLAGS, *(extra_flags or []), "-I", os.path.join(ROOT, "include"), "-I", CSRC,
-           *[os.path.join(CSRC, s) for s in SOURCES], "-o", LIB_PATH]
+           *[os.path.join(CSRC, s) for s in sources], "-o", out_path]
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
@@ -35,7 +37,21 @@ def build_library(verbose: bool = False, extra_flags: list[str] | None = None) -
         raise RuntimeError(f"hipcc failed ({res.returncode}):\n{err}")
     if verbose and err.strip():
         print(err, file=sys.stderr)
-    return LIB_PATH
+    return out_path
+
+
+def build_library(verbose: bool = False, extra_flags: list[str] | None = None) -> str:
+    """Compile every HIP source into paper_2602_08426_amd/libprism.so (and the bench-only
+    libprism_peaks.so beside it) and return the path of libprism.so."""
+    # the hand-scheduled row loop of the 64-queries-per-wave attention kernel is generated
+    gen = subprocess.run([sys.executable, os.path.join(CSRC, "gen_attn_w64.py"),
+                          os.path.join(CSRC, "prism_attn_w64_body.inc")], capture_output=True, text=True)
+    if gen.returncode != 0:
+        raise RuntimeError(f"gen_attn_w64.py failed:\n{gen.stderr}")
+    if verbose:
+        print(gen.stderr.strip(), flush=True)
+    _compile(PEAKS_SOURCES, PEAKS_LIB_PATH, verbose, None)
+    return _compile(SOURCES, LIB_PATH, verbose, extra_flags)
 
 
 if __name__ == "__main__":

@@ -177,7 +177,11 @@ __device__ __forceinline__ void tile_barrier() {
 // pull counters[8] }; a workgroup's pulls p = 0, 1, 2, ... from queue x are the entries
 // start[x] + p while p < len[x].
 enum { kItemEnd = 0, kItemRow = 2 };
-constexpr int kPlanStart = 0, kPlanLen = 8, kPlanCounter = 16, kPlanInts = 24;
+constexpr int kPlanStart = 0, kPlanLen = 8, kPlanCounter = 16, kPlanFlags = 24, kPlanInts = 32;
+// plan[kPlanFlags]: bit 0 = some list holds an entry that must be skipped (negative, beyond the
+// row's last admissible block): such lists go through the general kernel, clean lists through the
+// 64-queries-per-wave kernel; each of the two kernels returns at once when it is not its turn.
+constexpr int kFlagDirtyLists = 1;
 
 __device__ __forceinline__ int item_kind(int pulled, int seg_start, int seg_len, int* entry) {
   if (pulled >= seg_len) return kItemEnd;
@@ -192,9 +196,11 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ vt,
     const int32_t* __restrict__ col_idx, const int4* __restrict__ items, int32_t* __restrict__ plan,
     uint16_t* __restrict__ out, float* __restrict__ lse, int h, int h_kv, int L, int N,
-    int causal) {
+    int causal, int only_dirty) {
 #if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the kernel's signature
   using C = AttnCfg<BLK>;
+  // launched behind the 64-queries-per-wave kernel: only lists that kernel does not take
+  if (only_dirty && (plan[kPlanFlags] & kFlagDirtyLists) == 0) return;
   constexpr int KT = BLK / 32;                       // 32-key tiles per kv block
   __shared__ __attribute__((aligned(16))) char lds_k[C::kTileBytes];
   __shared__ __attribute__((aligned(16))) char lds_v[C::kTileBytes];
@@ -564,6 +570,140 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
 }
 
 // =====================================================================================
+// The same computation with 64 queries per wave (B = 128, whole blocks, clean lists): workgroup =
+// 2 waves = one (q-head, q-block) row, one wave per SIMD, two workgroups per CU.  Every K / V^T
+// fragment read from LDS feeds two MFMAs, K and V^T travel as 64-key half tiles through two LDS
+// buffers each, and the row loop (software-pipelined over half-steps, softmax in the shadow of the
+// neighbouring half-steps' MFMAs, accumulators and Q fragments in AGPRs) is a generated,
+// hand-scheduled instruction sequence: prism_attn_w64_body.inc, written by gen_attn_w64.py, which
+// also documents the register map and the pipeline.  This function supplies the persistent-workgroup
+// loop around it: the same per-XCD queues as the general kernel.
+// =====================================================================================
+__global__ __launch_bounds__(128) void sparse_attn_w64_kernel(
+    const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ vt,
+    const int32_t* __restrict__ col_idx, const int4* __restrict__ items, int32_t* __restrict__ plan,
+    uint16_t* __restrict__ out, float* __restrict__ lse, int h, int h_kv, int L, int N, int causal) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  __shared__ __attribute__((aligned(1024))) char lds_tiles[65536];
+  __shared__ int s_pulled, s_queue;
+  if ((plan[kPlanFlags] & kFlagDirtyLists) != 0) return;    // the general kernel takes this call
+
+  const int t = threadIdx.x;
+  const int lane = t & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+  const int g = h / h_kv;
+  const int n_queues = gridDim.x < 8 ? 1 : 8;
+  int my_queue = blockIdx.x % n_queues;
+  int seg_start = plan[kPlanStart + my_queue];
+  int seg_len = plan[kPlanLen + my_queue];
+  int32_t* counter = plan + kPlanCounter;
+  const uint32_t lds_base = (uint32_t)(size_t)lds_tiles;
+  const uint32_t k_bytes = (uint32_t)L * kHeadDim * 2;
+  const uint32_t vt_bytes = (uint32_t)N * 128u * kHeadDim * 2;
+
+  int pulled = 0;
+  if (t == 0) pulled = atomicAdd(counter + my_queue, 1);
+  for (;;) {
+    // hand the pulled queue position to both waves
+    __syncthreads();
+    if (t == 0) s_pulled = pulled;
+    __syncthreads();
+    int pos = __builtin_amdgcn_readfirstlane(s_pulled);
+    if (pos >= seg_len) {
+      // Own queue exhausted: go on with rows of the nearest queue that still has some.  A pull
+      // counter only grows, so a queue seen exhausted stays so; the atomic decides who gets a row.
+      __syncthreads();
+      if (wave == 0) {
+        int found_pos = -1, found_queue = -1;
+        for (;;) {
+          int pulls = 0x7fffffff, len = 0;
+          if (lane < n_queues) {
+            pulls = __hip_atomic_load(counter + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            len = plan[kPlanLen + lane];
+          }
+          const unsigned long long open = __ballot(pulls < len);
+          if (open == 0ull) break;
+          int pick = -1;
+          for (int s = 1; s <= n_queues && pick < 0; ++s) {
+            const int x = (my_queue + s) % n_queues;
+            if ((open >> x) & 1ull) pick = x;
+          }
+          int got = 0;
+          if (lane == 0) got = atomicAdd(counter + pick, 1);
+          got = __builtin_amdgcn_readfirstlane(got);
+          if (got < plan[kPlanLen + pick]) {
+            found_pos = got;
+            found_queue = pick;
+            break;
+          }
+        }
+        if (lane == 0) {
+          s_pulled = found_pos;
+          s_queue = found_queue;
+        }
+      }
+      __syncthreads();
+      pos = __builtin_amdgcn_readfirstlane(s_pulled);
+      const int nq = __builtin_amdgcn_readfirstlane(s_queue);
+      if (nq < 0) break;                                    // every queue is exhausted
+      my_queue = nq;
+      seg_start = plan[kPlanStart + my_queue];
+      seg_len = plan[kPlanLen + my_queue];
+    }
+    const int4 it0 = items[seg_start + pos];
+    const int hq = __builtin_amdgcn_readfirstlane(it0.x);
+    const int u = __builtin_amdgcn_readfirstlane(it0.y) & 0xffff;
+    const int c_first = (__builtin_amdgcn_readfirstlane(it0.y) >> 16) & 0xffff;   // first listed block
+    const int it = __builtin_amdgcn_readfirstlane(it0.z);
+    const int end = __builtin_amdgcn_readfirstlane(it0.w);
+    // the next row's queue position is pulled now and looked at after this row
+    if (t == 0) pulled = atomicAdd(counter + my_queue, 1);
+
+    const size_t row0 = (size_t)hq * L + (size_t)u * 128 + (size_t)wave * 64;   // this wave's first query
+    if (it >= end) {
+      // a row without entries: o = 0, lse = -inf
+      const int r = lane;                                   // 64 rows per wave, one per lane
+      uint16_t* op = out + (row0 + r) * kHeadDim;
+#pragma unroll
+      for (int c = 0; c < 16; ++c) *reinterpret_cast<uint4*>(op + c * 8) = make_uint4(0u, 0u, 0u, 0u);
+      if (lse != nullptr) lse[row0 + r] = -INFINITY;
+      continue;
+    }
+    const uint16_t* q_row = q + row0 * kHeadDim;
+    uint16_t* o_row = out + row0 * kHeadDim;
+    float* lse_row = lse != nullptr ? lse + row0 : nullptr;
+    const int kvh = hq / g;
+    const uint16_t* k_head = k + (size_t)kvh * L * kHeadDim;
+    const uint16_t* vt_head = vt + (size_t)kvh * N * 128 * kHeadDim;
+    const int32_t* col_row = col_idx + it;
+    const int n_entries = end - it;
+#include "prism_attn_w64_body.inc"
+  }
+#endif
+}
+
+// One wave per row: does the row's list hold an entry the attention kernels must skip?
+__global__ __launch_bounds__(256) void queue_validate_kernel(const int32_t* __restrict__ row_ptr,
+                                                             const int32_t* __restrict__ col_idx, int h,
+                                                             int N, int cap, int causal,
+                                                             int32_t* __restrict__ plan) {
+  const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (r >= h * N) return;
+  int b = row_ptr[r], e = row_ptr[r + 1];
+  const bool clamped = b < 0 || b > cap || e < b || e > cap;
+  b = b < 0 ? 0 : (b > cap ? cap : b);
+  e = e < b ? b : (e > cap ? cap : e);
+  const int vmax = causal ? r % N : N - 1;
+  bool bad = clamped;
+  for (int i = b + lane; i < e; i += 64) {
+    const int v = col_idx[i];
+    bad |= v < 0 || v > vmax;
+  }
+  if (__ballot(bad) != 0ull && lane == 0) atomicOr(plan + kPlanFlags, kFlagDirtyLists);
+}
+
+// =====================================================================================
 // Work queues.  The rows (q-head, q-block) are put in the order
 //     (phase, length class, q-head, q-block descending)
 // and every (phase, class) group of that order is cut into one contiguous part per queue, the
@@ -606,7 +746,8 @@ __device__ __forceinline__ void row_bounds(const int32_t* __restrict__ row_ptr, 
 // bins = { rows[h][kClasses], work[h][kClasses] }; parts[n_phases][kClasses][8] is cleared here.
 __global__ __launch_bounds__(256) void queue_count_kernel(const int32_t* __restrict__ row_ptr, PlanCfg c,
                                                           int32_t* __restrict__ bins,
-                                                          int32_t* __restrict__ parts) {
+                                                          int32_t* __restrict__ parts,
+                                                          int32_t* __restrict__ plan) {
   __shared__ int s_rows[kClasses], s_work[kClasses];
   const int t = threadIdx.x, hq = blockIdx.x;
   if (t < kClasses) {
@@ -614,6 +755,7 @@ __global__ __launch_bounds__(256) void queue_count_kernel(const int32_t* __restr
     s_work[t] = 0;
   }
   for (int i = hq * 256 + t; i < c.n_phases * kClasses * 8; i += c.h * 256) parts[i] = 0;
+  if (hq == 0 && t < kPlanInts - kPlanFlags) plan[kPlanFlags + t] = 0;
   __syncthreads();
   for (int u = t; u < c.N; u += 256) {
     int beg, end;
@@ -904,7 +1046,7 @@ extern "C" int prism_sparse_attn_pre(const prism_params* params, const void* q_b
   pc.cap = col_count > 0x7fffffff ? 0x7fffffff : (int)col_count;     // CSR offsets are int32
   pc.causal = (params->flags & PRISM_FLAG_BIDIRECTIONAL) ? 0 : 1;
 
-  hipLaunchKernelGGL(queue_count_kernel, dim3(h), dim3(256), 0, st, row_ptr, pc, bins, parts);
+  hipLaunchKernelGGL(queue_count_kernel, dim3(h), dim3(256), 0, st, row_ptr, pc, bins, parts, plan);
   hipLaunchKernelGGL(queue_rank_kernel, dim3(h), dim3(256), 0, st, row_ptr, pc, bins, parts, row_rank,
                      row_part);
   hipLaunchKernelGGL(queue_fill_kernel, dim3((R + 255) / 256), dim3(256), 0, st, row_ptr, col_idx, pc,
@@ -916,22 +1058,34 @@ extern "C" int prism_sparse_attn_pre(const prism_params* params, const void* q_b
   const uint16_t* kp = (const uint16_t*)k_bf16;
   const uint16_t* vp = (const uint16_t*)v_image;
   uint16_t* op = (uint16_t*)out_bf16;
+  // Whole blocks of 128 tokens go through the 64-queries-per-wave kernel when every list is clean
+  // (decided on the device, so the general kernel is queued behind it and returns at once unless
+  // the lists turn out to need it).
+  const bool w64 = params->block == 128 && L % 128 == 0 && !stream_only &&
+                   !(params->flags & PRISM_FLAG_GENERAL_KERNEL);
+  const int only_dirty = w64 ? 1 : 0;
+  if (w64) {
+    hipLaunchKernelGGL(queue_validate_kernel, dim3((R + 3) / 4), dim3(256), 0, st, row_ptr, col_idx, h, N,
+                       pc.cap, causal, plan);
+    hipLaunchKernelGGL(sparse_attn_w64_kernel, grid3, dim3(128), 0, st, qp, kp, vp, col_idx, items, plan, op,
+                       lse, h, h_kv, L, N, causal);
+  }
   if (params->block == 128) {
     const dim3 block3(AttnCfg<128>::kThreads);
     if (stream_only)
       hipLaunchKernelGGL((sparse_attn_kernel<128, true>), grid3, block3, 0, st, qp, kp, vp, col_idx, items,
-                         plan, op, lse, h, h_kv, L, N, causal);
+                         plan, op, lse, h, h_kv, L, N, causal, only_dirty);
     else
       hipLaunchKernelGGL((sparse_attn_kernel<128, false>), grid3, block3, 0, st, qp, kp, vp, col_idx, items,
-                         plan, op, lse, h, h_kv, L, N, causal);
+                         plan, op, lse, h, h_kv, L, N, causal, only_dirty);
   } else {
     const dim3 block3(AttnCfg<64>::kThreads);
     if (stream_only)
       hipLaunchKernelGGL((sparse_attn_kernel<64, true>), grid3, block3, 0, st, qp, kp, vp, col_idx, items,
-                         plan, op, lse, h, h_kv, L, N, causal);
+                         plan, op, lse, h, h_kv, L, N, causal, only_dirty);
     else
       hipLaunchKernelGGL((sparse_attn_kernel<64, false>), grid3, block3, 0, st, qp, kp, vp, col_idx, items,
-                         plan, op, lse, h, h_kv, L, N, causal);
+                         plan, op, lse, h, h_kv, L, N, causal, only_dirty);
   }
   return launch_status();
 }

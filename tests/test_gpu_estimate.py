@@ -145,7 +145,7 @@ def test_exact_selection_on_separated_rows(N, B):
     np.testing.assert_array_equal(res["mask"].sum(-1)[clean], sel.mask.sum(-1)[clean])
     lens = sel.mask.sum(-1)[clean]
     print(f"  N={N}: {clean.sum()} of {clean.size} rows clean, selected counts {lens.min()}..{lens.max()}", flush=True)
-    assert lens.max() > 2 * 64 * (N > 128)                # long lists really occur
+    assert lens.max() > N // 4                          # long lists really occur
     _check_mask(None, res["mask"], sel, p, max_dont_care=0.02)
 
 
