@@ -104,6 +104,7 @@ class Workload:
     k_lognormal_sigma: float = 0.0   # heavy-tailed per-token key scales (0 = off)
     amp_scale: float = 1.0           # multiplies the planted q-side amplitudes (density knob)
     yarn: Optional[Tuple[int, float, float, float]] = None   # (native_len, scale, alpha, beta): YaRN-style frequencies
+    noise_topic_amp: float = 0.3     # topic amplitude of the near-noise heads (their density knob)
 
     @property
     def n_blocks(self) -> int:
@@ -144,7 +145,8 @@ def small_variant(w: Workload, seq_len: int, n_q_heads: int | None = None,
         n_kv_heads=n_kv_heads or w.n_kv_heads, seq_len=seq_len, block=block or w.block,
         rope_base=w.rope_base, top_p=w.top_p, seed=w.seed, recipe=w.recipe,
         head_dim=w.head_dim, d_high=w.d_high, d_low=w.d_low,
-        k_lognormal_sigma=w.k_lognormal_sigma, amp_scale=w.amp_scale)
+        k_lognormal_sigma=w.k_lognormal_sigma, amp_scale=w.amp_scale,
+        noise_topic_amp=w.noise_topic_amp)
 
 
 @dataclass
@@ -154,6 +156,7 @@ class HeadPlan:
     slash_offsets: List[int] = field(default_factory=list)
     slash_amp: float = 0.0
     vert_amp: float = 0.0
+    topic_amp: float = 1.0        # amplitude of the q side's block-level topic vectors
 
 
 @dataclass
@@ -169,7 +172,14 @@ class KVPlan:
 # Amplitudes (and each workload's amp_scale) were tuned once against the CPU oracle so
 # that top-p selection at the workload's p keeps roughly 5-15% of the causal block
 # pairs at 32K-128K; they are frozen here together with the seeds.
+# Role of q-head i in the "mixed" recipe: local / slash / vertical / mixed in turn, and every
+# sixteenth head (i % 16 == 15) a near-noise head whose weak structure leaves the block-level
+# distribution flat, so that top-p keeps almost every causal block (measured 0.92 - 0.97 of them).
+# A full quarter of such heads would put the layer's density at 0.3, outside the 0.05 - 0.15 the
+# benchmark configurations ask for; one in sixteen keeps the layer inside it and still exercises
+# the long, high-entropy rows.
 _ROLE_TABLE = ("local", "slash", "vertical", "mixed")
+_NOISE_EVERY = 16
 _SLASH_CHOICES = (16, 100, 1000, 5000)
 
 
@@ -197,7 +207,7 @@ def _plan(w: Workload) -> Tuple[List[HeadPlan], List[KVPlan], np.ndarray, np.nda
         head_plans = [HeadPlan("slash", [16], 3.0, 1.0) for _ in range(w.n_q_heads)]
     elif w.recipe == "mixed":
         for hq in range(w.n_q_heads):
-            role = _ROLE_TABLE[hq % 4]
+            role = "noise" if hq % _NOISE_EVERY == _NOISE_EVERY - 1 else _ROLE_TABLE[hq % 4]
             if role == "local":
                 hp = HeadPlan(role, [0, w.block // 2, w.block], float(rng.uniform(2.0, 3.0)),
                               float(rng.uniform(0.5, 1.0)))
@@ -209,11 +219,16 @@ def _plan(w: Workload) -> Tuple[List[HeadPlan], List[KVPlan], np.ndarray, np.nda
             elif role == "vertical":
                 hp = HeadPlan(role, [0], float(rng.uniform(1.0, 1.5)),
                               float(rng.uniform(2.0, 3.0)))
-            else:
+            elif role == "mixed":
                 offs = [o for o in _SLASH_CHOICES if o < w.seq_len // 2]
                 o = int(rng.choice(offs))
                 hp = HeadPlan(role, [0, o], float(rng.uniform(1.5, 2.5)),
                               float(rng.uniform(1.5, 2.5)))
+            else:
+                offs = [o for o in _SLASH_CHOICES if o < w.seq_len // 2]
+                rng.choice(offs)                       # same number of draws as the role it replaces
+                hp = HeadPlan(role, [0], float(rng.uniform(0.2, 0.5)), float(rng.uniform(0.1, 0.3)),
+                              topic_amp=w.noise_topic_amp)
             head_plans.append(hp)
     else:
         raise ValueError(f"unknown recipe {w.recipe!r}")
@@ -271,7 +286,7 @@ def generate(w: Workload, n_threads: int = 8, rotate: bool = True) -> Tuple[np.n
             const = const + (hp.slash_amp / np.sqrt(len(hp.slash_offsets))) * \
                 rotate_vector(g_vecs[kvh], -o, d, w.rope_base, w.yarn)
         x += const.astype(np.float32)[None, :]
-        _add_block_topics(x, rng, B, d, _Q_TOPIC_AMP)
+        _add_block_topics(x, rng, B, d, _Q_TOPIC_AMP * hp.topic_amp)
         Q[hq] = f32_to_bf16_bits(apply_rope(x, cos, sin))
 
     def make_k(kvh: int) -> None:
