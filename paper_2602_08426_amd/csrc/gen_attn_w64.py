@@ -103,6 +103,10 @@ LDS_V = (32768, 49152)  # ... and of the V^T half-tile buffers
 
 LOG2E_OVER_SQRT_D = 0x3E0293EE      # log2(e) / sqrt(128) = 0.12751743 as fp32 bits
 RESCALE_THRESHOLD = 8.0             # rescale O only when a running max grows by more than 2^8
+# P and V^T enter the PV product as fp16.  The running max is kept M_OFFSET below the true one, so
+# p = 2^(s - m) reaches 2^(M_OFFSET + RESCALE_THRESHOLD) = 4096 at most (fp16 holds 65504) and a
+# probability 2^-36 of the largest one is still a non-zero fp16 value.
+M_OFFSET = 4.0
 
 
 # ----------------------------------------------------------------------------------------------
@@ -142,7 +146,7 @@ def mfma_s(dst, afrag, qreg, first):
 def mfma_pv(odst, afrag, preg):
     """O tile (AGPR) += V^T fragment (VGPR) x P fragment (VGPR)."""
     rd = vr(afrag, 4) + vr(preg, 4) + ar(odst, 16)
-    return Ins(f"v_mfma_f32_32x32x16_bf16 {atxt(odst, 16)}, {vtxt(afrag, 4)}, {vtxt(preg, 4)}, {atxt(odst, 16)}",
+    return Ins(f"v_mfma_f32_32x32x16_f16 {atxt(odst, 16)}, {vtxt(afrag, 4)}, {vtxt(preg, 4)}, {atxt(odst, 16)}",
                "mfma", rd, ar(odst, 16))
 
 
@@ -255,7 +259,7 @@ def softmax_ops(p, qt, tag):
     ops.append(valu(f"v_permlane32_swap_b32 v{t_mx}, v{t_mc}", vr(t_mx) + vr(t_mc), vr(t_mx) + vr(t_mc), "lane"))
     ops.append(valu(f"v_max_f32 v{t_mx}, v{t_mx}, v{t_mc}", vr(t_mx) + vr(t_mc), vr(t_mx)))
     # --- m_cand = max(m, mx * scale); move only if it exceeds m + threshold
-    ops.append(valu(f"v_mul_f32 v{t_mx}, s{S_SCALE}, v{t_mx}", vr(t_mx), vr(t_mx)))
+    ops.append(valu(f"v_fma_f32 v{t_mx}, v{t_mx}, s{S_SCALE}, -{M_OFFSET:.1f}", vr(t_mx), vr(t_mx)))
     ops.append(valu(f"v_max_f32 v{t_mc}, v{m}, v{t_mx}", vr(m) + vr(t_mx), vr(t_mc)))
     ops.append(valu(f"v_add_f32 v{t_a}, 0x{f32_bits(RESCALE_THRESHOLD):08x}, v{m}", vr(m), vr(t_a)))
     ops.append(valu(f"v_cmp_gt_f32 s[{fl}:{fl + 1}], v{t_mc}, v{t_a}", vr(t_mc) + vr(t_a), [("s", fl), ("s", fl + 1)]))
@@ -278,7 +282,7 @@ def softmax_ops(p, qt, tag):
         if k % 2 == 1:                          # both members of the pair (k-1, k) have been summed
             kt, r = divmod(k, 16)
             dst = SB(p, kt, qt) + (r - 1) // 2
-            ops.append(valu(f"v_cvt_pk_bf16_f32 v{dst}, v{regs[k - 1]}, v{regs[k]}",
+            ops.append(valu(f"v_cvt_pk_f16_f32 v{dst}, v{regs[k - 1]}, v{regs[k]}",
                             vr(regs[k - 1]) + vr(regs[k]), vr(dst)))
     for k in range(32):
         ops.append(valu(f"v_fma_f32 v{regs[k]}, v{regs[k]}, s{S_SCALE}, -v{m}", vr(regs[k]) + vr(m), vr(regs[k])))
@@ -716,7 +720,8 @@ def prologue(inp):
 
 
 def epilogue():
-    """O = O^T / l as bf16 rows, lse = (m + log2 l) ln 2."""
+    """O = O^T / l as bf16 rows, lse = (m + log2 l) ln 2 (the offset of m cancels: l is the sum
+    of 2^(s - m) with the same m)."""
     T = V_T
     ops = []
     a = ops.append

@@ -25,13 +25,23 @@ namespace prism {
 // V re-layout: V [h_kv, L, d]  ->  image [h_kv, N, d, B] with permuted key positions; keys
 // past the end of a ragged last block are written as zeros.
 // =====================================================================================
+// With vt16 != nullptr a second image with the same layout holds the values as fp16 (the
+// 64-queries-per-wave kernel forms its P V product in fp16: 11 significant bits for P instead of 8).
+// Every bf16 value of magnitude in [2^-17, 65504] (and zero) is an fp16 value, so the conversion is
+// exact there; smaller magnitudes lose at most 2^-25 absolute.  A block holding a finite value beyond
+// the fp16 range sets range_flags[kv head * N + block] = 1 (else 0): such inputs go through the
+// general kernel and the bf16 image.
 template <int BLK>
 __global__ __launch_bounds__(256) void vt_image_kernel(const uint16_t* __restrict__ v,
-                                                       uint16_t* __restrict__ vt, int L, int N) {
+                                                       uint16_t* __restrict__ vt, int L, int N,
+                                                       uint16_t* __restrict__ vt16,
+                                                       int32_t* __restrict__ range_flags) {
   __shared__ uint16_t tile[BLK][kHeadDim + 2];
+  __shared__ int s_over;
   const int blk = blockIdx.x, kvh = blockIdx.y, t = threadIdx.x;
   const uint16_t* src = v + ((size_t)kvh * L + (size_t)blk * BLK) * kHeadDim;
   const int cnt = min(BLK, L - blk * BLK);
+  if (t == 0) s_over = 0;
   for (int idx = t; idx < BLK * 16; idx += 256) {
     const int row = idx >> 4, c = idx & 15;
     u32x4 x = {0u, 0u, 0u, 0u};                       // V is read once: streaming (non-temporal) loads
@@ -42,18 +52,34 @@ __global__ __launch_bounds__(256) void vt_image_kernel(const uint16_t* __restric
   __syncthreads();
   constexpr int CPR = BLK / 8;                       // 16-byte chunks per image row
   uint16_t* dstb = vt + ((size_t)kvh * N + blk) * (size_t)kHeadDim * BLK;
+  bool over = false;
   for (int idx = t; idx < kHeadDim * CPR; idx += 256) {
     const int d = idx / CPR, c = idx % CPR;
-    uint32_t w[4];
+    uint32_t w[4], w16[4];
 #pragma unroll
     for (int e = 0; e < 8; e += 2) {
       // position p = c*8 + e inside the row; group a = p/16, hf = (p/8)&1, g = (p/4)&1, i = p&3
       const int p0 = c * 8 + e, p1 = p0 + 1;
       const int k0 = (p0 & ~15) + 8 * ((p0 >> 2) & 1) + 4 * ((p0 >> 3) & 1) + (p0 & 3);
       const int k1 = (p1 & ~15) + 8 * ((p1 >> 2) & 1) + 4 * ((p1 >> 3) & 1) + (p1 & 3);
-      w[e >> 1] = (uint32_t)tile[k0][d] | ((uint32_t)tile[k1][d] << 16);
+      const uint32_t a = tile[k0][d], b = tile[k1][d];
+      w[e >> 1] = a | (b << 16);
+      if (vt16 != nullptr) {
+        const float fa = bf16_bits_to_float(a), fb = bf16_bits_to_float(b);
+        over |= (fabsf(fa) > 65504.f && fabsf(fa) < INFINITY) || (fabsf(fb) > 65504.f && fabsf(fb) < INFINITY);
+        const _Float16 ha = (_Float16)fa, hb = (_Float16)fb;
+        w16[e >> 1] = (uint32_t)__builtin_bit_cast(uint16_t, ha) | ((uint32_t)__builtin_bit_cast(uint16_t, hb) << 16);
+      }
     }
     *reinterpret_cast<uint4*>(dstb + (size_t)d * BLK + c * 8) = make_uint4(w[0], w[1], w[2], w[3]);
+    if (vt16 != nullptr)
+      *reinterpret_cast<uint4*>(vt16 + ((size_t)kvh * N + blk) * (size_t)kHeadDim * BLK + (size_t)d * BLK + c * 8) =
+          make_uint4(w16[0], w16[1], w16[2], w16[3]);
+  }
+  if (vt16 != nullptr) {
+    if (over) s_over = 1;                            // benign race: every writer stores 1
+    __syncthreads();
+    if (t == 0) range_flags[kvh * N + blk] = s_over;
   }
 }
 
@@ -686,9 +712,13 @@ __global__ __launch_bounds__(128) void sparse_attn_w64_kernel(
 __global__ __launch_bounds__(256) void queue_validate_kernel(const int32_t* __restrict__ row_ptr,
                                                              const int32_t* __restrict__ col_idx, int h,
                                                              int N, int cap, int causal,
-                                                             int32_t* __restrict__ plan) {
+                                                             const int32_t* __restrict__ range_flags,
+                                                             int n_range_flags, int32_t* __restrict__ plan) {
   const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
+  // values of V beyond the fp16 range (flagged per block by vt_image_kernel) also need the general kernel
+  const int fi = blockIdx.x * 256 + threadIdx.x;
+  if (fi < n_range_flags && range_flags[fi] != 0) atomicOr(plan + kPlanFlags, kFlagDirtyLists);
   if (r >= h * N) return;
   int b = row_ptr[r], e = row_ptr[r + 1];
   const bool clamped = b < 0 || b > cap || e < b || e > cap;
@@ -938,20 +968,31 @@ using namespace prism;
 // ---- workspace layout: [ V image | items[h*N] (queue entries) | row_rank[h*N] | row_part[h*N] |
 //                            bins[2*h*kClasses] | parts[h_kv*kClasses*8] | plan[24] ] ----
 struct AttnWs {
-  size_t image, items, row_rank, row_part, bins, parts, plan, total;
+  size_t image, items, row_rank, row_part, bins, parts, plan, image16, range_flags, total;
 };
+// the fp16 image exists where the 64-queries-per-wave kernel can take the call
+static bool w64_shape(const prism_params* p) { return p->block == 128 && p->seq_len % 128 == 0; }
+
 static AttnWs attn_ws(const prism_params* p) {
   const size_t N = n_blocks(p);
   const size_t rows = (size_t)p->n_q_heads * N;
+  const size_t image_bytes = (size_t)p->n_kv_heads * N * p->block * kHeadDim * 2;
   AttnWs w;
   size_t off = 0;
-  w.image = off;    off = align_up(off + (size_t)p->n_kv_heads * N * p->block * kHeadDim * 2, 256);
+  w.image = off;    off = align_up(off + image_bytes, 256);
   w.items = off;    off = align_up(off + rows * sizeof(int4), 256);
   w.row_rank = off; off = align_up(off + rows * sizeof(int32_t), 256);
   w.row_part = off; off = align_up(off + rows * sizeof(int32_t), 256);
   w.bins = off;     off = align_up(off + (size_t)2 * p->n_q_heads * kClasses * sizeof(int32_t), 256);
   w.parts = off;    off = align_up(off + (size_t)p->n_kv_heads * kClasses * 8 * sizeof(int32_t), 256);
   w.plan = off;     off = align_up(off + kPlanInts * sizeof(int32_t), 256);
+  w.image16 = off;
+  w.range_flags = off;
+  if (w64_shape(p)) {
+    off = align_up(off + image_bytes, 256);
+    w.range_flags = off;
+    off = align_up(off + (size_t)p->n_kv_heads * N * sizeof(int32_t), 256);
+  }
   w.total = off;
   return w;
 }
@@ -993,12 +1034,17 @@ extern "C" int prism_v_image(const prism_params* params, const void* v_bf16, voi
   if (rc != PRISM_OK) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
   const int N = n_blocks(params);
+  const AttnWs W = attn_ws(params);
+  char* ws = static_cast<char*>(v_image);
+  uint16_t* vt16 = w64_shape(params) ? reinterpret_cast<uint16_t*>(ws + W.image16) : nullptr;
+  int32_t* range_flags = reinterpret_cast<int32_t*>(ws + W.range_flags);
   if (params->block == 128)
     hipLaunchKernelGGL(vt_image_kernel<128>, dim3(N, params->n_kv_heads), dim3(256), 0, st,
-                       (const uint16_t*)v_bf16, (uint16_t*)v_image, params->seq_len, N);
+                       (const uint16_t*)v_bf16, (uint16_t*)v_image, params->seq_len, N, vt16, range_flags);
   else
     hipLaunchKernelGGL(vt_image_kernel<64>, dim3(N, params->n_kv_heads), dim3(256), 0, st,
-                       (const uint16_t*)v_bf16, (uint16_t*)v_image, params->seq_len, N);
+                       (const uint16_t*)v_bf16, (uint16_t*)v_image, params->seq_len, N, (uint16_t*)nullptr,
+                       (int32_t*)nullptr);
   return launch_status();
 }
 
@@ -1061,14 +1107,17 @@ extern "C" int prism_sparse_attn_pre(const prism_params* params, const void* q_b
   // Whole blocks of 128 tokens go through the 64-queries-per-wave kernel when every list is clean
   // (decided on the device, so the general kernel is queued behind it and returns at once unless
   // the lists turn out to need it).
-  const bool w64 = params->block == 128 && L % 128 == 0 && !stream_only &&
+  const bool w64 = w64_shape(params) && !stream_only &&
                    !(params->flags & PRISM_FLAG_GENERAL_KERNEL);
   const int only_dirty = w64 ? 1 : 0;
   if (w64) {
-    hipLaunchKernelGGL(queue_validate_kernel, dim3((R + 3) / 4), dim3(256), 0, st, row_ptr, col_idx, h, N,
-                       pc.cap, causal, plan);
-    hipLaunchKernelGGL(sparse_attn_w64_kernel, grid3, dim3(128), 0, st, qp, kp, vp, col_idx, items, plan, op,
-                       lse, h, h_kv, L, N, causal);
+    const int n_range_flags = h_kv * N;
+    const int vgrid = ((R + 3) / 4) > ((n_range_flags + 255) / 256) ? (R + 3) / 4 : (n_range_flags + 255) / 256;
+    hipLaunchKernelGGL(queue_validate_kernel, dim3(vgrid), dim3(256), 0, st, row_ptr, col_idx, h, N,
+                       pc.cap, causal, reinterpret_cast<const int32_t*>(ws + W.range_flags), n_range_flags, plan);
+    hipLaunchKernelGGL(sparse_attn_w64_kernel, grid3, dim3(128), 0, st, qp, kp,
+                       reinterpret_cast<const uint16_t*>(ws + W.image16), col_idx, items, plan, op, lse, h, h_kv,
+                       L, N, causal);
   }
   if (params->block == 128) {
     const dim3 block3(AttnCfg<128>::kThreads);

@@ -10,6 +10,7 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    config.addinivalue_line("markers", "timeout(seconds): per-test time limit (pytest-timeout, when installed)")
 
 
 def gpu_available() -> bool:

@@ -182,21 +182,65 @@ def test_attention_is_deterministic_across_runs():
         assert torch.equal(a.view(torch.int16), b.view(torch.int16)) and torch.equal(la, lb)
 
 
-FULL = [("c3_llama_32k", 300), ("c5_qwen_64k", 300), ("c4_llama_128k", 900), ("c4_llama_128k_b64", 900)]
+# (workload, rows compared with the oracle: None = every row, flags of the attention call)
+FULL = [("c3_llama_32k", None, 0), ("c3_llama_32k", None, pb.PRISM_FLAG_GENERAL_KERNEL),
+        ("c5_qwen_64k", None, 0), ("c4_llama_128k", 1200, 0), ("c4_llama_128k_b64", 1200, 0)]
 
 
-@pytest.mark.timeout(1200)
-@pytest.mark.parametrize("name,limit", FULL)
-def test_full_size_workloads_sampled_rows(name, limit):
+def _queue_tables(image, w):
+    """The attention kernel's row entries and queue plan, read back from the workspace behind the
+    V^T image (layout restated in tests/test_gpu_queues.py)."""
+    from tests.test_gpu_queues import _layout
+    lay = _layout(w.n_q_heads, w.n_kv_heads, w.n_blocks, w.block, w.seq_len)
+    rows = w.n_q_heads * w.n_blocks
+    tail = image[lay["items"]:].cpu().numpy()
+    items = tail[:rows * 16].view(np.int32).reshape(rows, 4)
+    plan = tail[lay["plan"] - lay["items"]:lay["plan"] - lay["items"] + 96].view(np.int32)
+    return items, plan[0:8], plan[8:16]
+
+
+def _stratified_rows(items, start, length, lens, N, want, rng):
+    """Rows to compare at full size: the first and last entry of every queue and of every (queue,
+    list-length class) stretch inside it, q-blocks 0 / 1 / N/2 / N-1 of every head, and a random
+    sample of every (queue, class) stretch until `want` rows are reached."""
+    from tests.test_gpu_queues import _length_class
+    hq, u = items[:, 0], items[:, 1] & 0xFFFF
+    cls = np.array([_length_class(int(n)) for n in lens[hq * N + u]])
+    picked = set()
+    stretches = []
+    for x in range(8):
+        if length[x] == 0:
+            continue
+        seg = np.arange(start[x], start[x] + length[x])
+        picked.update((int(seg[0]), int(seg[-1])))
+        cut = np.nonzero(np.diff(cls[seg]) != 0)[0] + 1
+        for part in np.split(seg, cut):
+            picked.update((int(part[0]), int(part[-1])))
+            stretches.append(part)
+    h = int(hq.max()) + 1
+    fixed = {(a, b) for a in range(h) for b in (0, 1, N // 2, N - 1)}
+    per = max(1, (want - len(picked) - len(fixed)) // max(1, len(stretches)))
+    for part in stretches:
+        picked.update(int(e) for e in rng.choice(part, size=min(len(part), per), replace=False))
+    rows = {(int(hq[e]), int(u[e])) for e in picked} | fixed
+    classes = {(int(np.searchsorted(start + length, e, side="right")), int(cls[e])) for e in picked}
+    return sorted(rows), len(stretches), len(classes)
+
+
+@pytest.mark.timeout(1500)
+@pytest.mark.parametrize("name,n_rows,flags", FULL)
+def test_full_size_workloads(name, n_rows, flags):
     """BASELINE sizes in the launch configuration bench.py times: block masks against the
-    oracle's selection (whole mask), attention on a seeded sample of (head, q-block) rows
-    (first, second, middle and last q-block of every head plus 64 random rows)."""
+    oracle's selection (whole mask); attention against the oracle on every row (32K, 64K) or on
+    a sample stratified over the kernel's own queues and list-length classes (128K); on every row
+    of the tensor, cheap invariants that hold at any size."""
     w = wl.WORKLOADS[name]
-    print(f"case {w.name}: generating", flush=True)
+    print(f"case {w.name} flags={flags:#x}: generating", flush=True)
     Qb, Kb, Vb = wl.generate(w, n_threads=16)
     params = gu.params_for(w)
+    aparams = gu.params_for(w, flags=flags)
     qd, kd, vd = _dev(Qb, Kb, Vb)
-    N, h = w.n_blocks, w.n_q_heads
+    N, h, B = w.n_blocks, w.n_q_heads, w.block
     pairs = h * N * (N + 1) // 2
     mask_bits, row_ptr, col_idx, info = pb.alloc_estimate_outputs(params, pairs)
     ws = pb.alloc_workspace(pb.prism_estimate_workspace_bytes(params))
@@ -206,49 +250,107 @@ def test_full_size_workloads_sampled_rows(name, limit):
     # exactly the three calls of a bench step, col_count = capacity
     pb.prism_estimate(params, qd, kd, mask_bits, row_ptr, col_idx, pairs, info, ws)
     pb.prism_v_image(params, vd, image)
-    pb.prism_sparse_attn_pre(params, qd, kd, image, row_ptr, col_idx, pairs, out, lse)
+    pb.prism_sparse_attn_pre(aparams, qd, kd, image, row_ptr, col_idx, pairs, out, lse)
     torch.cuda.synchronize()
     gmask = gu.unpack_mask(mask_bits.cpu().numpy().view(np.uint64), N)
     nnz = int(info.cpu()[0])
-    print(f"  gpu done: density {nnz / pairs:.4f}; oracle selection ...", flush=True)
-    assert not torch.isnan(out.float()).any()
+    print(f"  gpu done: density {nnz / pairs:.4f}", flush=True)
+
+    # every row of the tensor: finite, lse finite (no list is empty: top-p keeps >= 1 block), and
+    # every output inside the range of the head's values (a convex combination, bf16-rounded)
+    assert torch.isfinite(out.float()).all() and torch.isfinite(lse).all()
+    g = w.group
+    vmax = vd.float().abs().amax(dim=(1, 2)).repeat_interleave(g)           # per q-head
+    assert (out.float().abs().amax(dim=(1, 2)) <= vmax * (1 + 2.0 ** -7)).all()
 
     # selection oracle one kv group at a time (bounds host memory at 128K)
-    g = w.group
-    worst_dc = 0.0
-    for kvh in range(w.n_kv_heads):
-        hs = slice(kvh * g, (kvh + 1) * g)
-        sel = orc.prism_select(orc.bf16_to_f64(Qb[hs]), orc.bf16_to_f64(Kb[kvh:kvh + 1]),
-                               w.d_high, w.d_low, w.block, w.top_p)
-        tol = orc.selection_tolerance(sel, w.top_p)
-        missing = tol.must & ~gmask[hs]
-        extra = tol.must_not & gmask[hs]
-        assert not missing.any() and not extra.any(), \
-            f"kv group {kvh}: {missing.sum()} missing, {extra.sum()} extra blocks"
-        worst_dc = max(worst_dc, tol.dont_care_fraction)
-        print(f"  kv group {kvh}: mask ok (don't-care {tol.dont_care_fraction:.5f})", flush=True)
-    assert worst_dc < 0.02
     rp = row_ptr.cpu().numpy()
     np.testing.assert_array_equal(np.diff(rp), gmask.reshape(h * N, N).sum(1))
+    if flags == 0:
+        worst_dc = 0.0
+        for kvh in range(w.n_kv_heads):
+            hs = slice(kvh * g, (kvh + 1) * g)
+            sel = orc.prism_select(orc.bf16_to_f64(Qb[hs]), orc.bf16_to_f64(Kb[kvh:kvh + 1]),
+                                   w.d_high, w.d_low, w.block, w.top_p)
+            tol = orc.selection_tolerance(sel, w.top_p)
+            missing = tol.must & ~gmask[hs]
+            extra = tol.must_not & gmask[hs]
+            assert not missing.any() and not extra.any(), \
+                f"kv group {kvh}: {missing.sum()} missing, {extra.sum()} extra blocks"
+            worst_dc = max(worst_dc, tol.dont_care_fraction)
+        print(f"  masks ok, don't-care share <= {worst_dc:.5f}", flush=True)
+        assert worst_dc < 0.005
 
-    rng = np.random.default_rng(1)
-    rows = {(hq, u) for hq in range(h) for u in (0, 1, N // 2, N - 1)}
-    while len(rows) < 4 * h + 64:
-        rows.add((int(rng.integers(h)), int(rng.integers(N))))
-    rows = sorted(rows)
-    o = None
+    lens = np.diff(rp)
+    if n_rows is None:
+        rows = [(hq, u) for hq in range(h) for u in range(N)]
+        note = "every row"
+    else:
+        items, start, length = _queue_tables(image, w)
+        rows, n_stretch, n_cls = _stratified_rows(items, start, length, lens, N, n_rows, np.random.default_rng(1))
+        note = f"{len(rows)} rows over {n_stretch} (queue, class) stretches, {n_cls} distinct"
+        assert len(rows) >= 1024
     worst = 0.0
-    B = w.block
-    for kvh in range(w.n_kv_heads):
-        mine = [(hq, u) for hq, u in rows if hq // g == kvh]
+    o_all = out.float().cpu().numpy()
+    l_all = lse.cpu().numpy()
+    by_kv = {}
+    for hq, u in rows:
+        by_kv.setdefault(hq // g, []).append((hq, u))
+    for kvh, mine in sorted(by_kv.items()):
         Kf, Vf = orc.bf16_to_f64(Kb[kvh]), orc.bf16_to_f64(Vb[kvh])
+        Qf = {}
         for hq, u in mine:
+            if hq not in Qf:
+                Qf = {hq: orc.bf16_to_f64(Qb[hq])}
             blocks = np.nonzero(gmask[hq, u, :u + 1])[0]
-            ro, rl = orc.block_sparse_attention_row(orc.bf16_to_f64(Qb[hq]), Kf, Vf, u, blocks, B)
-            go = out[hq, u * B:(u + 1) * B].float().cpu().numpy().astype(np.float64)
-            gl = lse[hq, u * B:(u + 1) * B].cpu().numpy().astype(np.float64)
-            err = np.abs(go - ro).max()
+            ro, rl = orc.block_sparse_attention_row(Qf[hq], Kf, Vf, u, blocks, B)
+            err = np.abs(o_all[hq, u * B:(u + 1) * B] - ro).max()
             worst = max(worst, err)
             assert err <= OUT_TOL, f"head {hq} q-block {u}: max-abs {err}"
-            assert np.abs(gl - rl).max() <= LSE_TOL
-    print(f"  attention ok on {len(rows)} rows, worst max-abs {worst:.4g}", flush=True)
+            assert np.abs(l_all[hq, u * B:(u + 1) * B] - rl).max() <= LSE_TOL, (hq, u)
+    print(f"  attention ok on {note}, worst max-abs {worst:.4g}", flush=True)
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_fuzz_random_lists_and_values(seed):
+    """Seeded random shapes, list patterns and value scales (large scores, heavy-tailed keys, rows
+    of one block, empty rows, entries to skip), both attention kernels where both apply."""
+    rng = np.random.default_rng(9000 + seed)
+    B = int(rng.choice([64, 128]))
+    g = int(rng.choice([1, 2, 4, 7]))
+    hkv = int(rng.integers(1, 3))
+    h = g * hkv
+    N = int(rng.integers(1, 20))
+    ragged = B == 128 and rng.random() < 0.3
+    L = N * B - (int(rng.integers(1, B)) if ragged else 0)
+    qs, ks = float(rng.choice([0.5, 1.0, 2.5])), float(rng.choice([0.5, 1.0, 2.5]))
+    print(f"seed {seed}: h={h}/{hkv} L={L} B={B} q-scale {qs} k-scale {ks}", flush=True)
+    K = rng.standard_normal((hkv, L, 128)).astype(np.float32) * ks
+    if rng.random() < 0.3:
+        K *= np.exp(0.75 * rng.standard_normal((hkv, L, 1))).astype(np.float32)
+    Qb = wl.f32_to_bf16_bits(rng.standard_normal((h, L, 128)).astype(np.float32) * qs)
+    Kb = wl.f32_to_bf16_bits(K)
+    # values stay N(0, 1): the bar is absolute, and the bf16 rounding of an output of magnitude 8
+    # alone is 0.03
+    Vb = wl.f32_to_bf16_bits(rng.standard_normal((hkv, L, 128)).astype(np.float32))
+    dens = rng.choice([0.1, 0.5, 1.0], size=h)
+    mask = np.tril(rng.random((h, N, N)) < dens[:, None, None])
+    mask[rng.random((h, N)) < 0.1] = False                      # empty rows
+    dirty = rng.random() < 0.3                                   # entries the kernels must skip
+    rows = []
+    for hq in range(h):
+        for u in range(N):
+            cols = list(np.nonzero(mask[hq, u])[0])
+            if dirty and rng.random() < 0.3:
+                cols.insert(int(rng.integers(len(cols) + 1)), int(rng.choice([-1, u + 1, N + 5])))
+            rows.append(cols)
+    rp = np.zeros(h * N + 1, np.int32)
+    rp[1:] = np.cumsum([len(r) for r in rows])
+    ci = np.array([c for r in rows for c in r], np.int32)
+    rp_d, ci_d, cnt = gu.csr_to_device(rp, ci)
+    qd, kd, vd = _dev(Qb, Kb, Vb)
+    Q, K64, V = orc.bf16_to_f64(Qb), orc.bf16_to_f64(Kb), orc.bf16_to_f64(Vb)
+    for flags in (0, pb.PRISM_FLAG_GENERAL_KERNEL):
+        params = pb.make_params(h, hkv, L, B, flags=flags)
+        out, lse = gu.gpu_sparse_attn(params, qd, kd, vd, rp_d, ci_d, cnt)
+        _compare_rows(params, out, lse, Q, K64, V, mask, None)

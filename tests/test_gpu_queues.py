@@ -8,7 +8,8 @@ list and its first valid entry; the segments tile the table; every queue was pul
 inside a queue the (phase, length class) groups come in order; the queues hold about equal work.
 
 The offsets below restate the workspace layout of prism_attn.hip (V^T image, then the int4
-entries, two int32 tables of h*N, class counts, part counts, the 24-int plan; every piece
+entries, two int32 tables of h*N, class counts, part counts, the 32-int plan, and for whole
+blocks of 128 tokens an fp16 copy of the image with one range flag per kv block; every piece
 aligned to 256 bytes).  They are not part of the C ABI: this file changes with that layout.
 """
 import numpy as np
@@ -26,7 +27,7 @@ def _align(x, a=256):
     return (x + a - 1) // a * a
 
 
-def _layout(h, hkv, N, B):
+def _layout(h, hkv, N, B, L=None):
     rows = h * N
     off = {}
     o = 0
@@ -43,7 +44,13 @@ def _layout(h, hkv, N, B):
     off["parts"] = o
     o = _align(o + hkv * N_CLASSES * 8 * 4)
     off["plan"] = o
-    o = _align(o + 24 * 4)
+    o = _align(o + 32 * 4)
+    if B == 128 and (L is None or L % 128 == 0):
+        # whole blocks of 128 tokens: a second V^T image in fp16 and one range flag per kv block
+        off["image16"] = o
+        o = _align(o + hkv * N * B * 128 * 2)
+        off["range_flags"] = o
+        o = _align(o + hkv * N * 4)
     off["total"] = o
     return off
 
@@ -68,7 +75,7 @@ def test_every_row_is_queued_once_and_the_queues_are_balanced(h, hkv, L, B, bidi
     N = (L + B - 1) // B
     flags = pb.PRISM_FLAG_BIDIRECTIONAL if bidir else 0
     params = pb.make_params(h, hkv, L, B, flags=flags)
-    lay = _layout(h, hkv, N, B)
+    lay = _layout(h, hkv, N, B, L)
     assert pb.prism_sparse_attn_workspace_bytes(params) == lay["total"]
 
     # heads of very different density, some empty rows, some entries that the kernel must skip
