@@ -33,19 +33,28 @@ def log(msg: str) -> None:
 
 
 def profiled_traffic(workload: str, kernel: str):
-    """HBM bytes per launch of `kernel` from the committed rocprofv3 summary of this workload
-    (profiles/hot_path_<workload>.txt, lines 'TRAFFIC kernel=... read_bytes=... write_bytes=...');
-    None when no summary is there."""
-    path = os.path.join(ROOT, "profiles", f"hot_path_{workload}.txt")
+    """(HBM bytes per launch of `kernel`, file it was read from) out of the committed rocprofv3
+    counter summary of this workload (profiles/hot_path_<workload>.txt, lines
+    'TRAFFIC kernel=... read_bytes=... write_bytes=...'); (None, None) when there is none.
+    Counter runs are separate rocprofv3 --pmc passes, so this figure is never measured in the
+    timed run itself: the JSON line carries the file name beside it."""
+    rel = os.path.join("profiles", f"hot_path_{workload}.txt")
     try:
-        with open(path) as f:
+        with open(os.path.join(ROOT, rel)) as f:
             for line in f:
                 if line.startswith("TRAFFIC") and f"kernel={kernel} " in line:
                     kv = dict(x.split("=") for x in line.split()[1:])
-                    return float(kv["read_bytes"]) + float(kv["write_bytes"])
+                    return float(kv["read_bytes"]) + float(kv["write_bytes"]), rel
     except OSError:
         pass
-    return None
+    return None, None
+
+
+def stats(xs):
+    """mean / median / min of a list of per-step times, rounded."""
+    import numpy as np
+    a = np.asarray(xs, dtype=np.float64)
+    return {"mean": round(float(a.mean()), 4), "median": round(float(np.median(a)), 4), "min": round(float(a.min()), 4)}
 
 
 PEAK_PROBES = (("mfma_32x32x16_bf16_only", (1, 2)), ("mfma_plus_lds_read_1_to_1", (2,)),
@@ -56,7 +65,8 @@ PEAK_PROBES = (("mfma_32x32x16_bf16_only", (1, 2)), ("mfma_plus_lds_read_1_to_1"
 
 def measure_peaks(which=None):
     """Achievable peaks of this GPU from the probe loops of libprism_peaks.so (bench-only library
-    built beside libprism.so): rows of {probe, arg, ms, rate, unit, shader_mhz, cycles_per_op}."""
+    built beside libprism.so): rows of {probe, arg, ms, rate, unit, shader_mhz, cycles_per_op}.
+    `which` = {probe name: args} restricts the run; None runs every probe at every argument."""
     import ctypes
     path = os.path.join(ROOT, "paper_2602_08426_amd", "libprism_peaks.so")
     if not os.path.exists(path):
@@ -67,8 +77,10 @@ def measure_peaks(which=None):
     index = {lib.prism_peaks_name(i).decode(): i for i in range(lib.prism_peaks_count())}
     rows = []
     for name, args in PEAK_PROBES:
-        if which is not None and name not in which:
-            continue
+        if which is not None:
+            if name not in which:
+                continue
+            args = which[name]
         for arg in args:
             out = (ctypes.c_double * 4)()
             if lib.prism_peaks_measure(index[name], arg, out) != 0:
@@ -95,10 +107,10 @@ def peaks_main() -> int:
     return 0
 
 
-def cpu_baseline(w, Qb, Kb, Vb, mask, flop_dense: float, budget_rows: int = 48):
-    """Time the oracle (as it stands) on a bounded sample and scale to the whole workload:
-    selection on one kv group, block-masked attention on a seeded sample of (head, q-block)
-    rows extrapolated by executed-block count."""
+def cpu_baseline(w, Qb, Kb, Vb, mask, flop_dense: float, budget_rows: int = 2048):
+    """Time the oracle (as it stands): the selection in full, kv group by kv group, and the
+    block-masked attention on a seeded sample of (head, q-block) rows drawn over all heads and
+    extrapolated by executed-block count."""
     import numpy as np
     from oracle import prism_oracle as orc
     try:
@@ -108,26 +120,33 @@ def cpu_baseline(w, Qb, Kb, Vb, mask, flop_dense: float, budget_rows: int = 48):
         cores = os.cpu_count() or 1
     g = w.group
     N, B = w.n_blocks, w.block
-    t0 = time.perf_counter()
-    Qg = orc.bf16_to_f64(Qb[:g])
-    Kg = orc.bf16_to_f64(Kb[:1])
-    orc.prism_select(Qg, Kg, w.d_high, w.d_low, B, w.top_p)
-    t_sel = (time.perf_counter() - t0) * (w.n_q_heads / g)
-    Vg = orc.bf16_to_f64(Vb[:1])
+    t_sel = 0.0
+    for kv in range(w.n_kv_heads):
+        Qg = orc.bf16_to_f64(Qb[kv * g:(kv + 1) * g])
+        Kg = orc.bf16_to_f64(Kb[kv:kv + 1])
+        t0 = time.perf_counter()
+        orc.prism_select(Qg, Kg, w.d_high, w.d_low, B, w.top_p)
+        t_sel += time.perf_counter() - t0
     rng = np.random.default_rng(0)
-    rows = [(int(rng.integers(g)), int(rng.integers(N))) for _ in range(budget_rows)]
-    t0 = time.perf_counter()
-    orc.block_sparse_attention(Qg, Kg, Vg, mask[:g], B, rows)
-    t_rows = time.perf_counter() - t0
-    blocks_sample = sum(int(mask[hq, u, :u + 1].sum()) for hq, u in rows)
+    rows = sorted((int(rng.integers(w.n_q_heads)), int(rng.integers(N))) for _ in range(budget_rows))
+    t_rows, blocks_sample = 0.0, 0
+    for kv in sorted({hq // g for hq, _ in rows}):
+        Qg = orc.bf16_to_f64(Qb[kv * g:(kv + 1) * g])
+        Kg = orc.bf16_to_f64(Kb[kv:kv + 1])
+        Vg = orc.bf16_to_f64(Vb[kv:kv + 1])
+        mine = [(hq - kv * g, u) for hq, u in rows if hq // g == kv]
+        t0 = time.perf_counter()
+        orc.block_sparse_attention(Qg, Kg, Vg, mask[kv * g:(kv + 1) * g], B, mine)
+        t_rows += time.perf_counter() - t0
+        blocks_sample += sum(int(mask[kv * g + hq, u, :u + 1].sum()) for hq, u in mine)
     t_attn = t_rows * (float(mask.sum()) / max(blocks_sample, 1))
     total = t_sel + t_attn
     return {
         "value": flop_dense / total / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
-        "sample": (f"selection oracle on 1 of {w.n_kv_heads} kv groups ({g} q-heads), scaled x{w.n_q_heads // g}; "
-                   f"attention oracle on {budget_rows} seeded (head,q-block) rows ({blocks_sample} blocks), "
-                   f"scaled by executed-block count to {int(mask.sum())} blocks"),
-        "est_seconds_extrapolated": round(t_sel, 2), "attn_seconds_extrapolated": round(t_attn, 2),
+        "sample": (f"selection oracle timed in full (all {w.n_kv_heads} kv groups, {w.n_q_heads} q-heads); "
+                   f"attention oracle on {budget_rows} seeded (head,q-block) rows over all heads ({blocks_sample} "
+                   f"blocks, {t_rows:.1f} s), scaled by executed-block count to {int(mask.sum())} blocks"),
+        "est_seconds": round(t_sel, 2), "attn_seconds_extrapolated": round(t_attn, 2),
     }
 
 
@@ -255,9 +274,11 @@ def main() -> int:
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_step = wall * 1e3 / args.steps
-    ms_est = float(np.mean([e[0].elapsed_time(e[1]) for e in events]))
-    ms_vimg = float(np.mean([e[1].elapsed_time(e[2]) for e in events]))
-    ms_attn = float(np.mean([e[2].elapsed_time(e[3]) for e in events]))
+    t_est = [e[0].elapsed_time(e[1]) for e in events]
+    t_vimg = [e[1].elapsed_time(e[2]) for e in events]
+    t_attn = [e[2].elapsed_time(e[3]) for e in events]
+    t_all = [e[0].elapsed_time(e[3]) for e in events]
+    ms_est, ms_vimg, ms_attn = float(np.mean(t_est)), float(np.mean(t_vimg)), float(np.mean(t_attn))
     log(f"step {ms_step:.3f} ms  (estimate {ms_est:.3f}, v_image {ms_vimg:.3f}, sparse attention {ms_attn:.3f})")
 
     # the same step replayed from a HIP graph (launch overhead of the ~11 kernels taken out; matters
@@ -329,18 +350,36 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
+    # achievable peaks of this very box, measured after the timed region: an MFMA-only loop with
+    # operands in registers and a 16-byte streaming read over an 8 GiB footprint
+    peak_mfma = peak_stream = None
+    if not args.no_peaks:
+        rows = measure_peaks({"mfma_32x32x16_bf16_only": (2,), "stream_read_16B": (8192,)})
+        peak_mfma = next(r for r in rows if r["probe"].startswith("mfma"))
+        peak_stream = next(r for r in rows if r["probe"].startswith("stream"))
+
+    def vs_measured(x, row):
+        return None if row is None else round(x / row["rate"], 4)
+
     flop_block = 4.0 * B * B * d
     flop_dense = flop_block * pairs
     flop_exec = flop_block * nnz
     density = nnz / pairs
     eff_tflops = flop_dense / (ms_step * 1e-3) / 1e12
     exec_tflops = flop_exec / (ms_attn * 1e-3) / 1e12
-    # bytes the attention kernel has to move when no tile is reused: K and V^T tile per listed
-    # block, Q rows in and O rows out once per (head, q-block)
+    # the attention kernel against the memory roof: bytes that crossed the L2 <-> fabric boundary
+    # per launch (rocprofv3 counters of the committed profile of this workload) over the launch time
+    # measured here.  The no-reuse bytes (K and V^T tile per listed block, Q in, O out) are kept
+    # beside it as the algorithmic figure; rows that share tiles are served by the L2s.
+    w64 = (B == 128 and L % 128 == 0)
+    attn_kernel = "sparse_attn_w64_kernel" if w64 else f"sparse_attn_kernel<{B}, false>"
+    attn_key = "sparse_attn_w64_kernel" if w64 else "sparse_attn_kernel"
+    attn_traffic, attn_src = profiled_traffic(w.name, attn_key)
     attn_bytes = nnz * 2 * B * d * 2 + 2 * Qb.nbytes
-    attn_gbs = attn_bytes / (ms_attn * 1e-3) / 1e9
+    attn_gbs = None if attn_traffic is None else attn_traffic / (ms_attn * 1e-3) / 1e9
     est_bytes = (Qb.nbytes + Kb.nbytes)
     est_gbs = est_bytes / (ms_est * 1e-3) / 1e9
+    est_traffic, est_src = profiled_traffic(w.name, "pool_energy_kernel")
 
     result = {
         "metric": "prefill attention effective TFLOP/s at 128K (estimate+sparse), ms alongside",
@@ -353,6 +392,8 @@ def main() -> int:
         "detail": {
             "ms_estimate": round(ms_est, 4), "ms_v_image": round(ms_vimg, 4),
             "ms_sparse_attn": round(ms_attn, 4),
+            "ms_step_events": stats(t_all), "ms_estimate_events": stats(t_est),
+            "ms_sparse_attn_events": stats(t_attn),
             "ms_per_step_hip_graph": None if ms_graph is None else round(ms_graph, 4),
             "ms_sparse_attn_stream_only": None if ms_stream is None else round(ms_stream, 4),
             "ms_dense_same_kernel": None if ms_dense is None else round(ms_dense, 3),
@@ -360,30 +401,44 @@ def main() -> int:
             "estimate_over_dense": None if ms_dense is None else round(ms_est / ms_dense, 5),
             "block_density": round(density, 5), "nnz_blocks": nnz,
             "executed_tflops": round(exec_tflops, 2),
+            "executed_tflops_best_step": round(flop_exec / (min(t_attn) * 1e-3) / 1e12, 2),
             "dense_tflops": None if ms_dense is None else round(flop_dense / ((ms_dense - ms_vimg) * 1e-3) / 1e12, 2),
             "estimate_gbs": round(est_gbs, 1), "estimate_frac_hbm_peak": round(est_gbs / PEAK_HBM_GBS, 4),
             "paper_context": "paper reports up to 5.1x over FlashAttention-2 at 128K on one H100 (different hardware)",
         },
-        "roofline": {"kernel": f"sparse_attn_kernel<{B}, false>", "bound": "mfma", "achieved": round(exec_tflops, 2),
+        "roofline": {"kernel": attn_kernel, "bound": "mfma", "achieved": round(exec_tflops, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(exec_tflops / PEAK_BF16_TFLOPS, 4),
-                     "traffic": profiled_traffic(w.name, "sparse_attn_kernel"),
-                     "flops_per_launch": flop_exec, "avg_launch_ms": round(ms_attn, 4)},
-        # the same kernel against the memory roof: without tile reuse it has 128 flop per byte,
-        # below the machine's ridge (2500 TFLOP/s / 8 TB/s = 312 flop/B)
-        "roofline_sparse_attn_memory": {"kernel": f"sparse_attn_kernel<{B}, false>", "bound": "hbm",
-                                        "achieved": round(attn_gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                                        "frac": round(attn_gbs / PEAK_HBM_GBS, 4),
-                                        "traffic": profiled_traffic(w.name, "sparse_attn_kernel"),
-                                        "bytes_per_launch": attn_bytes, "avg_launch_ms": round(ms_attn, 4),
+                     "traffic": attn_traffic, "traffic_source": attn_src,
+                     "peak_measured": None if peak_mfma is None else peak_mfma["rate"],
+                     "peak_measured_probe": None if peak_mfma is None else
+                     f"mfma_32x32x16_bf16_only, 2 workgroups per CU, {peak_mfma['shader_mhz']:.0f} MHz under load",
+                     "frac_of_measured": vs_measured(exec_tflops, peak_mfma),
+                     "flops_per_launch": flop_exec, "avg_launch_ms": round(ms_attn, 4),
+                     "launch_ms": stats(t_attn),
+                     "note": "avg_launch_ms is the whole prism_sparse_attn_pre call (queue build + list check + "
+                             "attention kernel), so `achieved` is a lower bound for the kernel alone"},
+        "roofline_sparse_attn_memory": {"kernel": attn_kernel, "bound": "hbm",
+                                        "achieved": None if attn_gbs is None else round(attn_gbs, 1),
+                                        "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                                        "frac": None if attn_gbs is None else round(attn_gbs / PEAK_HBM_GBS, 4),
+                                        "traffic": attn_traffic, "traffic_source": attn_src,
+                                        "peak_measured": None if peak_stream is None else peak_stream["rate"],
+                                        "peak_measured_probe": None if peak_stream is None else
+                                        "stream_read_16B over 8 GiB",
+                                        "frac_of_measured": None if attn_gbs is None else vs_measured(attn_gbs, peak_stream),
+                                        "bytes_per_launch_no_reuse": attn_bytes, "avg_launch_ms": round(ms_attn, 4),
                                         "stream_only_ms": None if ms_stream is None else round(ms_stream, 4),
-                                        "note": "algorithmic bytes (64 KB per listed block pair + Q in + O out); "
-                                                "tiles that rows share are served by L2, so this can exceed the HBM "
-                                                "peak: `traffic` is what left the L2s"},
+                                        "note": "achieved = counter bytes of the committed profile / launch time of "
+                                                "this run; bytes_per_launch_no_reuse = 64 KB per listed block pair + "
+                                                "Q in + O out, what the kernel would move if no tile were shared"},
         "roofline_estimate": {"kernel": "prism_estimate (5 kernels; pool_energy_kernel carries the bytes)",
                               "bound": "hbm", "achieved": round(est_gbs, 1), "peak": PEAK_HBM_GBS,
                               "unit": "GB/s", "frac": round(est_gbs / PEAK_HBM_GBS, 4),
-                              "traffic": profiled_traffic(w.name, "pool_energy_kernel"),
-                              "bytes_per_launch": est_bytes, "avg_launch_ms": round(ms_est, 4)},
+                              "traffic": est_traffic, "traffic_source": est_src,
+                              "peak_measured": None if peak_stream is None else peak_stream["rate"],
+                              "frac_of_measured": vs_measured(est_gbs, peak_stream),
+                              "bytes_per_launch": est_bytes, "avg_launch_ms": round(ms_est, 4),
+                              "launch_ms": stats(t_est)},
     }
 
     if not args.no_cpu_baseline:
