@@ -38,7 +38,7 @@ extern "C" {
 typedef enum prism_status {
   PRISM_OK = 0,
   PRISM_ERR_INVALID_ARG = -1,     /* null pointer, inconsistent sizes, p outside (0,1], ... */
-  PRISM_ERR_UNSUPPORTED = -2,     /* head_dim != 128, block not in {64,128}, more than 2048 blocks, ... */
+  PRISM_ERR_UNSUPPORTED = -2,     /* head_dim not in {64,128,256}, block not in {64,128}, more than 2048 blocks, ... */
   PRISM_ERR_WORKSPACE = -3,       /* workspace missing, misaligned or too small */
   PRISM_ERR_HIP = -4,             /* a HIP runtime call failed (launch error) */
   PRISM_ERR_TOO_LARGE = -5        /* prism_estimate_static: the problem needs more scratch than the
@@ -66,7 +66,7 @@ typedef struct prism_params {
   int32_t n_q_heads;    /* h   (batch folded in)                                   */
   int32_t n_kv_heads;   /* h_kv, must divide n_q_heads                             */
   int32_t seq_len;      /* L; the last block may be ragged (holds L mod B tokens)   */
-  int32_t head_dim;     /* d, must be 128                                           */
+  int32_t head_dim;     /* d: 64, 128 or 256                                        */
   int32_t block;        /* B, 64 or 128; N = ceil(L / B) blocks, N <= 2048          */
   int32_t d_high;       /* width of the high-frequency band, 0..d (0 = band off)    */
   int32_t d_low;        /* width of the low-frequency band,  0..d (0 = band off)    */
@@ -280,6 +280,53 @@ int prism_sparse_attn_pre(const prism_params* params,
                           void* v_image, size_t v_image_bytes,
                           const int32_t* row_ptr, const int32_t* col_idx, int64_t col_count,
                           void* out_bf16, float* lse, void* stream);
+
+/* ------------------------------------------------------------------------------------
+ * Packed variable-length batches — the batch axis of Sec. 3.4 (Fig. "PyTorch-style
+ * implementation of Prism" carries a leading batch dimension) for sequences of unequal length.
+ *
+ * The batch is stored without padding: Q, O are [n_q_heads, T, d], K, V are [n_kv_heads, T, d],
+ * lse is [n_q_heads, T]; sequence s owns tokens cu_seqlens[s] .. cu_seqlens[s+1]-1 of the T
+ * axis.  params->seq_len = T = cu_seqlens[n_seqs]; cu_seqlens is a HOST array of n_seqs + 1
+ * strictly increasing offsets starting at 0.  Every sequence is a problem of its own, exactly
+ * as if prism_estimate / prism_sparse_attn were called on its slice: own blocks (the first
+ * block of a sequence starts at its first token, N_s = ceil(L_s / B) <= 2048), own RMS
+ * statistics, own causal structure, own index lists.  The limits on N apply per sequence, not
+ * to T.
+ *
+ * Outputs of the sequences lie one behind the other; prism_varlen_layout gives the start of
+ * each (arrays of n_seqs + 1 int64 on the HOST, last entry = total; any may be NULL):
+ *   mask_offsets : in uint64 words; sequence s holds [n_q_heads, N_s, ceil(N_s/64)] words
+ *   row_offsets  : in int32;        sequence s holds n_q_heads*N_s + 1 row offsets, which start
+ *                                   at 0 and index the sequence's own part of col_idx
+ *   col_offsets  : in int32;        sequence s holds room for all its admissible pairs
+ *                                   (n_q_heads*N_s*(N_s+1)/2, or n_q_heads*N_s*N_s when bidirectional)
+ *   info         : [4 * n_seqs] int32, four per sequence as in prism_estimate (never overflows)
+ * The sequences are processed one after the other on `stream` and share the workspace
+ * (prism_*_varlen_workspace_bytes: the largest single sequence's need), so a batch of many
+ * short sequences costs one set of kernel launches per sequence.
+ * Errors: PRISM_ERR_INVALID_ARG for malformed offsets, PRISM_ERR_UNSUPPORTED if a sequence
+ * exceeds the per-sequence limits; nothing is launched in either case.
+ * ---------------------------------------------------------------------------------- */
+int prism_varlen_layout(const prism_params* params, const int32_t* cu_seqlens /* host */, int n_seqs,
+                        int64_t* mask_offsets, int64_t* row_offsets, int64_t* col_offsets /* host, out */);
+
+int prism_estimate_varlen_workspace_bytes(const prism_params* params, const int32_t* cu_seqlens /* host */,
+                                          int n_seqs, size_t* bytes /* host, out */);
+
+int prism_estimate_varlen(const prism_params* params, const int32_t* cu_seqlens /* host */, int n_seqs,
+                          const void* q_bf16, const void* k_bf16,
+                          uint64_t* mask_bits, int32_t* row_ptr, int32_t* col_idx, int32_t* info,
+                          void* workspace, size_t workspace_bytes, void* stream);
+
+int prism_sparse_attn_varlen_workspace_bytes(const prism_params* params, const int32_t* cu_seqlens /* host */,
+                                             int n_seqs, size_t* bytes /* host, out */);
+
+int prism_sparse_attn_varlen(const prism_params* params, const int32_t* cu_seqlens /* host */, int n_seqs,
+                             const void* q_bf16, const void* k_bf16, const void* v_bf16,
+                             const int32_t* row_ptr, const int32_t* col_idx,
+                             void* out_bf16, float* lse,
+                             void* workspace, size_t workspace_bytes, void* stream);
 
 #ifdef __cplusplus
 }

@@ -66,7 +66,8 @@ EXPORTS = ("prism_version", "prism_status_string", "prism_estimate_workspace_byt
            "prism_estimate", "prism_estimate_static", "prism_estimate_bands", "prism_rope_estimate", "prism_block_scores",
            "prism_block_scores_bands", "prism_mask_to_csr", "prism_causal_csr", "prism_dense_csr",
            "prism_sparse_attn_workspace_bytes", "prism_sparse_attn", "prism_v_image",
-           "prism_sparse_attn_pre")
+           "prism_sparse_attn_pre", "prism_varlen_layout", "prism_estimate_varlen_workspace_bytes",
+           "prism_estimate_varlen", "prism_sparse_attn_varlen_workspace_bytes", "prism_sparse_attn_varlen")
 
 
 def _load() -> ctypes.CDLL:
@@ -99,6 +100,12 @@ def _load() -> ctypes.CDLL:
     lib.prism_sparse_attn.argtypes = [P, vp, vp, vp, vp, vp, i64, vp, vp, vp, sz, vp]
     lib.prism_v_image.argtypes = [P, vp, vp, sz, vp]
     lib.prism_sparse_attn_pre.argtypes = [P, vp, vp, vp, sz, vp, vp, i64, vp, vp, vp]
+    I32P, I64P = ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int64)
+    lib.prism_varlen_layout.argtypes = [P, I32P, ctypes.c_int, I64P, I64P, I64P]
+    lib.prism_estimate_varlen_workspace_bytes.argtypes = [P, I32P, ctypes.c_int, ctypes.POINTER(sz)]
+    lib.prism_estimate_varlen.argtypes = [P, I32P, ctypes.c_int, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.prism_sparse_attn_varlen_workspace_bytes.argtypes = [P, I32P, ctypes.c_int, ctypes.POINTER(sz)]
+    lib.prism_sparse_attn_varlen.argtypes = [P, I32P, ctypes.c_int, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     for name in EXPORTS[2:]:
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
@@ -284,6 +291,56 @@ def prism_sparse_attn_pre(params: prism_params, q: torch.Tensor, k: torch.Tensor
     _check(_load().prism_sparse_attn_pre(ctypes.byref(params), _ptr(q), _ptr(k), _ptr(v_image),
                                          v_image.numel(), _ptr(row_ptr), _ptr(col_idx), col_count,
                                          _ptr(out), _ptr(lse), _stream()), "prism_sparse_attn_pre")
+
+
+# ---- packed variable-length batches ---------------------------------------------------------
+def _cu(cu_seqlens):
+    """host int32 array of sequence offsets -> (ctypes array, number of sequences)"""
+    vals = [int(x) for x in cu_seqlens]
+    return (ctypes.c_int32 * len(vals))(*vals), len(vals) - 1
+
+
+def prism_varlen_layout(params: prism_params, cu_seqlens):
+    """(mask_offsets, row_offsets, col_offsets): lists of n_seqs + 1 ints, last = total."""
+    cu, n = _cu(cu_seqlens)
+    outs = [(ctypes.c_int64 * (n + 1))() for _ in range(3)]
+    _check(_load().prism_varlen_layout(ctypes.byref(params), cu, n, *outs), "prism_varlen_layout")
+    return tuple(list(o) for o in outs)
+
+
+def prism_estimate_varlen_workspace_bytes(params: prism_params, cu_seqlens) -> int:
+    cu, n = _cu(cu_seqlens)
+    nb = ctypes.c_size_t(0)
+    _check(_load().prism_estimate_varlen_workspace_bytes(ctypes.byref(params), cu, n, ctypes.byref(nb)),
+           "prism_estimate_varlen_workspace_bytes")
+    return nb.value
+
+
+def prism_estimate_varlen(params: prism_params, cu_seqlens, q: torch.Tensor, k: torch.Tensor,
+                          mask_bits: torch.Tensor, row_ptr: torch.Tensor, col_idx: torch.Tensor,
+                          info: torch.Tensor, workspace: torch.Tensor) -> None:
+    cu, n = _cu(cu_seqlens)
+    _check(_load().prism_estimate_varlen(ctypes.byref(params), cu, n, _ptr(q), _ptr(k), _ptr(mask_bits),
+                                         _ptr(row_ptr), _ptr(col_idx), _ptr(info), _ptr(workspace),
+                                         workspace.numel(), _stream()), "prism_estimate_varlen")
+
+
+def prism_sparse_attn_varlen_workspace_bytes(params: prism_params, cu_seqlens) -> int:
+    cu, n = _cu(cu_seqlens)
+    nb = ctypes.c_size_t(0)
+    _check(_load().prism_sparse_attn_varlen_workspace_bytes(ctypes.byref(params), cu, n, ctypes.byref(nb)),
+           "prism_sparse_attn_varlen_workspace_bytes")
+    return nb.value
+
+
+def prism_sparse_attn_varlen(params: prism_params, cu_seqlens, q: torch.Tensor, k: torch.Tensor,
+                             v: torch.Tensor, row_ptr: torch.Tensor, col_idx: torch.Tensor,
+                             out: torch.Tensor, lse: Optional[torch.Tensor], workspace: torch.Tensor) -> None:
+    cu, n = _cu(cu_seqlens)
+    _check(_load().prism_sparse_attn_varlen(ctypes.byref(params), cu, n, _ptr(q), _ptr(k), _ptr(v),
+                                            _ptr(row_ptr), _ptr(col_idx), _ptr(out), _ptr(lse),
+                                            _ptr(workspace), workspace.numel(), _stream()),
+           "prism_sparse_attn_varlen")
 
 
 # ---- conveniences for callers holding numpy bf16 bit patterns --------------------------

@@ -17,6 +17,7 @@
 // A operand.
 #include "prism_common.h"
 
+#include <mutex>
 #include <type_traits>
 
 namespace prism {
@@ -31,29 +32,31 @@ namespace prism {
 // exact there; smaller magnitudes lose at most 2^-25 absolute.  A block holding a finite value beyond
 // the fp16 range sets range_flags[kv head * N + block] = 1 (else 0): such inputs go through the
 // general kernel and the bf16 image.
-template <int BLK>
+template <int BLK, int D>
 __global__ __launch_bounds__(256) void vt_image_kernel(const uint16_t* __restrict__ v,
                                                        uint16_t* __restrict__ vt, int L, int N,
+                                                       size_t kv_head_stride,
                                                        uint16_t* __restrict__ vt16,
                                                        int32_t* __restrict__ range_flags) {
-  __shared__ uint16_t tile[BLK][kHeadDim + 2];
+  __shared__ uint16_t tile[BLK][D + 2];
   __shared__ int s_over;
   const int blk = blockIdx.x, kvh = blockIdx.y, t = threadIdx.x;
-  const uint16_t* src = v + ((size_t)kvh * L + (size_t)blk * BLK) * kHeadDim;
+  const uint16_t* src = v + (size_t)kvh * kv_head_stride + (size_t)blk * BLK * D;
   const int cnt = min(BLK, L - blk * BLK);
   if (t == 0) s_over = 0;
-  for (int idx = t; idx < BLK * 16; idx += 256) {
-    const int row = idx >> 4, c = idx & 15;
+  constexpr int RCH = D / 8;                         // 16-byte chunks per token row
+  for (int idx = t; idx < BLK * RCH; idx += 256) {
+    const int row = idx / RCH, c = idx % RCH;
     u32x4 x = {0u, 0u, 0u, 0u};                       // V is read once: streaming (non-temporal) loads
-    if (row < cnt) x = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + (size_t)row * kHeadDim + c * 8));
-    uint32_t* dst = reinterpret_cast<uint32_t*>(&tile[row][c * 8]);   // 4-byte aligned: row stride 260 B
+    if (row < cnt) x = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + (size_t)row * D + c * 8));
+    uint32_t* dst = reinterpret_cast<uint32_t*>(&tile[row][c * 8]);   // 4-byte aligned: row stride 2*D + 4 B
     dst[0] = x[0]; dst[1] = x[1]; dst[2] = x[2]; dst[3] = x[3];
   }
   __syncthreads();
   constexpr int CPR = BLK / 8;                       // 16-byte chunks per image row
-  uint16_t* dstb = vt + ((size_t)kvh * N + blk) * (size_t)kHeadDim * BLK;
+  uint16_t* dstb = vt + ((size_t)kvh * N + blk) * (size_t)D * BLK;
   bool over = false;
-  for (int idx = t; idx < kHeadDim * CPR; idx += 256) {
+  for (int idx = t; idx < D * CPR; idx += 256) {
     const int d = idx / CPR, c = idx % CPR;
     uint32_t w[4], w16[4];
 #pragma unroll
@@ -73,7 +76,7 @@ __global__ __launch_bounds__(256) void vt_image_kernel(const uint16_t* __restric
     }
     *reinterpret_cast<uint4*>(dstb + (size_t)d * BLK + c * 8) = make_uint4(w[0], w[1], w[2], w[3]);
     if (vt16 != nullptr)
-      *reinterpret_cast<uint4*>(vt16 + ((size_t)kvh * N + blk) * (size_t)kHeadDim * BLK + (size_t)d * BLK + c * 8) =
+      *reinterpret_cast<uint4*>(vt16 + ((size_t)kvh * N + blk) * (size_t)D * BLK + (size_t)d * BLK + c * 8) =
           make_uint4(w16[0], w16[1], w16[2], w16[3]);
   }
   if (vt16 != nullptr) {
@@ -96,21 +99,25 @@ __global__ __launch_bounds__(256) void vt_image_kernel(const uint16_t* __restric
 // of the last step of the current row and reads that row's queue entry during the last PV, so
 // a row switch exposes only the load of the Q rows and of the first K tile.
 // =====================================================================================
-template <int BLK>
+template <int BLK, int D>
 struct AttnCfg {
   static constexpr int kWaves = BLK / 32;
   static constexpr int kThreads = kWaves * 64;
-  static constexpr int kTileBytes = BLK * kHeadDim * 2;
+  static constexpr int kTileBytes = BLK * D * 2;
   static constexpr int kChunks = kTileBytes / 16;          // 16-byte pieces per tile
-  static constexpr int kPerThread = kChunks / kThreads;    // = 8
+  static constexpr int kPerThread = kChunks / kThreads;    // = D / 16
+  static constexpr int kKCpr = D / 8;                      // chunks per K row
   static constexpr int kVtCpr = BLK / 8;                   // chunks per V^T row
+  static constexpr int kDTiles = D / 32;                   // 32-dim tiles of the output
+  static constexpr int kKSteps = D / 16;                   // MFMA k-steps of S^T = K Q^T
+  static constexpr int kWavesPerSimd = D > 128 ? 1 : 2;    // register budget: 512 or 256 per lane
 };
 
 // Asynchronous global -> LDS tile copies (buffer_load_dwordx4 ... lds: every lane fetches 16
 // bytes at rsrc.base + voffset + soffset and the wave's 64 pieces land contiguously in LDS
 // at M0-base + 16*lane).  LDS slot p (16-byte units) of a tile belongs to (row, c') with c'
 // the swizzled chunk position; the lane that fills it reads global chunk
-// c = c' ^ (row mod chunks-per-row), i.e. the swizzle is applied on the global side.
+// c = c' ^ swizzle(row), i.e. the swizzle is applied on the global side.
 // Buffer (not flat/global) addressing is used on purpose: LDS reads issued while such
 // copies are in flight then keep exact lgkmcnt tracking in the compiler.
 typedef __attribute__((address_space(3))) void* lptr_t;
@@ -120,23 +127,32 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, ui
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
 }
 
-// byte offset inside a tile of the 16-byte piece that LDS slot p holds
-template <int BLK>
-__device__ __forceinline__ int k_piece_offset(int p) {
-  const int row = p >> 4;
-  return row * 256 + (((p & 15) ^ (row & 15)) << 4);
+// XOR applied to the chunk index of K-tile row `row` so that 16 consecutive rows put the same
+// chunk on 16 different LDS bank groups: rows of 128 bytes (d = 64) come two to a 256-byte line,
+// rows of 512 bytes (d = 256) wrap the banks twice.
+template <int D>
+__device__ __forceinline__ int k_row_swizzle(int row) {
+  return D == 64 ? ((row >> 1) & 7) : (row & 15);
 }
-template <int BLK>
+
+// byte offset inside a tile of the 16-byte piece that LDS slot p holds
+template <int BLK, int D>
+__device__ __forceinline__ int k_piece_offset(int p) {
+  using C = AttnCfg<BLK, D>;
+  const int row = p / C::kKCpr;
+  return row * (D * 2) + (((p % C::kKCpr) ^ k_row_swizzle<D>(row)) << 4);
+}
+template <int BLK, int D>
 __device__ __forceinline__ int vt_piece_offset(int p) {
-  using C = AttnCfg<BLK>;
+  using C = AttnCfg<BLK, D>;
   const int row = p / C::kVtCpr;
   return row * (BLK * 2) + (((p % C::kVtCpr) ^ (row & (C::kVtCpr - 1))) << 4);
 }
 
-template <int BLK>
+template <int BLK, int D>
 __device__ __forceinline__ void async_load_k_tile(__amdgpu_buffer_rsrc_t rs, int tile_off, char* lds,
                                                   int t) {
-  using C = AttnCfg<BLK>;
+  using C = AttnCfg<BLK, D>;
   // wave-uniform LDS base, re-materialised here so that the per-piece M0 values are formed
   // with scalar adds instead of being kept live (and spilled) across the whole loop
   int wave_base = __builtin_amdgcn_readfirstlane(t & ~63);
@@ -144,19 +160,19 @@ __device__ __forceinline__ void async_load_k_tile(__amdgpu_buffer_rsrc_t rs, int
 #pragma unroll
   for (int i = 0; i < C::kPerThread; ++i)
     __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lptr_t)(lds + (i * C::kThreads + wave_base) * 16), 16,
-                                             k_piece_offset<BLK>(i * C::kThreads + t), tile_off, 0, 0);
+                                             k_piece_offset<BLK, D>(i * C::kThreads + t), tile_off, 0, 0);
 }
 
-template <int BLK>
+template <int BLK, int D>
 __device__ __forceinline__ void async_load_vt_tile(__amdgpu_buffer_rsrc_t rs, int tile_off, char* lds,
                                                    int t) {
-  using C = AttnCfg<BLK>;
+  using C = AttnCfg<BLK, D>;
   int wave_base = __builtin_amdgcn_readfirstlane(t & ~63);
   asm volatile("" : "+s"(wave_base));
 #pragma unroll
   for (int i = 0; i < C::kPerThread; ++i)
     __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lptr_t)(lds + (i * C::kThreads + wave_base) * 16), 16,
-                                             vt_piece_offset<BLK>(i * C::kThreads + t), tile_off, 0, 0);
+                                             vt_piece_offset<BLK, D>(i * C::kThreads + t), tile_off, 0, 0);
 }
 
 // Waits on the vector-memory counter, written with the builtin (immediate: vmcnt in bits 3:0,
@@ -168,10 +184,13 @@ __device__ __forceinline__ void wait_async_loads() {
   __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0)
   asm volatile("" ::: "memory");
 }
-// all but the 8 youngest vector-memory operations (one tile copy = 8 per thread) are complete
+// all but the youngest tile copy (kPerThread = d/16 vector-memory operations per thread) are complete
+template <int kPerThread>
 __device__ __forceinline__ void wait_async_loads_but_last_tile() {
+  static_assert(kPerThread <= 16, "vmcnt immediate");
   asm volatile("" ::: "memory");
-  __builtin_amdgcn_s_waitcnt(0x0F78);          // vmcnt(8)
+  // vmcnt(kPerThread): low four bits in 3:0, the two high bits in 15:14
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (kPerThread & 15) | ((kPerThread >> 4) << 14));
   asm volatile("" ::: "memory");
 }
 
@@ -203,6 +222,9 @@ __device__ __forceinline__ void tile_barrier() {
 // pull counters[8] }; a workgroup's pulls p = 0, 1, 2, ... from queue x are the entries
 // start[x] + p while p < len[x].
 enum { kItemEnd = 0, kItemRow = 2 };
+// MI355X: 8 accelerator dies (XCDs), each with its own L2; workgroups are dealt to them round-robin,
+// so the attention kernels keep one work queue per XCD (the plan below has room for exactly kXcds).
+constexpr int kXcds = 8;
 constexpr int kPlanStart = 0, kPlanLen = 8, kPlanCounter = 16, kPlanFlags = 24, kPlanInts = 32;
 // plan[kPlanFlags]: bit 0 = some list holds an entry that must be skipped (negative, beyond the
 // row's last admissible block): such lists go through the general kernel, clean lists through the
@@ -217,14 +239,15 @@ __device__ __forceinline__ int item_kind(int pulled, int seg_start, int seg_len,
 
 // kStreamOnly (PRISM_FLAG_STREAM_ONLY): the same tile copies, waits, barriers and queue traffic
 // with the arithmetic left out; it measures how long the memory side of a call takes alone.
-template <int BLK, bool kStreamOnly>
-__global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
+template <int BLK, bool kStreamOnly, int D>
+__global__ __launch_bounds__((AttnCfg<BLK, D>::kThreads), (AttnCfg<BLK, D>::kWavesPerSimd)) void sparse_attn_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ vt,
     const int32_t* __restrict__ col_idx, const int4* __restrict__ items, int32_t* __restrict__ plan,
     uint16_t* __restrict__ out, float* __restrict__ lse, int h, int h_kv, int L, int N,
-    int causal, int only_dirty) {
+    HeadStrides hs, int causal, int only_dirty) {
 #if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the kernel's signature
-  using C = AttnCfg<BLK>;
+  using C = AttnCfg<BLK, D>;
+  constexpr int KS = C::kKSteps, DT = C::kDTiles;
   // launched behind the 64-queries-per-wave kernel: only lists that kernel does not take
   if (only_dirty && (plan[kPlanFlags] & kFlagDirtyLists) == 0) return;
   constexpr int KT = BLK / 32;                       // 32-key tiles per kv block
@@ -235,15 +258,16 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int l32 = lane & 31, hf = lane >> 5;
   const int g = h / h_kv;
-  const float sm_scale = 1.4426950408889634f * 0.08838834764831845f;   // log2(e) / sqrt(128)
+  // log2(e) / sqrt(d)
+  const float sm_scale = 1.4426950408889634f * (D == 64 ? 0.125f : (D == 128 ? 0.08838834764831845f : 0.0625f));
 
   // LDS read offsets of this lane inside a 32-row slab: row l32, swizzled chunk
-  // (2*step + hf) ^ (row mod chunks-per-row).  The K tile has 16 chunks per row; the V^T
-  // tile has BLK/8 (for BLK = 128 the two tables coincide).
+  // (2*step + hf) ^ swizzle(row).  The K tile has d/8 chunks per row; the V^T tile has BLK/8
+  // (for BLK = 128 and d = 128 the two tables coincide).
   constexpr int kDepth = 8;                                // LDS reads kept in flight
-  int koff[8], voff[KT * 2];
+  int koff[KS], voff[KT * 2];
 #pragma unroll
-  for (int st = 0; st < 8; ++st) koff[st] = l32 * 256 + (((2 * st + hf) ^ (l32 & 15)) << 4);
+  for (int st = 0; st < KS; ++st) koff[st] = l32 * (D * 2) + (((2 * st + hf) ^ k_row_swizzle<D>(l32)) << 4);
 #pragma unroll
   for (int st = 0; st < KT * 2; ++st)
     voff[st] = l32 * (BLK * 2) + (((2 * st + hf) ^ (l32 & (C::kVtCpr - 1))) << 4);
@@ -257,14 +281,14 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
   // A workgroup whose queue is exhausted goes on with rows of another XCD's queue, so the XCDs
   // finish together although the lists of one may take longer per block than those of another;
   // it leaves the loop once it has seen every queue exhausted.
-  const int n_queues = gridDim.x < 8 ? 1 : 8;
+  const int n_queues = gridDim.x < kXcds ? 1 : kXcds;
   int my_queue = blockIdx.x % n_queues;
   int seg_start = plan[kPlanStart + my_queue];
   int seg_len = plan[kPlanLen + my_queue];
   int32_t* counter = plan + kPlanCounter;
   const int vmax_nc = N - 1;
   const int tail = L - (N - 1) * BLK;              // tokens in the last block (BLK unless ragged)
-  const uint32_t head_bytes = (uint32_t)L * kHeadDim * 2;
+  const uint32_t head_bytes = (uint32_t)L * D * 2;
   const uint32_t image_head_bytes = (uint32_t)N * C::kTileBytes;
 
   // The queue is pulled when a workgroup is about to become free (at the top of the last
@@ -340,10 +364,10 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
     if (!has_work) {
       // a row without a valid entry (o = 0, lse = -inf): no tile work; pull the next row right away
       if (kind_cur == kItemRow && qrow < L) {
-        uint16_t* op = out + ((size_t)hq * L + qrow) * kHeadDim + hf * 64;
+        uint16_t* op = out + (size_t)hq * hs.q + (size_t)qrow * D + hf * (D / 2);
 #pragma unroll
-        for (int c = 0; c < 8; ++c) *reinterpret_cast<uint4*>(op + c * 8) = make_uint4(0u, 0u, 0u, 0u);
-        if (lse != nullptr && hf == 0) lse[(size_t)hq * L + qrow] = -INFINITY;
+        for (int c = 0; c < D / 16; ++c) *reinterpret_cast<uint4*>(op + c * 8) = make_uint4(0u, 0u, 0u, 0u);
+        if (lse != nullptr && hf == 0) lse[(size_t)hq * hs.lse + qrow] = -INFINITY;
       }
       if (t == 0) next_item = atomicAdd(counter + my_queue, 1);
       __syncthreads();
@@ -360,24 +384,24 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
     // K and V^T of this kv head as buffer resources (tile v starts at byte v * kTileBytes).
     // K is the caller's tensor: rows past L in a ragged last block are outside the resource and
     // read as zeros.  The V^T image is padded to whole blocks.
-    const __amdgpu_buffer_rsrc_t krs = make_rsrc(k + (size_t)kvh * L * kHeadDim, head_bytes);
-    const __amdgpu_buffer_rsrc_t vrs = make_rsrc(vt + (size_t)kvh * N * BLK * kHeadDim, image_head_bytes);
+    const __amdgpu_buffer_rsrc_t krs = make_rsrc(k + (size_t)kvh * hs.kv, head_bytes);
+    const __amdgpu_buffer_rsrc_t vrs = make_rsrc(vt + (size_t)kvh * N * BLK * D, image_head_bytes);
     const int vmax = causal ? u : vmax_nc;
 
     // Q fragments (B operand of S^T = K Q^T): query row 32*wave + l32, dims 16*ks + 8*hf ..+7
-    bf16x8 qf[8];
+    bf16x8 qf[KS];
     {
-      const uint16_t* qp = q + ((size_t)hq * L + min(qrow, L - 1)) * kHeadDim + hf * 8;
+      const uint16_t* qp = q + (size_t)hq * hs.q + (size_t)min(qrow, L - 1) * D + hf * 8;
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16);
+      for (int ks = 0; ks < KS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16);
     }
-    async_load_k_tile<BLK>(krs, v * C::kTileBytes, lds_k, t);
+    async_load_k_tile<BLK, D>(krs, v * C::kTileBytes, lds_k, t);
     wait_async_loads();
     tile_barrier();
 
-    f32x16 oacc[4];
+    f32x16 oacc[DT];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < DT; ++i)
 #pragma unroll
       for (int r = 0; r < 16; ++r) oacc[i][r] = 0.f;
     float m_run = -INFINITY;          // running max, in units of log2: s * sm_scale
@@ -391,20 +415,22 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
       if (kLast && t == 0) pulled_reg = atomicAdd(counter + my_queue, 1);
 
       // ---- V(j) -> LDS, in flight during S^T and the softmax ----
-      async_load_vt_tile<BLK>(vrs, v * C::kTileBytes, lds_v, t);
+      async_load_vt_tile<BLK, D>(vrs, v * C::kTileBytes, lds_v, t);
 
       f32x16 sacc[KT];
       if (!kStreamOnly) {
       // ---- S^T = K Q^T ----
-      // Flat software pipeline over the KT*8 (tile, k-step) pairs: the LDS read of step
+      // Flat software pipeline over the KT*KS (tile, k-step) pairs: the LDS read of step
       // i + kDepth is issued right after the MFMA of step i, in source order.
       const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
       {
-        constexpr int kSteps = KT * 8;
+        constexpr int kSteps = KT * KS;
+        constexpr int kSlab = 32 * D * 2;              // bytes of 32 key rows
+        static_assert(kSteps >= kDepth, "pipeline deeper than the phase");
         bf16x8 fr[kDepth];
 #pragma unroll
         for (int i = 0; i < kDepth; ++i)
-          fr[i] = *reinterpret_cast<const bf16x8*>(lds_k + (i % KT) * 8192 + koff[i / KT]);
+          fr[i] = *reinterpret_cast<const bf16x8*>(lds_k + (i % KT) * kSlab + koff[i / KT]);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < kSteps; ++i) {
@@ -412,7 +438,7 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
           sacc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i % kDepth], qf[ks], ks == 0 ? zero16 : sacc[kt], 0, 0, 0);
           if (i + kDepth < kSteps) {
             const int j = i + kDepth;
-            fr[i % kDepth] = *reinterpret_cast<const bf16x8*>(lds_k + (j % KT) * 8192 + koff[j / KT]);
+            fr[i % kDepth] = *reinterpret_cast<const bf16x8*>(lds_k + (j % KT) * kSlab + koff[j / KT]);
           }
           __builtin_amdgcn_sched_barrier(0);
         }
@@ -422,7 +448,7 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
 
       // every wave is done reading K(j): K(j+1) can start now and land during softmax + PV
       tile_barrier();
-      if (!kLast) async_load_k_tile<BLK>(krs, v_next * C::kTileBytes, lds_k, t);
+      if (!kLast) async_load_k_tile<BLK, D>(krs, v_next * C::kTileBytes, lds_k, t);
 
       bf16x8 pf[KT][2];
       if (!kStreamOnly) {
@@ -461,7 +487,7 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
         const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
         l_run *= alpha;
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < DT; ++i)
 #pragma unroll
           for (int r = 0; r < 16; ++r) oacc[i][r] *= alpha;
         m_run = m_new;
@@ -495,7 +521,7 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
         if (t == 0) next_item = pulled_reg;         // the queue position pulled at the top of the step
         wait_async_loads();                          // this wave's share of V(j) has landed
       } else {
-        wait_async_loads_but_last_tile();            // ... while the 8 younger loads of K(j+1) may still be in flight
+        wait_async_loads_but_last_tile<C::kPerThread>();   // ... while the younger loads of K(j+1) may still be in flight
       }
       tile_barrier();                                // V(j) complete
 
@@ -509,22 +535,23 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
       }
 
       if (!kStreamOnly) {
-      // ---- O^T += V^T P^T ----  (same flat pipeline over the 4*KT*2 (d-tile, k-step) pairs)
+      // ---- O^T += V^T P^T ----  (same flat pipeline over the DT*KT*2 (d-tile, k-step) pairs)
       {
         constexpr int kPer = KT * 2;                   // k-steps per d-tile
-        constexpr int kSteps = 4 * kPer;
+        constexpr int kSteps = DT * kPer;
+        static_assert(kSteps >= kDepth, "pipeline deeper than the phase");
         bf16x8 fr[kDepth];
 #pragma unroll
         for (int i = 0; i < kDepth; ++i)
-          fr[i] = *reinterpret_cast<const bf16x8*>(lds_v + (i % 4) * (32 * BLK * 2) + voff[i / 4]);
+          fr[i] = *reinterpret_cast<const bf16x8*>(lds_v + (i % DT) * (32 * BLK * 2) + voff[i / DT]);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < kSteps; ++i) {
-          const int dt = i % 4, st = i / 4;            // consecutive MFMAs: independent accumulators
+          const int dt = i % DT, st = i / DT;          // consecutive MFMAs: independent accumulators
           oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i % kDepth], pf[st >> 1][st & 1], oacc[dt], 0, 0, 0);
           if (i + kDepth < kSteps) {
             const int j = i + kDepth;
-            fr[i % kDepth] = *reinterpret_cast<const bf16x8*>(lds_v + (j % 4) * (32 * BLK * 2) + voff[j / 4]);
+            fr[i % kDepth] = *reinterpret_cast<const bf16x8*>(lds_v + (j % DT) * (32 * BLK * 2) + voff[j / DT]);
           }
           __builtin_amdgcn_sched_barrier(0);
         }
@@ -564,10 +591,10 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
     // ---- epilogue: O = O^T / l, bf16, [q][d] ----
     const float l_tot = other_half_sum(l_run);
     const float inv_l = l_tot > 0.f ? 1.0f / l_tot : 0.f;
-    uint16_t* op = out + ((size_t)hq * L + qrow) * kHeadDim;
+    uint16_t* op = out + (size_t)hq * hs.q + (size_t)qrow * D;
     if (qrow < L) {
 #pragma unroll
-      for (int dt = 0; dt < 4; ++dt)
+      for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
         for (int gq = 0; gq < 4; ++gq) {
           const int d0 = dt * 32 + gq * 8 + hf * 4;
@@ -582,7 +609,7 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
         }
     }
     if (lse != nullptr && hf == 0 && qrow < L)
-      lse[(size_t)hq * L + qrow] =
+      lse[(size_t)hq * hs.lse + qrow] =
           l_tot > 0.f ? (m_run + log2f(l_tot)) * 0.6931471805599453f : -INFINITY;
 
     // ---- the row pulled in the last step becomes the current one ----
@@ -608,7 +635,8 @@ __global__ __launch_bounds__(AttnCfg<BLK>::kThreads, 2) void sparse_attn_kernel(
 __global__ __launch_bounds__(128) void sparse_attn_w64_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ vt,
     const int32_t* __restrict__ col_idx, const int4* __restrict__ items, int32_t* __restrict__ plan,
-    uint16_t* __restrict__ out, float* __restrict__ lse, int h, int h_kv, int L, int N, int causal) {
+    uint16_t* __restrict__ out, float* __restrict__ lse, int h, int h_kv, int L, int N, HeadStrides hs,
+    int causal) {
 #if defined(__HIP_DEVICE_COMPILE__)
   __shared__ __attribute__((aligned(1024))) char lds_tiles[65536];
   __shared__ int s_pulled, s_queue;
@@ -618,7 +646,7 @@ __global__ __launch_bounds__(128) void sparse_attn_w64_kernel(
   const int lane = t & 63;
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
   const int g = h / h_kv;
-  const int n_queues = gridDim.x < 8 ? 1 : 8;
+  const int n_queues = gridDim.x < kXcds ? 1 : kXcds;
   int my_queue = blockIdx.x % n_queues;
   int seg_start = plan[kPlanStart + my_queue];
   int seg_len = plan[kPlanLen + my_queue];
@@ -685,21 +713,22 @@ __global__ __launch_bounds__(128) void sparse_attn_w64_kernel(
     // the next row's queue position is pulled now and looked at after this row
     if (t == 0) pulled = atomicAdd(counter + my_queue, 1);
 
-    const size_t row0 = (size_t)hq * L + (size_t)u * 128 + (size_t)wave * 64;   // this wave's first query
+    const size_t tok0 = (size_t)u * 128 + (size_t)wave * 64;                    // this wave's first query
+    const size_t row0 = (size_t)hq * hs.q + tok0 * kHeadDim;                     // its element offset in Q / O
     if (it >= end) {
       // a row without entries: o = 0, lse = -inf
       const int r = lane;                                   // 64 rows per wave, one per lane
-      uint16_t* op = out + (row0 + r) * kHeadDim;
+      uint16_t* op = out + row0 + (size_t)r * kHeadDim;
 #pragma unroll
       for (int c = 0; c < 16; ++c) *reinterpret_cast<uint4*>(op + c * 8) = make_uint4(0u, 0u, 0u, 0u);
-      if (lse != nullptr) lse[row0 + r] = -INFINITY;
+      if (lse != nullptr) lse[(size_t)hq * hs.lse + tok0 + r] = -INFINITY;
       continue;
     }
-    const uint16_t* q_row = q + row0 * kHeadDim;
-    uint16_t* o_row = out + row0 * kHeadDim;
-    float* lse_row = lse != nullptr ? lse + row0 : nullptr;
+    const uint16_t* q_row = q + row0;
+    uint16_t* o_row = out + row0;
+    float* lse_row = lse != nullptr ? lse + (size_t)hq * hs.lse + tok0 : nullptr;
     const int kvh = hq / g;
-    const uint16_t* k_head = k + (size_t)kvh * L * kHeadDim;
+    const uint16_t* k_head = k + (size_t)kvh * hs.kv;
     const uint16_t* vt_head = vt + (size_t)kvh * N * 128 * kHeadDim;
     const int32_t* col_row = col_idx + it;
     const int n_entries = end - it;
@@ -971,12 +1000,14 @@ struct AttnWs {
   size_t image, items, row_rank, row_part, bins, parts, plan, image16, range_flags, total;
 };
 // the fp16 image exists where the 64-queries-per-wave kernel can take the call
-static bool w64_shape(const prism_params* p) { return p->block == 128 && p->seq_len % 128 == 0; }
+static bool w64_shape(const prism_params* p) {
+  return p->block == 128 && p->head_dim == kHeadDim && p->seq_len % 128 == 0;
+}
 
 static AttnWs attn_ws(const prism_params* p) {
   const size_t N = n_blocks(p);
   const size_t rows = (size_t)p->n_q_heads * N;
-  const size_t image_bytes = (size_t)p->n_kv_heads * N * p->block * kHeadDim * 2;
+  const size_t image_bytes = (size_t)p->n_kv_heads * N * p->block * p->head_dim * 2;
   AttnWs w;
   size_t off = 0;
   w.image = off;    off = align_up(off + image_bytes, 256);
@@ -1004,16 +1035,36 @@ static int check_image(const prism_params* params, const void* img, size_t bytes
   return PRISM_OK;
 }
 
-static int persistent_grid(int rows, int wgs_per_cu) {
-  static int cus = 0;                       // compute units of the current device
-  if (cus == 0) {
-    int dev = 0;
+// Facts about the device the calls run on, asked from the runtime once per device.
+struct DeviceFacts {
+  int cus;          // compute units
+};
+constexpr int kMaxDevices = 64;
+static int device_facts(DeviceFacts* out) {
+  static std::mutex mu;
+  static DeviceFacts facts[kMaxDevices];
+  static bool known[kMaxDevices];
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return PRISM_ERR_HIP;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!known[dev]) {
     hipDeviceProp_t prop;
-    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess)
-      return -1;
-    cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    if (hipGetDeviceProperties(&prop, dev) != hipSuccess) return PRISM_ERR_HIP;
+    facts[dev].cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    known[dev] = true;
   }
-  const int resident = cus * wgs_per_cu;
+  *out = facts[dev];
+  return PRISM_OK;
+}
+
+// The memory-side cache holds 256 MB; the K and V^T of the kv heads that are in flight together are
+// kept to kCacheBudgetBytes of it.
+constexpr size_t kCacheBudgetBytes = (size_t)160 << 20;
+
+static int persistent_grid(int rows, int wgs_per_cu) {
+  DeviceFacts f;
+  if (device_facts(&f) != PRISM_OK) return -1;
+  const int resident = f.cus * wgs_per_cu;
   return rows < resident ? rows : resident;
 }
 
@@ -1025,6 +1076,33 @@ extern "C" int prism_sparse_attn_workspace_bytes(const prism_params* params, siz
   return PRISM_OK;
 }
 
+template <int BLK, int D>
+static void launch_vt_image(const prism_params* p, const HeadStrides& hs, const uint16_t* v, uint16_t* vt,
+                            uint16_t* vt16, int32_t* range_flags, hipStream_t st) {
+  const int N = n_blocks(p);
+  hipLaunchKernelGGL((vt_image_kernel<BLK, D>), dim3(N, p->n_kv_heads), dim3(256), 0, st, v, vt, p->seq_len, N,
+                     hs.kv, vt16, range_flags);
+}
+
+static int v_image_core(const prism_params* params, const HeadStrides& hs, const void* v_bf16, char* ws,
+                        hipStream_t st) {
+  const AttnWs W = attn_ws(params);
+  uint16_t* vt16 = w64_shape(params) ? reinterpret_cast<uint16_t*>(ws + W.image16) : nullptr;
+  int32_t* range_flags = w64_shape(params) ? reinterpret_cast<int32_t*>(ws + W.range_flags) : nullptr;
+  const uint16_t* v = (const uint16_t*)v_bf16;
+  uint16_t* vt = reinterpret_cast<uint16_t*>(ws + W.image);
+  if (params->block == 128) {
+    if (params->head_dim == 64) launch_vt_image<128, 64>(params, hs, v, vt, vt16, range_flags, st);
+    else if (params->head_dim == 128) launch_vt_image<128, 128>(params, hs, v, vt, vt16, range_flags, st);
+    else launch_vt_image<128, 256>(params, hs, v, vt, vt16, range_flags, st);
+  } else {
+    if (params->head_dim == 64) launch_vt_image<64, 64>(params, hs, v, vt, vt16, range_flags, st);
+    else if (params->head_dim == 128) launch_vt_image<64, 128>(params, hs, v, vt, vt16, range_flags, st);
+    else launch_vt_image<64, 256>(params, hs, v, vt, vt16, range_flags, st);
+  }
+  return launch_status();
+}
+
 extern "C" int prism_v_image(const prism_params* params, const void* v_bf16, void* v_image,
                              size_t v_image_bytes, void* stream) {
   int rc = check_params(params);
@@ -1032,46 +1110,40 @@ extern "C" int prism_v_image(const prism_params* params, const void* v_bf16, voi
   if (!v_bf16) return PRISM_ERR_INVALID_ARG;
   rc = check_image(params, v_image, v_image_bytes);
   if (rc != PRISM_OK) return rc;
-  hipStream_t st = static_cast<hipStream_t>(stream);
-  const int N = n_blocks(params);
-  const AttnWs W = attn_ws(params);
-  char* ws = static_cast<char*>(v_image);
-  uint16_t* vt16 = w64_shape(params) ? reinterpret_cast<uint16_t*>(ws + W.image16) : nullptr;
-  int32_t* range_flags = reinterpret_cast<int32_t*>(ws + W.range_flags);
-  if (params->block == 128)
-    hipLaunchKernelGGL(vt_image_kernel<128>, dim3(N, params->n_kv_heads), dim3(256), 0, st,
-                       (const uint16_t*)v_bf16, (uint16_t*)v_image, params->seq_len, N, vt16, range_flags);
-  else
-    hipLaunchKernelGGL(vt_image_kernel<64>, dim3(N, params->n_kv_heads), dim3(256), 0, st,
-                       (const uint16_t*)v_bf16, (uint16_t*)v_image, params->seq_len, N, (uint16_t*)nullptr,
-                       (int32_t*)nullptr);
-  return launch_status();
+  return v_image_core(params, contiguous_heads(params), v_bf16, static_cast<char*>(v_image),
+                      static_cast<hipStream_t>(stream));
 }
 
-extern "C" int prism_sparse_attn_pre(const prism_params* params, const void* q_bf16,
-                                     const void* k_bf16, void* v_image, size_t v_image_bytes,
-                                     const int32_t* row_ptr, const int32_t* col_idx,
-                                     int64_t col_count, void* out_bf16, float* lse, void* stream) {
-  int rc = check_params(params);
-  if (rc != PRISM_OK) return rc;
-  if (!q_bf16 || !k_bf16 || !row_ptr || !col_idx || !out_bf16 || col_count < 0)
-    return PRISM_ERR_INVALID_ARG;
-  rc = check_image(params, v_image, v_image_bytes);
-  if (rc != PRISM_OK) return rc;
-  hipStream_t st = static_cast<hipStream_t>(stream);
+template <int BLK, bool kStreamOnly, int D>
+static void launch_attn(int grid, hipStream_t st, const uint16_t* q, const uint16_t* k, const uint16_t* vt,
+                        const int32_t* col_idx, const int4* items, int32_t* plan, uint16_t* out, float* lse,
+                        int h, int h_kv, int L, int N, const HeadStrides& hs, int causal, int only_dirty) {
+  hipLaunchKernelGGL((sparse_attn_kernel<BLK, kStreamOnly, D>), dim3(grid), dim3(AttnCfg<BLK, D>::kThreads), 0, st,
+                     q, k, vt, col_idx, items, plan, out, lse, h, h_kv, L, N, hs, causal, only_dirty);
+}
+
+// Queue build + attention kernels of one sequence (arguments already validated).
+static int attn_core(const prism_params* params, const HeadStrides& hs, const void* q_bf16, const void* k_bf16,
+                     char* ws, const int32_t* row_ptr, const int32_t* col_idx, int64_t col_count,
+                     void* out_bf16, float* lse, hipStream_t st) {
   const int N = n_blocks(params);
-  const int h = params->n_q_heads, h_kv = params->n_kv_heads, L = params->seq_len;
+  const int h = params->n_q_heads, h_kv = params->n_kv_heads, L = params->seq_len, d = params->head_dim;
   const int R = h * N;
   const AttnWs W = attn_ws(params);
-  char* ws = static_cast<char*>(v_image);
   int4* items = reinterpret_cast<int4*>(ws + W.items);
   int32_t* row_rank = reinterpret_cast<int32_t*>(ws + W.row_rank);
   int32_t* row_part = reinterpret_cast<int32_t*>(ws + W.row_part);
   int32_t* bins = reinterpret_cast<int32_t*>(ws + W.bins);
   int32_t* parts = reinterpret_cast<int32_t*>(ws + W.parts);
   int32_t* plan = reinterpret_cast<int32_t*>(ws + W.plan);
-  // resident workgroups per CU: 64 KB of LDS and 4 waves each at B = 128, half of that at B = 64
-  const int grid = persistent_grid(R, params->block == 128 ? 2 : 4);
+  // resident workgroups per CU, by the LDS the two tiles of a workgroup take (2 * B * d * 2 bytes of the
+  // CU's 160 KB) and its waves: 2 at B = 128, d = 128 (64 KB, 4 waves); one when d = 256
+  const int tile_pair = 2 * params->block * d * 2;
+  int per_cu = (160 * 1024) / tile_pair;
+  per_cu = per_cu > 4 ? 4 : per_cu;
+  if (d > 128) per_cu = 1;
+  else if (params->block == 128 && per_cu > 2) per_cu = 2;
+  const int grid = persistent_grid(R, per_cu);
   if (grid <= 0) return PRISM_ERR_HIP;
 
   // queue plan: kv heads in phases that fit the memory-side cache
@@ -1079,10 +1151,9 @@ extern "C" int prism_sparse_attn_pre(const prism_params* params, const void* q_b
   pc.h = h;
   pc.g = h / h_kv;
   pc.N = N;
-  pc.n_queues = grid < 8 ? 1 : 8;
-  const size_t head_bytes = (size_t)L * kHeadDim * 2 * 2;                 // K + V^T of one kv head
-  const size_t cache_budget = (size_t)160 << 20;
-  pc.heads_per_phase = (int)(cache_budget / head_bytes) < 1 ? 1 : (int)(cache_budget / head_bytes);
+  pc.n_queues = grid < kXcds ? 1 : kXcds;
+  const size_t head_bytes = (size_t)L * d * 2 * 2;                        // K + V^T of one kv head
+  pc.heads_per_phase = (int)(kCacheBudgetBytes / head_bytes) < 1 ? 1 : (int)(kCacheBudgetBytes / head_bytes);
   pc.n_phases = (h_kv + pc.heads_per_phase - 1) / pc.heads_per_phase;
   if (pc.n_phases * kClasses > kMaxGroups) {                               // very many kv heads: larger phases
     pc.n_phases = kMaxGroups / kClasses;
@@ -1099,10 +1170,9 @@ extern "C" int prism_sparse_attn_pre(const prism_params* params, const void* q_b
                      parts, row_rank, row_part, plan, items);
   const int causal = pc.causal;
   const bool stream_only = (params->flags & PRISM_FLAG_STREAM_ONLY) != 0;
-  const dim3 grid3(grid);
   const uint16_t* qp = (const uint16_t*)q_bf16;
   const uint16_t* kp = (const uint16_t*)k_bf16;
-  const uint16_t* vp = (const uint16_t*)v_image;
+  const uint16_t* vp = reinterpret_cast<const uint16_t*>(ws + W.image);
   uint16_t* op = (uint16_t*)out_bf16;
   // Whole blocks of 128 tokens go through the 64-queries-per-wave kernel when every list is clean
   // (decided on the device, so the general kernel is queued behind it and returns at once unless
@@ -1115,28 +1185,42 @@ extern "C" int prism_sparse_attn_pre(const prism_params* params, const void* q_b
     const int vgrid = ((R + 3) / 4) > ((n_range_flags + 255) / 256) ? (R + 3) / 4 : (n_range_flags + 255) / 256;
     hipLaunchKernelGGL(queue_validate_kernel, dim3(vgrid), dim3(256), 0, st, row_ptr, col_idx, h, N,
                        pc.cap, causal, reinterpret_cast<const int32_t*>(ws + W.range_flags), n_range_flags, plan);
-    hipLaunchKernelGGL(sparse_attn_w64_kernel, grid3, dim3(128), 0, st, qp, kp,
+    hipLaunchKernelGGL(sparse_attn_w64_kernel, dim3(grid), dim3(128), 0, st, qp, kp,
                        reinterpret_cast<const uint16_t*>(ws + W.image16), col_idx, items, plan, op, lse, h, h_kv,
-                       L, N, causal);
+                       L, N, hs, causal);
   }
-  if (params->block == 128) {
-    const dim3 block3(AttnCfg<128>::kThreads);
-    if (stream_only)
-      hipLaunchKernelGGL((sparse_attn_kernel<128, true>), grid3, block3, 0, st, qp, kp, vp, col_idx, items,
-                         plan, op, lse, h, h_kv, L, N, causal, only_dirty);
-    else
-      hipLaunchKernelGGL((sparse_attn_kernel<128, false>), grid3, block3, 0, st, qp, kp, vp, col_idx, items,
-                         plan, op, lse, h, h_kv, L, N, causal, only_dirty);
+#define PRISM_ATTN(BLK, SO, D) \
+  launch_attn<BLK, SO, D>(grid, st, qp, kp, vp, col_idx, items, plan, op, lse, h, h_kv, L, N, hs, causal, only_dirty)
+  if (stream_only) {
+    // measurement aid of the d = 128 kernels only
+    if (d != 128) return PRISM_ERR_UNSUPPORTED;
+    if (params->block == 128) PRISM_ATTN(128, true, 128);
+    else PRISM_ATTN(64, true, 128);
+  } else if (params->block == 128) {
+    if (d == 64) PRISM_ATTN(128, false, 64);
+    else if (d == 128) PRISM_ATTN(128, false, 128);
+    else PRISM_ATTN(128, false, 256);
   } else {
-    const dim3 block3(AttnCfg<64>::kThreads);
-    if (stream_only)
-      hipLaunchKernelGGL((sparse_attn_kernel<64, true>), grid3, block3, 0, st, qp, kp, vp, col_idx, items,
-                         plan, op, lse, h, h_kv, L, N, causal, only_dirty);
-    else
-      hipLaunchKernelGGL((sparse_attn_kernel<64, false>), grid3, block3, 0, st, qp, kp, vp, col_idx, items,
-                         plan, op, lse, h, h_kv, L, N, causal, only_dirty);
+    if (d == 64) PRISM_ATTN(64, false, 64);
+    else if (d == 128) PRISM_ATTN(64, false, 128);
+    else PRISM_ATTN(64, false, 256);
   }
+#undef PRISM_ATTN
   return launch_status();
+}
+
+extern "C" int prism_sparse_attn_pre(const prism_params* params, const void* q_bf16,
+                                     const void* k_bf16, void* v_image, size_t v_image_bytes,
+                                     const int32_t* row_ptr, const int32_t* col_idx,
+                                     int64_t col_count, void* out_bf16, float* lse, void* stream) {
+  int rc = check_params(params);
+  if (rc != PRISM_OK) return rc;
+  if (!q_bf16 || !k_bf16 || !row_ptr || !col_idx || !out_bf16 || col_count < 0)
+    return PRISM_ERR_INVALID_ARG;
+  rc = check_image(params, v_image, v_image_bytes);
+  if (rc != PRISM_OK) return rc;
+  return attn_core(params, contiguous_heads(params), q_bf16, k_bf16, static_cast<char*>(v_image), row_ptr,
+                   col_idx, col_count, out_bf16, lse, static_cast<hipStream_t>(stream));
 }
 
 extern "C" int prism_sparse_attn(const prism_params* params, const void* q_bf16, const void* k_bf16,
@@ -1153,4 +1237,53 @@ extern "C" int prism_sparse_attn(const prism_params* params, const void* q_bf16,
   if (rc != PRISM_OK) return rc;
   return prism_sparse_attn_pre(params, q_bf16, k_bf16, workspace, workspace_bytes, row_ptr, col_idx,
                                col_count, out_bf16, lse, stream);
+}
+
+// ---- packed variable-length batches: one sequence after the other on the stream ---------
+extern "C" int prism_sparse_attn_varlen_workspace_bytes(const prism_params* params, const int32_t* cu_seqlens,
+                                                        int n_seqs, size_t* bytes) {
+  if (bytes == nullptr) return PRISM_ERR_INVALID_ARG;
+  int rc = prism_varlen_layout(params, cu_seqlens, n_seqs, nullptr, nullptr, nullptr);
+  if (rc != PRISM_OK) return rc;
+  size_t need = 0;
+  for (int s = 0; s < n_seqs; ++s) {
+    prism_params ps = *params;
+    ps.seq_len = cu_seqlens[s + 1] - cu_seqlens[s];
+    const size_t b = attn_ws(&ps).total;
+    need = b > need ? b : need;
+  }
+  *bytes = need;
+  return PRISM_OK;
+}
+
+extern "C" int prism_sparse_attn_varlen(const prism_params* params, const int32_t* cu_seqlens, int n_seqs,
+                                        const void* q_bf16, const void* k_bf16, const void* v_bf16,
+                                        const int32_t* row_ptr, const int32_t* col_idx, void* out_bf16,
+                                        float* lse, void* workspace, size_t workspace_bytes, void* stream) {
+  size_t need = 0;
+  int rc = prism_sparse_attn_varlen_workspace_bytes(params, cu_seqlens, n_seqs, &need);
+  if (rc != PRISM_OK) return rc;
+  if (!q_bf16 || !k_bf16 || !v_bf16 || !row_ptr || !col_idx || !out_bf16) return PRISM_ERR_INVALID_ARG;
+  if (workspace == nullptr || (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0 || workspace_bytes < need)
+    return PRISM_ERR_WORKSPACE;
+  const size_t d = params->head_dim, T = params->seq_len;
+  const HeadStrides hs{T * d, T * d, T};
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  int64_t ro = 0, co = 0;
+  for (int s = 0; s < n_seqs; ++s) {
+    prism_params ps = *params;
+    ps.seq_len = cu_seqlens[s + 1] - cu_seqlens[s];
+    const int64_t N = n_blocks(&ps), h = ps.n_q_heads;
+    const int64_t cap = (ps.flags & PRISM_FLAG_BIDIRECTIONAL) ? h * N * N : h * N * (N + 1) / 2;
+    const size_t tok = (size_t)cu_seqlens[s];
+    rc = v_image_core(&ps, hs, (const uint16_t*)v_bf16 + tok * d, static_cast<char*>(workspace), st);
+    if (rc != PRISM_OK) return rc;
+    rc = attn_core(&ps, hs, (const uint16_t*)q_bf16 + tok * d, (const uint16_t*)k_bf16 + tok * d,
+                   static_cast<char*>(workspace), row_ptr + ro, col_idx + co, cap, (uint16_t*)out_bf16 + tok * d,
+                   lse != nullptr ? lse + tok : nullptr, st);
+    if (rc != PRISM_OK) return rc;
+    ro += h * N + 1;
+    co += cap;
+  }
+  return PRISM_OK;
 }

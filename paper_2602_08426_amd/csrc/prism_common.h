@@ -8,7 +8,8 @@
 
 namespace prism {
 
-constexpr int kHeadDim = 128;
+constexpr int kHeadDim = 128;           // the head dim of the 64-queries-per-wave attention kernel
+constexpr int kMaxHeadDim = 256;        // head_dim is 64, 128 or 256
 constexpr int kMaxBlocks = 2048;       // N <= 2048  (128K tokens at B = 64)
 constexpr int kWave = 64;
 
@@ -25,7 +26,7 @@ inline int check_params(const prism_params* p) {
   if (p == nullptr) return PRISM_ERR_INVALID_ARG;
   if (p->n_q_heads <= 0 || p->n_kv_heads <= 0 || p->seq_len <= 0) return PRISM_ERR_INVALID_ARG;
   if (p->n_q_heads % p->n_kv_heads != 0) return PRISM_ERR_INVALID_ARG;
-  if (p->head_dim != kHeadDim) return PRISM_ERR_UNSUPPORTED;
+  if (p->head_dim != 64 && p->head_dim != 128 && p->head_dim != 256) return PRISM_ERR_UNSUPPORTED;
   if (p->block != 64 && p->block != 128) return PRISM_ERR_UNSUPPORTED;
   const int64_t n = ((int64_t)p->seq_len + p->block - 1) / p->block;   // a ragged last block is allowed
   if (n > kMaxBlocks) return PRISM_ERR_UNSUPPORTED;
@@ -46,6 +47,19 @@ inline int check_bands(const prism_params* p) {
   if (p->d_high == 0 && p->d_low == 0) return PRISM_ERR_INVALID_ARG;
   if (!(p->top_p > 0.0f) || !(p->top_p <= 1.0f)) return PRISM_ERR_INVALID_ARG;   // also rejects NaN
   return PRISM_OK;
+}
+
+// Element strides between consecutive heads of the caller's tensors.  One sequence per call has
+// contiguous heads (L * d); a sequence of a packed variable-length batch [heads, T, d] is addressed
+// through pointers moved to its first token and the strides of the whole batch (T * d, T).
+struct HeadStrides {
+  size_t q;      // Q and O
+  size_t kv;     // K and V
+  size_t lse;    // the log-sum-exp output
+};
+inline HeadStrides contiguous_heads(const prism_params* p) {
+  const size_t s = (size_t)p->seq_len * p->head_dim;
+  return HeadStrides{s, s, (size_t)p->seq_len};
 }
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }

@@ -17,15 +17,16 @@ namespace prism {
 // Configuration": first / last dims of every axis subspace); its vector is the
 // concatenation of the slices, zero-padded to a multiple of 32 for the MFMA k-steps.
 struct BandMap {
-  int8_t pos[2][kHeadDim];   // position of dim c inside band z (0 = high, 1 = low), -1: not a member
+  int16_t pos[2][kMaxHeadDim];   // position of dim c inside band z (0 = high, 1 = low), -1: not a member
   int32_t dz[2];             // dims in the band, 0 = band disabled
   int32_t dpad[2];           // dz rounded up to a multiple of 32
 };
 
 // Band vectors of all heads and blocks: [z][term], term = hi, mid, lo, each bf16.
-//   q-heads (read once per strip of 16 q-blocks): [h][N][128], plain rows;
+//   q-heads (read once per strip of 16 q-blocks): [h][N][bs], plain rows of bs = max(128, d)
+//   elements (band_stride below);
 //   kv heads (read by every strip of the g q-heads): behind them, in the order the score GEMM
-//   reads them: per head ceil(N/16) tiles of 16 blocks; per tile 4 k-steps of 32 band dims; per
+//   reads them: per head ceil(N/16) tiles of 16 blocks; per tile bs/32 k-steps of 32 band dims; per
 //   (tile, k-step) the 64 lanes' 16-byte MFMA operand pieces back to back (lane =
 //   16 * (dim / 8 % 4) + block % 16).  One operand fetch of a wave is then one contiguous KB
 //   instead of 16 rows of 64 bytes (a fetch of 16 rows costs the address path four times as
@@ -33,20 +34,23 @@ struct BandMap {
 struct BandVectors {
   uint16_t* v[2][3];
 };
-constexpr int kBandTileElems = 16 * kHeadDim;          // one tile of 16 blocks
+// elements per band vector: room for the widest band a head dim allows, at least four k-steps
+__host__ __device__ inline int band_stride(int head_dim) { return head_dim > 128 ? head_dim : 128; }
 
-// element offset of (kv head, block, band position) behind the q-heads' h*N*128 elements
-__device__ __forceinline__ size_t kv_band_offset(int h, int N, int kvh, int blk, int pz) {
+// element offset of (kv head, block, band position) behind the q-heads' h*N*bs elements; one tile
+// of 16 blocks holds 16*bs elements
+__device__ __forceinline__ size_t kv_band_offset(int h, int N, int bs, int kvh, int blk, int pz) {
   const int n_tiles = (N + 15) >> 4;
   const int tile = blk >> 4, r = blk & 15, ks = pz >> 5, piece = (pz >> 3) & 3, j = pz & 7;
-  return (size_t)h * N * kHeadDim + ((size_t)kvh * n_tiles + tile) * kBandTileElems + ks * 512 +
+  return (size_t)h * N * bs + ((size_t)kvh * n_tiles + tile) * 16 * bs + ks * 512 +
          (piece * 16 + r) * 8 + j;
 }
 
 // =====================================================================================
 // Mean pooling (Eq. "mean-pooling") and band energies (Sec. 3.4, RMS definition).
-// One workgroup per (block, head); 256 threads read B x 128 bf16 = B*256 contiguous bytes
-// as 16-byte pieces: thread t owns dims 8*(t%16)..+7 of rows t/16, t/16+16, ...
+// One workgroup per (block, head); 256 threads read B x d bf16 = 2*B*d contiguous bytes
+// as 16-byte pieces: with d/8 pieces per row, thread t owns dims 8*(t % (d/8))..+7 of rows
+// t / (d/8), that + 2048/d, ...
 // Outputs per (head, block): the two band vectors, each as three bf16 terms hi + mid + lo
 // (together they carry the full fp32 mantissa), an optional fp32 copy of the pooled vector,
 // and the three sums of squares (all dims, high band, low band) in
@@ -68,8 +72,8 @@ struct RopeArgs {
 
 // theta'_j of feature pair j: plain RoPE, or (1 - gamma_j) theta_j / s + gamma_j theta_j with
 // gamma_j = clamp((r_j - alpha) / (beta - alpha), 0, 1), r_j = L theta_j / (2 pi).
-__device__ __forceinline__ double rope_theta(const RopeArgs& r, int j) {
-  const double theta = exp(-(2.0 * j / kHeadDim) * r.ln_base);
+__device__ __forceinline__ double rope_theta(const RopeArgs& r, int j, int d) {
+  const double theta = exp(-(2.0 * j / d) * r.ln_base);
   if (!(r.yarn_scale > 0.0)) return theta;
   const double rj = r.yarn_native_len * theta * 0.15915494309189535;          // / (2 pi)
   double gamma = (rj - r.yarn_alpha) / (r.yarn_beta - r.yarn_alpha);
@@ -85,48 +89,52 @@ __device__ __forceinline__ void rope_cos_sin(double angle, float* c, float* s) {
   sincosf((float)a, s, c);
 }
 
-template <int BLK, bool kRope>
+template <int BLK, bool kRope, int D>
 __global__ __launch_bounds__(256) void pool_energy_kernel(
-    const uint16_t* q, const uint16_t* k, int h, int L, int N,
+    const uint16_t* q, const uint16_t* k, int h, int L, int N, size_t q_head_stride, size_t kv_head_stride,
     BandMap map, BandVectors bv, float* __restrict__ energy,
     float* __restrict__ pooled_q_f32, float* __restrict__ pooled_k_f32,
     RopeArgs rope, uint16_t* q_out, uint16_t* k_out) {      // q_out / k_out may alias q / k
-  __shared__ float part[16][kHeadDim + 4];
-  __shared__ float esum[2][4];
+  constexpr int CPR = D / 8;                 // 16-byte pieces per token row
+  constexpr int RG = 256 / CPR;              // row groups: rows rg, rg + RG, ... belong to one thread
+  constexpr int ROWS = BLK / RG;             // rows per thread
+  constexpr int BS = D > 128 ? D : 128;      // band_stride(D)
+  __shared__ float part[RG][D + 4];
+  __shared__ float esum[4][4];
   const int blk = blockIdx.x, head = blockIdx.y, t = threadIdx.x;
-  const size_t head_off = (head < h) ? (size_t)head * L * kHeadDim : (size_t)(head - h) * L * kHeadDim;
-  const uint16_t* src = ((head < h) ? q : k) + head_off + (size_t)blk * BLK * kHeadDim;
-  const int c = t & 15, rg = t >> 4;
+  const size_t head_off = (head < h) ? (size_t)head * q_head_stride : (size_t)(head - h) * kv_head_stride;
+  const uint16_t* src = ((head < h) ? q : k) + head_off + (size_t)blk * BLK * D;
+  const int c = t % CPR, rg = t / CPR;
 
   const int cnt = min(BLK, L - blk * BLK);          // tokens in this block (ragged last block)
-  uint4 v[BLK / 16];
+  uint4 v[ROWS];
 #pragma unroll
-  for (int it = 0; it < BLK / 16; ++it) {
-    const int row = rg + it * 16;
+  for (int it = 0; it < ROWS; ++it) {
+    const int row = rg + it * RG;
     // streaming read (non-temporal): every token row is read once per call
     if (row < cnt) {
-      const u32x4 x = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + (size_t)row * kHeadDim + c * 8));
+      const u32x4 x = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + (size_t)row * D + c * 8));
       v[it] = make_uint4(x[0], x[1], x[2], x[3]);
     } else {
       v[it] = make_uint4(0u, 0u, 0u, 0u);
     }
   }
   if (kRope) {
-    // This thread holds feature pairs 4c .. 4c+3 of tokens rg, rg + 16, ...: one accurate
-    // cos / sin per pair for its first token, then a rotation by 16 theta per further token (the
-    // fp32 recurrence runs over at most BLK/16 - 1 = 7 steps).
-    uint16_t* dst = ((head < h) ? q_out : k_out) + head_off + (size_t)blk * BLK * kHeadDim;
+    // This thread holds feature pairs 4c .. 4c+3 of tokens rg, rg + RG, ...: one accurate
+    // cos / sin per pair for its first token, then a rotation by RG theta per further token (the
+    // fp32 recurrence runs over ROWS - 1 <= 15 steps).
+    uint16_t* dst = ((head < h) ? q_out : k_out) + head_off + (size_t)blk * BLK * D;
     const int pos0 = rope.position_offset + blk * BLK + rg;
     float cs[4], sn[4], dc[4], ds[4];
 #pragma unroll
     for (int pj = 0; pj < 4; ++pj) {
-      const double theta = rope_theta(rope, 4 * c + pj);
+      const double theta = rope_theta(rope, 4 * c + pj, D);
       rope_cos_sin((double)pos0 * theta, &cs[pj], &sn[pj]);
-      rope_cos_sin(16.0 * theta, &dc[pj], &ds[pj]);
+      rope_cos_sin((double)RG * theta, &dc[pj], &ds[pj]);
     }
 #pragma unroll
-    for (int it = 0; it < BLK / 16; ++it) {
-      const int row = rg + it * 16;
+    for (int it = 0; it < ROWS; ++it) {
+      const int row = rg + it * RG;
       uint32_t w[4] = {v[it].x, v[it].y, v[it].z, v[it].w};
 #pragma unroll
       for (int pj = 0; pj < 4; ++pj) {
@@ -139,12 +147,12 @@ __global__ __launch_bounds__(256) void pool_energy_kernel(
         cs[pj] = cn;
       }
       v[it] = make_uint4(w[0], w[1], w[2], w[3]);
-      if (row < cnt) *reinterpret_cast<uint4*>(dst + (size_t)row * kHeadDim + c * 8) = v[it];
+      if (row < cnt) *reinterpret_cast<uint4*>(dst + (size_t)row * D + c * 8) = v[it];
     }
   }
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-  for (int it = 0; it < BLK / 16; ++it) {
+  for (int it = 0; it < ROWS; ++it) {
     acc[0] += __uint_as_float(v[it].x << 16);
     acc[1] += __uint_as_float(v[it].x & 0xFFFF0000u);
     acc[2] += __uint_as_float(v[it].y << 16);
@@ -158,10 +166,10 @@ __global__ __launch_bounds__(256) void pool_energy_kernel(
   *reinterpret_cast<float4*>(&part[rg][c * 8 + 4]) = make_float4(acc[4], acc[5], acc[6], acc[7]);
   __syncthreads();
 
-  if (t < kHeadDim) {
+  if (t < D) {
     float s = 0.f;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) s += part[r][t];
+    for (int r = 0; r < RG; ++r) s += part[r][t];
     const float mean = s / (float)cnt;
     // mean = hi + mid + lo exactly up to 2^-26 relative (three bf16 terms of 8 bits each)
     const uint32_t hi = float_to_bf16_bits(mean);
@@ -169,9 +177,9 @@ __global__ __launch_bounds__(256) void pool_energy_kernel(
     const uint32_t mid = float_to_bf16_bits(rem1);
     const float rem2 = rem1 - bf16_bits_to_float(mid);
     const uint32_t lo = float_to_bf16_bits(rem2);
-    const size_t o = ((size_t)head * N + blk) * kHeadDim + t;
+    const size_t o = ((size_t)head * N + blk) * D + t;
     if (head < h) {
-      const size_t vec = ((size_t)head * N + blk) * kHeadDim;
+      const size_t vec = ((size_t)head * N + blk) * BS;
 #pragma unroll
       for (int z = 0; z < 2; ++z) {
         const int pz = map.pos[z][t];
@@ -193,7 +201,7 @@ __global__ __launch_bounds__(256) void pool_energy_kernel(
       for (int z = 0; z < 2; ++z) {
         const int pz = map.pos[z][t];
         if (pz >= 0) {
-          const size_t e = kv_band_offset(h, N, head - h, blk, pz);
+          const size_t e = kv_band_offset(h, N, BS, head - h, blk, pz);
           bv.v[z][0][e] = (uint16_t)hi;
           bv.v[z][1][e] = (uint16_t)mid;
           bv.v[z][2][e] = (uint16_t)lo;
@@ -201,7 +209,7 @@ __global__ __launch_bounds__(256) void pool_energy_kernel(
         for (int b = blk; b < blk_end; ++b) {
           // zero padding of the last k-step (dims dz .. dpad-1), and whole padding blocks
           if (t < map.dpad[z] && (b > blk || t >= map.dz[z])) {
-            const size_t e = kv_band_offset(h, N, head - h, b, t);
+            const size_t e = kv_band_offset(h, N, BS, head - h, b, t);
             bv.v[z][0][e] = 0;
             bv.v[z][1][e] = 0;
             bv.v[z][2][e] = 0;
@@ -212,7 +220,7 @@ __global__ __launch_bounds__(256) void pool_energy_kernel(
     if (head < h) {
       if (pooled_q_f32) pooled_q_f32[o] = mean;
     } else if (pooled_k_f32) {
-      pooled_k_f32[((size_t)(head - h) * N + blk) * kHeadDim + t] = mean;
+      pooled_k_f32[((size_t)(head - h) * N + blk) * D + t] = mean;
     }
     const float sq = mean * mean;
     const float e_full = wave_sum(sq);
@@ -225,7 +233,12 @@ __global__ __launch_bounds__(256) void pool_energy_kernel(
     }
   }
   __syncthreads();
-  if (t < 3) energy[((size_t)head * N + blk) * 4 + t] = esum[0][t] + esum[1][t];
+  if (t < 3) {
+    float e = 0.f;
+#pragma unroll
+    for (int wv = 0; wv < D / 64; ++wv) e += esum[wv][t];      // fixed order: deterministic
+    energy[((size_t)head * N + blk) * 4 + t] = e;
+  }
 }
 
 // =====================================================================================
@@ -235,7 +248,7 @@ __global__ __launch_bounds__(256) void pool_energy_kernel(
 // inv_scale[hq*2 + z] = 1/scale_z, or 0 when the band is disabled or has no energy.
 // =====================================================================================
 __global__ __launch_bounds__(64) void scale_kernel(const float* __restrict__ energy, int h, int h_kv,
-                                                   int N, int d_high, int d_low, int calibrate,
+                                                   int N, int head_dim, int d_high, int d_low, int calibrate,
                                                    float* __restrict__ inv_scale,
                                                    float* __restrict__ scales_out) {
   const int hq = blockIdx.x, lane = threadIdx.x;
@@ -254,7 +267,7 @@ __global__ __launch_bounds__(64) void scale_kernel(const float* __restrict__ ene
     ek[z] = wave_sum(ek[z]);
   }
   if (lane == 0) {
-    const double d = kHeadDim;
+    const double d = head_dim;
     const double rq = sqrt(eq[0] / (N * d)), rk = sqrt(ek[0] / (N * d));
     for (int z = 0; z < 2; ++z) {
       const int dz = z == 0 ? d_high : d_low;
@@ -476,7 +489,7 @@ constexpr int kSelForceSink = 4;       // block 0 of every row is switched on af
 template <int MAXCH, bool DUMP>
 __global__ __launch_bounds__(256) void select_kernel(
     BandVectors bv, const float* __restrict__ inv_scale, int h, int h_kv,
-    int N, int dpad_high, int dpad_low, float top_p, int select_flags,
+    int N, int bs, int dpad_high, int dpad_low, float top_p, int select_flags,
     uint64_t* __restrict__ mask_bits, int32_t* __restrict__ row_ptr,
     float* __restrict__ logits_high, float* __restrict__ logits_low) {
   extern __shared__ float lds_logits[];
@@ -509,13 +522,19 @@ __global__ __launch_bounds__(256) void select_kernel(
     const uint16_t* __restrict__ pooled_lo = bv.v[z][2];
 
     // ---------------- phase A: logits of the strip into LDS ----------------
-    {
+    // Four k-steps (128 band dims) per pass; a wider band (head dim 256) takes a second pass that
+    // adds to the logits of the first.  A wave meets the same tiles, and a lane the same LDS
+    // words, in every pass, so the passes need no barrier between them.
+#pragma unroll 1
+    for (int k0 = 0; k0 < ksteps; k0 += 4) {
+      const int kn = min(4, ksteps - k0);
+      const bool first = k0 == 0, last = k0 + 4 >= ksteps;
       const int arow = min(u0 + (lane & 15), N - 1);
-      const size_t aoff = ((size_t)hq * N + arow) * kHeadDim + (lane >> 4) * 8;
+      const size_t aoff = ((size_t)hq * N + arow) * bs + k0 * 32 + (lane >> 4) * 8;
       bf16x8 ah[4], am[4], al[4];
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks) {
-        if (ks < ksteps) {
+        if (ks < kn) {
           ah[ks] = *reinterpret_cast<const bf16x8*>(pooled_hi + aoff + ks * 32);
           am[ks] = *reinterpret_cast<const bf16x8*>(pooled_mid + aoff + ks * 32);
           al[ks] = *reinterpret_cast<const bf16x8*>(pooled_lo + aoff + ks * 32);
@@ -524,10 +543,10 @@ __global__ __launch_bounds__(256) void select_kernel(
       // B fragments of the next tile are fetched while the MFMAs of the current one run
       bf16x8 bh[4], bm[4], bl[4];
       auto load_b = [&](int ct) {
-        const size_t boff = kv_band_offset(h, N, kvh - h, ct * 16, 0) + lane * 8;
+        const size_t boff = kv_band_offset(h, N, bs, kvh - h, ct * 16, 0) + k0 * 512 + lane * 8;
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
-          if (ks < ksteps) {
+          if (ks < kn) {
             bh[ks] = *reinterpret_cast<const bf16x8*>(pooled_hi + boff + ks * 512);
             bm[ks] = *reinterpret_cast<const bf16x8*>(pooled_mid + boff + ks * 512);
             bl[ks] = *reinterpret_cast<const bf16x8*>(pooled_lo + boff + ks * 512);
@@ -547,7 +566,7 @@ __global__ __launch_bounds__(256) void select_kernel(
         if (ct + 4 < ntiles) load_b(ct + 4);
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
-          if (ks < ksteps) {
+          if (ks < kn) {
             // all cross terms down to 2^-24 relative, smallest first
             acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al[ks], ch[ks], acc, 0, 0, 0);
             acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah[ks], cl[ks], acc, 0, 0, 0);
@@ -561,9 +580,10 @@ __global__ __launch_bounds__(256) void select_kernel(
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
           const int row = (lane >> 4) * 4 + r;
-          const float lg = acc[r] * inv;
+          float lg = acc[r] * inv;
+          if (!first) lg += lds_logits[row * ld + col];
           lds_logits[row * ld + col] = lg;
-          if (DUMP) {
+          if (DUMP && last) {
             const int u = u0 + row;
             float* dst = z == 0 ? logits_high : logits_low;
             if (dst != nullptr && u < N && col < N && (col <= u || !causal))
@@ -730,7 +750,7 @@ static int make_band_map(const prism_params* p, const prism_bands* bands, BandMa
   if (!(p->top_p > 0.0f) || !(p->top_p <= 1.0f)) return PRISM_ERR_INVALID_ARG;   // also rejects NaN
   const prism_band* zb[2] = {&bands->high, &bands->low};
   for (int z = 0; z < 2; ++z) {
-    for (int c = 0; c < kHeadDim; ++c) map->pos[z][c] = -1;
+    for (int c = 0; c < kMaxHeadDim; ++c) map->pos[z][c] = -1;
     if (zb[z]->n_segments < 0 || zb[z]->n_segments > PRISM_MAX_SEGMENTS) return PRISM_ERR_INVALID_ARG;
     int n = 0;
     for (int i = 0; i < zb[z]->n_segments; ++i) {
@@ -738,7 +758,7 @@ static int make_band_map(const prism_params* p, const prism_bands* bands, BandMa
       if (start < 0 || width <= 0 || start + width > p->head_dim) return PRISM_ERR_INVALID_ARG;
       for (int c = (int)start; c < (int)(start + width); ++c) {
         if (map->pos[z][c] >= 0) return PRISM_ERR_INVALID_ARG;          // slices of one band overlap
-        map->pos[z][c] = (int8_t)n++;
+        map->pos[z][c] = (int16_t)n++;
       }
     }
     map->dz[z] = n;
@@ -761,7 +781,8 @@ static EstimateWs estimate_ws(const prism_params* p) {
     for (int term = 0; term < 3; ++term) {
       w.band[z][term] = off;
       // q-heads: N rows each; kv heads: whole tiles of 16 blocks
-      off = align_up(off + ((size_t)p->n_q_heads * N + (size_t)p->n_kv_heads * ((N + 15) / 16 * 16)) * kHeadDim * 2, 256);
+      off = align_up(off + ((size_t)p->n_q_heads * N + (size_t)p->n_kv_heads * ((N + 15) / 16 * 16)) *
+                               band_stride(p->head_dim) * 2, 256);
     }
   w.energy = off;    off = align_up(off + heads * N * 4 * sizeof(float), 256);
   w.inv_scale = off; off = align_up(off + (size_t)p->n_q_heads * 2 * sizeof(float), 256);
@@ -776,37 +797,48 @@ static BandVectors band_vectors(char* ws, const EstimateWs& L) {
   return bv;
 }
 
-static int run_pool_and_scale(const prism_params* p, const BandMap& map, const void* q, const void* k,
-                              char* ws, const EstimateWs& L, float* pooled_q, float* pooled_k,
+template <int BLK, bool kRope, int D>
+static void launch_pool(const prism_params* p, const HeadStrides& hs, const BandMap& map, const BandVectors& bv,
+                        const uint16_t* q, const uint16_t* k, float* energy, float* pooled_q, float* pooled_k,
+                        const RopeArgs& rope, uint16_t* q_out, uint16_t* k_out, hipStream_t st) {
+  const int N = n_blocks(p);
+  hipLaunchKernelGGL((pool_energy_kernel<BLK, kRope, D>), dim3(N, p->n_q_heads + p->n_kv_heads), dim3(256), 0,
+                     st, q, k, p->n_q_heads, p->seq_len, N, hs.q, hs.kv, map, bv, energy, pooled_q, pooled_k,
+                     rope, q_out, k_out);
+}
+
+static int run_pool_and_scale(const prism_params* p, const HeadStrides& hs, const BandMap& map, const void* q,
+                              const void* k, char* ws, const EstimateWs& L, float* pooled_q, float* pooled_k,
                               float* scales, hipStream_t st, const RopeArgs* rope = nullptr,
                               void* q_out = nullptr, void* k_out = nullptr) {
   const int N = n_blocks(p);
-  const dim3 grid(N, p->n_q_heads + p->n_kv_heads);
   const BandVectors bv = band_vectors(ws, L);
   float* energy = reinterpret_cast<float*>(ws + L.energy);
   float* inv = reinterpret_cast<float*>(ws + L.inv_scale);
   const uint16_t* qp = (const uint16_t*)q;
   const uint16_t* kp = (const uint16_t*)k;
-  const RopeArgs no_rope = {};
-  if (rope == nullptr) {
-    if (p->block == 128)
-      hipLaunchKernelGGL((pool_energy_kernel<128, false>), grid, dim3(256), 0, st, qp, kp, p->n_q_heads,
-                         p->seq_len, N, map, bv, energy, pooled_q, pooled_k, no_rope, nullptr, nullptr);
-    else
-      hipLaunchKernelGGL((pool_energy_kernel<64, false>), grid, dim3(256), 0, st, qp, kp, p->n_q_heads,
-                         p->seq_len, N, map, bv, energy, pooled_q, pooled_k, no_rope, nullptr, nullptr);
+  const RopeArgs ra = rope != nullptr ? *rope : RopeArgs{};
+  uint16_t* qo = (uint16_t*)q_out;
+  uint16_t* ko = (uint16_t*)k_out;
+#define PRISM_POOL(BLK, D)                                                                              \
+  do {                                                                                                  \
+    if (rope == nullptr)                                                                                \
+      launch_pool<BLK, false, D>(p, hs, map, bv, qp, kp, energy, pooled_q, pooled_k, ra, nullptr, nullptr, st); \
+    else                                                                                                \
+      launch_pool<BLK, true, D>(p, hs, map, bv, qp, kp, energy, pooled_q, pooled_k, ra, qo, ko, st);    \
+  } while (0)
+  if (p->block == 128) {
+    if (p->head_dim == 64) PRISM_POOL(128, 64);
+    else if (p->head_dim == 128) PRISM_POOL(128, 128);
+    else PRISM_POOL(128, 256);
   } else {
-    if (p->block == 128)
-      hipLaunchKernelGGL((pool_energy_kernel<128, true>), grid, dim3(256), 0, st, qp, kp, p->n_q_heads,
-                         p->seq_len, N, map, bv, energy, pooled_q, pooled_k, *rope, (uint16_t*)q_out,
-                         (uint16_t*)k_out);
-    else
-      hipLaunchKernelGGL((pool_energy_kernel<64, true>), grid, dim3(256), 0, st, qp, kp, p->n_q_heads,
-                         p->seq_len, N, map, bv, energy, pooled_q, pooled_k, *rope, (uint16_t*)q_out,
-                         (uint16_t*)k_out);
+    if (p->head_dim == 64) PRISM_POOL(64, 64);
+    else if (p->head_dim == 128) PRISM_POOL(64, 128);
+    else PRISM_POOL(64, 256);
   }
+#undef PRISM_POOL
   hipLaunchKernelGGL(scale_kernel, dim3(p->n_q_heads), dim3(64), 0, st, energy, p->n_q_heads,
-                     p->n_kv_heads, N, map.dz[0], map.dz[1],
+                     p->n_kv_heads, N, p->head_dim, map.dz[0], map.dz[1],
                      (p->flags & PRISM_FLAG_NO_CALIBRATION) ? 0 : 1, inv, scales);
   return launch_status();
 }
@@ -829,7 +861,7 @@ static int launch_select(const prism_params* p, const BandMap& map, char* ws, co
   if (p->flags & PRISM_FLAG_FORCE_SINK) select_flags |= kSelForceSink;
   hipLaunchKernelGGL(kern, dim3(strips, p->n_q_heads), dim3(256), lds, st, band_vectors(ws, L),
                      reinterpret_cast<const float*>(ws + L.inv_scale), p->n_q_heads, p->n_kv_heads, N,
-                     map.dpad[0], map.dpad[1], p->top_p, select_flags, mask_bits, row_ptr, lh, ll);
+                     band_stride(p->head_dim), map.dpad[0], map.dpad[1], p->top_p, select_flags, mask_bits, row_ptr, lh, ll);
   return launch_status();
 }
 
@@ -880,6 +912,24 @@ extern "C" int prism_estimate_workspace_bytes(const prism_params* params, size_t
   return PRISM_OK;
 }
 
+// The whole estimate of one sequence (arguments already validated): pooling (+ RoPE when `rope`
+// is given), calibration, selection, compaction.
+static int estimate_core(const prism_params* params, const HeadStrides& hs, const BandMap& map,
+                         const void* q, const void* k, uint64_t* mask_bits, int32_t* row_ptr,
+                         int32_t* col_idx, int64_t col_capacity, int32_t* info, char* ws,
+                         hipStream_t st, const RopeArgs* rope = nullptr, void* q_out = nullptr,
+                         void* k_out = nullptr) {
+  const EstimateWs L = estimate_ws(params);
+  int rc = run_pool_and_scale(params, hs, map, q, k, ws, L, nullptr, nullptr, nullptr, st, rope, q_out, k_out);
+  if (rc != PRISM_OK) return rc;
+  const int N = n_blocks(params);
+  rc = (N <= 1024)
+           ? launch_select<16, false>(params, map, ws, L, mask_bits, row_ptr, nullptr, nullptr, st)
+           : launch_select<32, false>(params, map, ws, L, mask_bits, row_ptr, nullptr, nullptr, st);
+  if (rc != PRISM_OK) return rc;
+  return run_compaction(params, mask_bits, row_ptr, col_idx, col_capacity, info, false, st);
+}
+
 extern "C" int prism_estimate_bands(const prism_params* params, const prism_bands* bands,
                                     const void* q_bf16, const void* k_bf16, uint64_t* mask_bits,
                                     int32_t* row_ptr, int32_t* col_idx, int64_t col_capacity,
@@ -892,19 +942,101 @@ extern "C" int prism_estimate_bands(const prism_params* params, const prism_band
   if (rc != PRISM_OK) return rc;
   if (!q_bf16 || !k_bf16 || !mask_bits || !row_ptr || !col_idx || !info || col_capacity < 0)
     return PRISM_ERR_INVALID_ARG;
-  const EstimateWs L = estimate_ws(params);
-  rc = check_ws(workspace, workspace_bytes, L.total);
+  rc = check_ws(workspace, workspace_bytes, estimate_ws(params).total);
   if (rc != PRISM_OK) return rc;
-  hipStream_t st = static_cast<hipStream_t>(stream);
-  char* ws = static_cast<char*>(workspace);
-  rc = run_pool_and_scale(params, map, q_bf16, k_bf16, ws, L, nullptr, nullptr, nullptr, st);
+  return estimate_core(params, contiguous_heads(params), map, q_bf16, k_bf16, mask_bits, row_ptr, col_idx,
+                       col_capacity, info, static_cast<char*>(workspace), static_cast<hipStream_t>(stream));
+}
+
+// ---- packed variable-length batches ---------------------------------------------------
+// parameters of sequence s of the batch
+static prism_params sequence_params(const prism_params* params, const int32_t* cu_seqlens, int s) {
+  prism_params ps = *params;
+  ps.seq_len = cu_seqlens[s + 1] - cu_seqlens[s];
+  return ps;
+}
+
+extern "C" int prism_varlen_layout(const prism_params* params, const int32_t* cu_seqlens, int n_seqs,
+                                   int64_t* mask_offsets, int64_t* row_offsets, int64_t* col_offsets) {
+  // a batch may hold more tokens than one sequence may: only the per-sequence limits apply
+  prism_params one = {};
+  if (params != nullptr) {
+    one = *params;
+    one.seq_len = 1;
+  }
+  int rc = check_params(params != nullptr ? &one : nullptr);
   if (rc != PRISM_OK) return rc;
-  const int N = n_blocks(params);
-  rc = (N <= 1024)
-           ? launch_select<16, false>(params, map, ws, L, mask_bits, row_ptr, nullptr, nullptr, st)
-           : launch_select<32, false>(params, map, ws, L, mask_bits, row_ptr, nullptr, nullptr, st);
+  if (cu_seqlens == nullptr || n_seqs <= 0 || cu_seqlens[0] != 0 || cu_seqlens[n_seqs] != params->seq_len)
+    return PRISM_ERR_INVALID_ARG;
+  int64_t mo = 0, ro = 0, co = 0;
+  for (int s = 0; s < n_seqs; ++s) {
+    if (cu_seqlens[s + 1] <= cu_seqlens[s]) return PRISM_ERR_INVALID_ARG;
+    const prism_params ps = sequence_params(params, cu_seqlens, s);
+    rc = check_params(&ps);
+    if (rc != PRISM_OK) return rc;
+    const int64_t N = n_blocks(&ps), h = ps.n_q_heads;
+    if (mask_offsets) mask_offsets[s] = mo;
+    if (row_offsets) row_offsets[s] = ro;
+    if (col_offsets) col_offsets[s] = co;
+    mo += h * N * ((N + 63) / 64);
+    ro += h * N + 1;
+    co += (ps.flags & PRISM_FLAG_BIDIRECTIONAL) ? h * N * N : h * N * (N + 1) / 2;
+  }
+  if (mask_offsets) mask_offsets[n_seqs] = mo;
+  if (row_offsets) row_offsets[n_seqs] = ro;
+  if (col_offsets) col_offsets[n_seqs] = co;
+  return PRISM_OK;
+}
+
+extern "C" int prism_estimate_varlen_workspace_bytes(const prism_params* params, const int32_t* cu_seqlens,
+                                                     int n_seqs, size_t* bytes) {
+  if (bytes == nullptr) return PRISM_ERR_INVALID_ARG;
+  int rc = prism_varlen_layout(params, cu_seqlens, n_seqs, nullptr, nullptr, nullptr);
   if (rc != PRISM_OK) return rc;
-  return run_compaction(params, mask_bits, row_ptr, col_idx, col_capacity, info, false, st);
+  size_t need = 0;
+  for (int s = 0; s < n_seqs; ++s) {
+    const prism_params ps = sequence_params(params, cu_seqlens, s);
+    const size_t b = estimate_ws(&ps).total;
+    need = b > need ? b : need;
+  }
+  *bytes = need;
+  return PRISM_OK;
+}
+
+extern "C" int prism_estimate_varlen(const prism_params* params, const int32_t* cu_seqlens, int n_seqs,
+                                     const void* q_bf16, const void* k_bf16, uint64_t* mask_bits,
+                                     int32_t* row_ptr, int32_t* col_idx, int32_t* info, void* workspace,
+                                     size_t workspace_bytes, void* stream) {
+  size_t need = 0;
+  int rc = prism_estimate_varlen_workspace_bytes(params, cu_seqlens, n_seqs, &need);
+  if (rc != PRISM_OK) return rc;
+  rc = check_bands(params);
+  if (rc != PRISM_OK) return rc;
+  if (!q_bf16 || !k_bf16 || !mask_bits || !row_ptr || !col_idx || !info) return PRISM_ERR_INVALID_ARG;
+  rc = check_ws(workspace, workspace_bytes, need);
+  if (rc != PRISM_OK) return rc;
+  const prism_bands bands = default_bands(params);
+  BandMap map;
+  rc = make_band_map(params, &bands, &map);
+  if (rc != PRISM_OK) return rc;
+  const size_t d = params->head_dim, T = params->seq_len;
+  const HeadStrides hs{T * d, T * d, T};
+  int64_t mo = 0, ro = 0, co = 0;
+  for (int s = 0; s < n_seqs; ++s) {
+    const prism_params ps = sequence_params(params, cu_seqlens, s);
+    const int64_t N = n_blocks(&ps), h = ps.n_q_heads;
+    const int64_t cap = (ps.flags & PRISM_FLAG_BIDIRECTIONAL) ? h * N * N : h * N * (N + 1) / 2;
+    const size_t tok = (size_t)cu_seqlens[s] * d;
+    // the sequences share the workspace: they run one after the other on the stream
+    rc = estimate_core(&ps, hs, map, (const uint16_t*)q_bf16 + tok, (const uint16_t*)k_bf16 + tok, mask_bits + mo,
+                       row_ptr + ro, col_idx + co, cap, info + 4 * s, static_cast<char*>(workspace),
+                       static_cast<hipStream_t>(stream));
+    if (rc != PRISM_OK) return rc;
+    mo += h * N * ((N + 63) / 64);
+    ro += h * N + 1;
+    co += cap;
+  }
+  return PRISM_OK;
 }
 
 extern "C" int prism_estimate(const prism_params* params, const void* q_bf16, const void* k_bf16,
@@ -1004,20 +1136,11 @@ extern "C" int prism_rope_estimate(const prism_params* params, const prism_rope*
     ra.yarn_beta = rope->yarn_beta;
     ra.yarn_native_len = (double)rope->yarn_native_len;
   }
-  const EstimateWs L = estimate_ws(params);
-  rc = check_ws(workspace, workspace_bytes, L.total);
+  rc = check_ws(workspace, workspace_bytes, estimate_ws(params).total);
   if (rc != PRISM_OK) return rc;
-  hipStream_t st = static_cast<hipStream_t>(stream);
-  char* ws = static_cast<char*>(workspace);
-  rc = run_pool_and_scale(params, map, q_in_bf16, k_in_bf16, ws, L, nullptr, nullptr, nullptr, st, &ra,
-                          q_out_bf16, k_out_bf16);
-  if (rc != PRISM_OK) return rc;
-  const int N = n_blocks(params);
-  rc = (N <= 1024)
-           ? launch_select<16, false>(params, map, ws, L, mask_bits, row_ptr, nullptr, nullptr, st)
-           : launch_select<32, false>(params, map, ws, L, mask_bits, row_ptr, nullptr, nullptr, st);
-  if (rc != PRISM_OK) return rc;
-  return run_compaction(params, mask_bits, row_ptr, col_idx, col_capacity, info, false, st);
+  return estimate_core(params, contiguous_heads(params), map, q_in_bf16, k_in_bf16, mask_bits, row_ptr, col_idx,
+                       col_capacity, info, static_cast<char*>(workspace), static_cast<hipStream_t>(stream),
+                       &ra, q_out_bf16, k_out_bf16);
 }
 
 extern "C" int prism_block_scores_bands(const prism_params* params, const prism_bands* bands,
@@ -1036,7 +1159,8 @@ extern "C" int prism_block_scores_bands(const prism_params* params, const prism_
   if (rc != PRISM_OK) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
   char* ws = static_cast<char*>(workspace);
-  rc = run_pool_and_scale(params, map, q_bf16, k_bf16, ws, L, pooled_q, pooled_k, scales, st);
+  rc = run_pool_and_scale(params, contiguous_heads(params), map, q_bf16, k_bf16, ws, L, pooled_q, pooled_k,
+                          scales, st);
   if (rc != PRISM_OK) return rc;
   if (logits_high == nullptr && logits_low == nullptr) return PRISM_OK;
   return launch_select<16, true>(params, map, ws, L, nullptr, nullptr, logits_high, logits_low, st);

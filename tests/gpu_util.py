@@ -26,7 +26,7 @@ def pack_mask(mask: np.ndarray) -> np.ndarray:
 
 def params_for(w, **over):
     kw = dict(n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, seq_len=w.seq_len, block=w.block,
-              d_high=w.d_high, d_low=w.d_low, top_p=w.top_p)
+              d_high=w.d_high, d_low=w.d_low, top_p=w.top_p, head_dim=w.head_dim)
     kw.update(over)
     return pb.make_params(**kw)
 
@@ -49,9 +49,9 @@ def gpu_estimate(params, q_dev, k_dev, col_capacity=None, bands=None):
 
 
 def gpu_block_scores(params, q_dev, k_dev, want_logits=True, bands=None):
-    h, hk, N = params.n_q_heads, params.n_kv_heads, params.n_blocks
-    pq = torch.empty((h, N, 128), dtype=torch.float32, device="cuda")
-    pk = torch.empty((hk, N, 128), dtype=torch.float32, device="cuda")
+    h, hk, N, d = params.n_q_heads, params.n_kv_heads, params.n_blocks, params.head_dim
+    pq = torch.empty((h, N, d), dtype=torch.float32, device="cuda")
+    pk = torch.empty((hk, N, d), dtype=torch.float32, device="cuda")
     sc = torch.empty((h, 2), dtype=torch.float32, device="cuda")
     lh = torch.full((h, N, N), float("nan"), dtype=torch.float32, device="cuda") if want_logits else None
     ll = torch.full((h, N, N), float("nan"), dtype=torch.float32, device="cuda") if want_logits else None
@@ -70,7 +70,7 @@ def gpu_block_scores(params, q_dev, k_dev, want_logits=True, bands=None):
 
 def gpu_sparse_attn(params, q_dev, k_dev, v_dev, row_ptr_dev, col_idx_dev, col_count, want_lse=True):
     h, L = params.n_q_heads, params.seq_len
-    out = torch.full((h, L, 128), float("nan"), dtype=torch.bfloat16, device="cuda")
+    out = torch.full((h, L, params.head_dim), float("nan"), dtype=torch.bfloat16, device="cuda")
     lse = torch.full((h, L), float("nan"), dtype=torch.float32, device="cuda") if want_lse else None
     ws = pb.alloc_workspace(pb.prism_sparse_attn_workspace_bytes(params))
     pb.prism_sparse_attn(params, q_dev, k_dev, v_dev, row_ptr_dev, col_idx_dev, col_count, out, lse, ws)

@@ -54,7 +54,8 @@ def test_workspace_queries(lib):
 @pytest.mark.parametrize("kw,status", [
     (dict(n_q_heads=6, n_kv_heads=4), -1),          # h % h_kv
     (dict(n_q_heads=0), -1),
-    (dict(head_dim=64), -2),
+    (dict(head_dim=96), -2),
+    (dict(head_dim=512), -2),
     (dict(block=32), -2),
     (dict(seq_len=0), -1),
     (dict(seq_len=128 * 4096), -2),                  # N > 2048
@@ -144,6 +145,35 @@ def test_bad_rope_descriptors_are_rejected_before_launch(lib, kw):
     assert call(ctypes.byref(rope)) == -1
     assert call(None) == -1                                           # no descriptor at all
     assert call(ctypes.byref(pb.make_rope(1e4)), None) == -1          # null input with a good descriptor
+
+
+def test_head_dims_64_128_256_are_accepted(lib):
+    for d in (64, 128, 256):
+        p = pb.make_params(4, 2, 4096, 128, d_high=d // 2, d_low=d // 2, head_dim=d)
+        assert pb.prism_estimate_workspace_bytes(p) > 0
+        assert pb.prism_sparse_attn_workspace_bytes(p) >= 2 * 4096 * d * 2
+
+
+def test_varlen_layout_and_malformed_offsets(lib):
+    params = pb.make_params(2, 1, 1000, 128)
+    mo, ro, co = pb.prism_varlen_layout(params, [0, 300, 1000])
+    # N = 3 and 6 blocks: words 2*3*1 and 2*6*1, rows 2*3+1 and 2*6+1, pairs 2*6 and 2*21
+    assert mo == [0, 6, 18] and ro == [0, 7, 20] and co == [0, 12, 54]
+    for cu in ([0, 500, 400, 1000], [1, 1000], [0, 1001], [0, 500, 500, 1000], [0, 999]):
+        with pytest.raises(pb.PrismError):
+            pb.prism_varlen_layout(params, cu)
+    # a sequence beyond the per-sequence block limit
+    big = pb.make_params(1, 1, 64 * 2049 + 64, 64)
+    with pytest.raises(pb.PrismError):
+        pb.prism_varlen_layout(big, [0, 64 * 2049, 64 * 2049 + 64])
+    # a batch longer than one sequence may be is fine
+    ok = pb.make_params(1, 1, 2 * 64 * 2048, 64)
+    mo, ro, co = pb.prism_varlen_layout(ok, [0, 64 * 2048, 2 * 64 * 2048])
+    assert ro == [0, 2049, 4098]
+    assert pb.prism_estimate_varlen_workspace_bytes(ok, [0, 64 * 2048, 2 * 64 * 2048]) == \
+        pb.prism_estimate_workspace_bytes(pb.make_params(1, 1, 64 * 2048, 64))
+    assert pb.prism_sparse_attn_varlen_workspace_bytes(params, [0, 300, 1000]) == \
+        pb.prism_sparse_attn_workspace_bytes(pb.make_params(2, 1, 700, 128))
 
 
 def test_mask_pack_roundtrip():
