@@ -1039,7 +1039,6 @@ static int check_image(const prism_params* params, const void* img, size_t bytes
 struct DeviceFacts {
   int cus;          // compute units
 };
-constexpr int kMaxDevices = 64;
 static int device_facts(DeviceFacts* out) {
   static std::mutex mu;
   static DeviceFacts facts[kMaxDevices];

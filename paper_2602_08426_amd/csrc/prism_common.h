@@ -12,6 +12,7 @@ constexpr int kHeadDim = 128;           // the head dim of the 64-queries-per-wa
 constexpr int kMaxHeadDim = 256;        // head_dim is 64, 128 or 256
 constexpr int kMaxBlocks = 2048;       // N <= 2048  (128K tokens at B = 64)
 constexpr int kWave = 64;
+constexpr int kMaxDevices = 64;         // GPUs of one process for which per-device host state is kept
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));

@@ -851,9 +851,20 @@ static int launch_select(const prism_params* p, const BandMap& map, char* ws, co
   const size_t lds = (size_t)kStripRows * (((N + 15) / 16) * 16 + 4) * sizeof(float);
   auto kern = select_kernel<MAXCH, DUMP>;
   if (lds > 64 * 1024) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-      return PRISM_ERR_HIP;
+    // more than 64 KB of dynamic LDS has to be allowed once per kernel and device: what the
+    // largest N needs is asked for on the first such call of this instantiation on a device
+    static std::mutex mu;
+    static bool raised[kMaxDevices];
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return PRISM_ERR_HIP;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!raised[dev]) {
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                              hipFuncAttributeMaxDynamicSharedMemorySize,
+                              (int)(kStripRows * (kMaxBlocks + 4) * sizeof(float))) != hipSuccess)
+        return PRISM_ERR_HIP;
+      raised[dev] = true;
+    }
   }
   int select_flags = 0;
   if (!(p->flags & PRISM_FLAG_BIDIRECTIONAL)) select_flags |= kSelCausal;
@@ -1060,7 +1071,6 @@ extern "C" int prism_estimate(const prism_params* params, const void* q_bf16, co
 constexpr size_t kStaticScratchBytes = (size_t)16 << 20;
 static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
-constexpr int kMaxDevices = 64;
 static void* g_scratch_ptr[kMaxDevices];
 static std::mutex g_scratch_mutex;
 
