@@ -11,8 +11,8 @@ half-step is placed by hand in the shadow of the MFMAs of its neighbours.  That 
 registers with the output accumulators and the Q fragments pinned in AGPRs and an explicit
 instruction order; both are fixed here rather than left to a register allocator.
 
-Formulation (same as the 32-query kernel): S^T = K Q^T, O^T += V^T P^T on
-v_mfma_f32_32x32x16_bf16; in the accumulator lane l holds query l%32 and keys
+Formulation (same as the 32-query kernel): S^T = K Q^T on v_mfma_f32_32x32x16_bf16, O^T += V^T P^T
+on v_mfma_f32_32x32x16_f16 (P and the V^T image as fp16); in the accumulator lane l holds query l%32 and keys
 8*(r/4) + 4*(l/32) + r%4 (r = 0..15) of a 32-key tile.
 
 Software pipeline over half-steps j (64 keys each, two per listed block):
@@ -20,7 +20,7 @@ Software pipeline over half-steps j (64 keys each, two per listed block):
                    VALU  : softmax(j)                     (in the MFMAs' shadow)
                    copies: K(j+2) -> Kbuf[j&1], V(j) -> Vbuf[j&1]   (global -> LDS, asynchronous)
     end of iteration: wait for this wave's copies, workgroup barrier.
-S(j) lives in VGPR bank j&1; softmax(j) turns it into P(j) in place (bf16 pairs in the first 8
+S(j) lives in VGPR bank j&1; softmax(j) turns it into P(j) in place (fp16 pairs in the first 8
 registers of every 16-register accumulator), which PV(j) reads as its B operand one iteration
 later, before S(j+2) overwrites the bank.
 
