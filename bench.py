@@ -389,6 +389,7 @@ def main() -> int:
         "config": {"workload": w.name, "n_q_heads": h, "n_kv_heads": hkv, "seq_len": L, "block": B,
                    "head_dim": d, "d_high": w.d_high, "d_low": w.d_low, "top_p": w.top_p,
                    "rope_base": w.rope_base, "seed": w.seed},
+        "library": os.path.relpath(pb.library_path(), ROOT),
         "detail": {
             "ms_estimate": round(ms_est, 4), "ms_v_image": round(ms_vimg, 4),
             "ms_sparse_attn": round(ms_attn, 4),

@@ -13,7 +13,10 @@ from typing import Optional
 
 import torch
 
-_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libprism.so")
+# PRISM_LIBRARY names another build of the same library (the measurement-only variants that
+# `python -m paper_2602_08426_amd.build --ablation` writes); there is still no fallback.
+_LIB_PATH = os.environ.get("PRISM_LIBRARY") or os.path.join(os.path.dirname(os.path.abspath(__file__)),
+                                                            "libprism.so")
 _lib: Optional[ctypes.CDLL] = None
 
 PRISM_FLAG_NO_CALIBRATION = 1

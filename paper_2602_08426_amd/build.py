@@ -54,5 +54,35 @@ def build_library(verbose: bool = False, extra_flags: list[str] | None = None) -
     return _compile(SOURCES, LIB_PATH, verbose, extra_flags)
 
 
+def build_ablation(experiment: str, out_path: str, verbose: bool = False) -> str:
+    """A measurement-only variant of libprism.so whose 64-queries-per-wave row loop leaves parts out
+    (PRISM_W64_EXPERIMENT of gen_attn_w64.py: "nosoft", "nocopy", "nowait", "nobar_mid", "nobar_end";
+    results are wrong by construction, control flow and bounds are unchanged).  The generated loop and
+    the library go to the given path; the product library is not touched."""
+    import shutil
+    import tempfile
+    with tempfile.TemporaryDirectory() as tmp:
+        for name in os.listdir(CSRC):
+            if name.endswith((".hip", ".h")):
+                shutil.copy(os.path.join(CSRC, name), tmp)
+        env = dict(os.environ, PRISM_W64_EXPERIMENT=experiment)
+        gen = subprocess.run([sys.executable, os.path.join(CSRC, "gen_attn_w64.py"),
+                              os.path.join(tmp, "prism_attn_w64_body.inc")], capture_output=True, text=True, env=env)
+        if gen.returncode != 0:
+            raise RuntimeError(f"gen_attn_w64.py failed:\n{gen.stderr}")
+        hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+        cmd = [hipcc, *HIPCC_FLAGS, "-I", os.path.join(ROOT, "include"), "-I", tmp,
+               *[os.path.join(tmp, s) for s in SOURCES], "-o", out_path]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        res = subprocess.run(cmd, capture_output=True, text=True)
+        if res.returncode != 0:
+            raise RuntimeError(f"hipcc failed ({res.returncode}):\n{res.stderr}")
+    return out_path
+
+
 if __name__ == "__main__":
-    print(build_library(verbose=True))
+    if len(sys.argv) == 4 and sys.argv[1] == "--ablation":
+        print(build_ablation(sys.argv[2], sys.argv[3], verbose=True))
+    else:
+        print(build_library(verbose=True))

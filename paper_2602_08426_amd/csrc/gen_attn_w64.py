@@ -471,6 +471,16 @@ DEPTH = 6               # fragment groups read ahead of their MFMAs
 INCOMING_SIDE = 14      # side instructions issued beside the held-back MFMAs (the copy's issue)
 
 
+def sync_point(which):
+    """Wait for this wave's older tile copy, then the workgroup barrier.  The timing experiments
+    (PRISM_W64_EXPERIMENT, wrong results by construction, never part of the product build) leave
+    out the barrier ("nobar_mid", "nobar_end") or the wait for the copies ("nowait")."""
+    ops = [Ins("s_waitcnt lgkmcnt(0)" if "nowait" in EXPERIMENT else WAIT_OLDER_COPY, "wait")]
+    if f"nobar_{which}" not in EXPERIMENT:
+        ops.append(Ins("s_barrier", "barrier"))
+    return ops
+
+
 def held_s_mfmas(bank):
     """MFMAs of the last HOLD fragment groups of an S phase into `bank` (their fragments sit in
     the last ring slots: every phase has 16 groups, so group 14 + i is in slot 6 + i)."""
@@ -554,7 +564,7 @@ def iteration(p, hh, do_pv, do_s, incoming, uid, sequential=False):
         held1 = []
         ops += copy_a
         ops += mask_block(p, hh, f"Lnomask_{uid}")
-    ops += [Ins(WAIT_OLDER_COPY, "wait"), Ins("s_barrier", "barrier")]
+    ops += sync_point("mid")
     # ---- second phase
     if do_s:
         pre, slots, held2 = segment(s_ops(q), 16 if do_pv else 0, q, q)
@@ -569,7 +579,7 @@ def iteration(p, hh, do_pv, do_s, incoming, uid, sequential=False):
         ops += interleave([[m] for m in held1], copy_b + vops[n_a:])
     if uid in ("o0", "oZ"):
         ops.append(salu(f"s_mov_b32 s{S_HAVE_O}, 1"))
-    ops += [Ins(WAIT_OLDER_COPY, "wait"), Ins("s_barrier", "barrier")]
+    ops += sync_point("end")
     if hh == 1:
         # next block: entry b+1 becomes b, the entry loaded two ahead becomes b+1
         ops += [salu(f"s_mov_b32 s{S_CV}, s{S_CK}"),
