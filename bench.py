@@ -98,12 +98,32 @@ def measure_peaks(which=None):
     return rows
 
 
+def measure_issue_patterns():
+    """Cycles per repetition of short instruction patterns for one wave per SIMD (libprism_peaks.so)."""
+    import ctypes
+    lib = ctypes.CDLL(os.path.join(ROOT, "paper_2602_08426_amd", "libprism_peaks.so"))
+    lib.prism_peaks_name.restype = ctypes.c_char_p
+    lib.prism_peaks_issue_pattern_name.restype = ctypes.c_char_p
+    lib.prism_peaks_measure.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_double)]
+    probe = {lib.prism_peaks_name(i).decode(): i for i in range(lib.prism_peaks_count())}["issue_pattern"]
+    rows = []
+    for pat in range(lib.prism_peaks_issue_patterns()):
+        out = (ctypes.c_double * 4)()
+        if lib.prism_peaks_measure(probe, pat, out) != 0:
+            raise RuntimeError(f"issue pattern {pat} failed")
+        name = lib.prism_peaks_issue_pattern_name(pat).decode()
+        rows.append({"pattern": name, "cycles_per_repetition": round(out[3], 2), "shader_mhz": round(out[2], 0)})
+        log(f"issue pattern [{name}]: {out[3]:.2f} cycles, {out[2]:.0f} MHz")
+    return rows
+
+
 def peaks_main() -> int:
     rows = measure_peaks()
     print(json.dumps({"metric": "achievable peaks of this GPU (probe loops of libprism_peaks.so)",
                       "published": {"bf16_mfma_tflops": PEAK_BF16_TFLOPS, "hbm_gbs": PEAK_HBM_GBS},
                       "arg_meaning": "workgroups per CU for the on-chip probes, footprint in MiB for stream_read_16B",
-                      "rows": rows}), flush=True)
+                      "rows": rows,
+                      "issue_patterns_one_wave_per_simd": measure_issue_patterns()}), flush=True)
     return 0
 
 

@@ -12,7 +12,9 @@
 //                instructions for the VALU probes)
 //       out[2] = shader clock in MHz seen by workgroup 0 (cycle counter / 100 MHz wall counter)
 //       out[3] = cycles per MFMA (or per LDS read / VALU instruction) of one wave of workgroup 0
-//     arg: workgroups per CU (1 or 2) for the on-chip probes, footprint in MiB for the stream probe.
+//     arg: workgroups per CU (1 or 2) for the on-chip probes, footprint in MiB for the stream probe,
+//          pattern index for issue_pattern (prism_peaks_issue_patterns / _issue_pattern_name list them;
+//          out[1] = pattern repetitions, out[3] = cycles per repetition for one wave per SIMD).
 //   Returns 0, or -1 on a HIP error / bad argument.  Allocates its own buffers and synchronises.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -32,13 +34,14 @@ enum Probe {
   kValuExp,             // v_exp_f32 stream
   kMfmaValuSameWave,    // per MFMA: 4 v_fma_f32 + 1 v_exp_f32 of the same wave in its shadow
   kStreamRead,          // 16-byte loads over a footprint of `arg` MiB, read again and again
+  kIssuePattern,        // `arg` = index of an instruction pattern: cycles one wave per SIMD needs per pattern
   kProbeCount
 };
 
 const char* const kNames[kProbeCount] = {
     "mfma_32x32x16_bf16_only", "mfma_plus_lds_read_1_to_1", "mfma_plus_lds_read_1_to_2",
     "lds_read_b128_only", "valu_fma_f32", "valu_exp_f32", "mfma_plus_4fma_1exp_same_wave",
-    "stream_read_16B"};
+    "stream_read_16B", "issue_pattern"};
 
 constexpr int kItersPerLaunch = 4000;      // outer iterations of the on-chip probes
 constexpr int kSlots = 32;                 // MFMA slots per outer iteration
@@ -153,6 +156,144 @@ __global__ __launch_bounds__(256) void stream_kernel(const u32x4* __restrict__ s
   if ((a[0] ^ a[1] ^ a[2] ^ a[3]) == 0x12345u) out[0] = 1u;    // keeps the loads alive
 }
 
+// ---- instruction-issue patterns ------------------------------------------------------------------
+// What a single wave per SIMD (the 64-queries-per-wave attention kernel's occupancy) can issue: each
+// pattern is a short fixed instruction sequence on independent registers, repeated 64 times per loop
+// trip in inline asm (so the order is the one written here), one workgroup of four waves per CU.
+// The result is cycles per repetition of the pattern.
+#define PRISM_FMA(d) "v_fma_f32 v" #d ", v120, v121, v" #d "\n"
+#define PRISM_EXP(d) "v_exp_f32 v" #d ", v122\n"
+#define PRISM_SALU "s_add_u32 s41, s41, 1\n"
+#define PRISM_LDS(d) "ds_read_b128 v[" #d ":" #d "+3], v123\n"
+#define PRISM_MFMA(a) "v_mfma_f32_32x32x16_bf16 a[" #a ":" #a "+15], v[124:127], v[124:127], a[" #a ":" #a "+15]\n"
+#define PRISM_G6(a) PRISM_MFMA(a) PRISM_FMA(100) PRISM_FMA(101) PRISM_FMA(102) PRISM_FMA(103) PRISM_FMA(108) PRISM_FMA(109) PRISM_FMA(110)
+#define PRISM_G7(a) PRISM_MFMA(a) PRISM_FMA(100) PRISM_FMA(101) PRISM_FMA(102) PRISM_EXP(111) PRISM_FMA(103) PRISM_FMA(108)
+#define PRISM_G8(a) PRISM_MFMA(a) PRISM_FMA(100) PRISM_FMA(101) PRISM_EXP(111) PRISM_SALU PRISM_FMA(102) PRISM_FMA(103)
+#define PRISM_G9(a) PRISM_MFMA(a) PRISM_EXP(111) PRISM_FMA(100) PRISM_FMA(101) PRISM_FMA(102) PRISM_FMA(103) PRISM_FMA(108)
+#define PRISM_DOT2(d) "v_dot2_f32_f16 v" #d ", v120, v121, v" #d "\n"
+#define PRISM_G12(a) PRISM_MFMA(a) PRISM_FMA(100) PRISM_FMA(101) PRISM_DOT2(109) PRISM_EXP(111) PRISM_FMA(103) PRISM_FMA(108)
+constexpr int kIssuePatterns = 20;
+const char* const kIssueNames[kIssuePatterns] = {
+    "2 x v_fma_f32",
+    "v_exp_f32 + v_fma_f32",
+    "v_exp_f32 + s_add_u32",
+    "v_fma_f32 + s_add_u32",
+    "v_exp_f32 + ds_read_b128",
+    "v_fma_f32 + ds_read_b128",
+    "2 x (v_mfma_32x32x16 + 7 v_fma_f32)",
+    "2 x (v_mfma_32x32x16 + 5 v_fma_f32 + v_exp_f32)",
+    "2 x (v_mfma_32x32x16 + 4 v_fma_f32 + v_exp_f32 + s_add_u32 right behind the exp)",
+    "2 x (v_mfma_32x32x16 + v_exp_f32 right behind it + 5 v_fma_f32)",
+    "2 x (v_exp_f32 + s_add_u32) + 2 v_fma_f32",
+    "2 x v_exp_f32",
+    "2 x (v_mfma_32x32x16 + 4 v_fma_f32 + v_dot2_f32_f16 + v_exp_f32)",
+    "4 x v_fma_f32 on four registers",
+    "4 x v_dot2_f32_f16 on four registers",
+    "4 x v_max3_f32 on four registers",
+    "4 x v_cvt_pk_f16_f32 on four registers",
+    "4 x v_fma_f32 + s_waitcnt lgkmcnt(0)",
+    "4 x v_fma_f32 + s_nop 0",
+    "4 x v_fma_f32 + v_permlane32_swap_b32",
+};
+
+template <int PATTERN>
+__global__ __launch_bounds__(256) void issue_kernel(float* out, long long* clk, int iters) {
+  __shared__ __attribute__((aligned(16))) char lds[4096];
+  lds[threadIdx.x * 16] = (char)threadIdx.x;
+  __syncthreads();
+  const int lds_off = (int)(size_t)lds + (threadIdx.x & 63) * 16;
+  const long long c0 = clock64(), w0 = wall_clock64();
+  asm volatile(
+      "v_mov_b32 v120, 1.0\n v_mov_b32 v121, 0.5\n v_mov_b32 v122, 0.5\n v_mov_b32 v123, %1\n"
+      "v_mov_b32 v124, 0\n v_mov_b32 v125, 0\n v_mov_b32 v126, 0\n v_mov_b32 v127, 0\n"
+      "s_mov_b32 s40, %0\n s_mov_b32 s41, 0\n"
+      "1:\n"
+      ".rept 64\n"
+      // the patterns; the assembler keeps only the one whose number matches
+      ".if %c2 == 0\n" PRISM_FMA(100) PRISM_FMA(101) ".endif\n"
+      ".if %c2 == 1\n" PRISM_EXP(100) PRISM_FMA(101) ".endif\n"
+      ".if %c2 == 2\n" PRISM_EXP(100) PRISM_SALU ".endif\n"
+      ".if %c2 == 3\n" PRISM_FMA(100) PRISM_SALU ".endif\n"
+      ".if %c2 == 4\n" PRISM_EXP(100) PRISM_LDS(104) ".endif\n"
+      ".if %c2 == 5\n" PRISM_FMA(100) PRISM_LDS(104) ".endif\n"
+      // MFMA groups come in pairs on two accumulators, so consecutive MFMAs are independent
+      ".if %c2 == 6\n" PRISM_G6(0) PRISM_G6(16) ".endif\n"
+      ".if %c2 == 7\n" PRISM_G7(0) PRISM_G7(16) ".endif\n"
+      ".if %c2 == 8\n" PRISM_G8(0) PRISM_G8(16) ".endif\n"
+      ".if %c2 == 9\n" PRISM_G9(0) PRISM_G9(16) ".endif\n"
+      ".if %c2 == 10\n" PRISM_EXP(100) PRISM_SALU PRISM_EXP(101) PRISM_SALU PRISM_FMA(102) PRISM_FMA(103) ".endif\n"
+      ".if %c2 == 11\n" PRISM_EXP(100) PRISM_EXP(101) ".endif\n"
+      ".if %c2 == 12\n" PRISM_G12(0) PRISM_G12(16) ".endif\n"
+      ".if %c2 == 13\n" PRISM_FMA(100) PRISM_FMA(101) PRISM_FMA(102) PRISM_FMA(103) ".endif\n"
+      ".if %c2 == 14\n" PRISM_DOT2(100) PRISM_DOT2(101) PRISM_DOT2(102) PRISM_DOT2(103) ".endif\n"
+      ".if %c2 == 15\n v_max3_f32 v100, v120, v121, v100\n v_max3_f32 v101, v120, v121, v101\n"
+      "v_max3_f32 v102, v120, v121, v102\n v_max3_f32 v103, v120, v121, v103\n .endif\n"
+      ".if %c2 == 16\n v_cvt_pk_f16_f32 v100, v120, v121\n v_cvt_pk_f16_f32 v101, v120, v121\n"
+      "v_cvt_pk_f16_f32 v102, v120, v121\n v_cvt_pk_f16_f32 v103, v120, v121\n .endif\n"
+      ".if %c2 == 17\n" PRISM_FMA(100) PRISM_FMA(101) PRISM_FMA(102) PRISM_FMA(103) "s_waitcnt lgkmcnt(0)\n .endif\n"
+      ".if %c2 == 18\n" PRISM_FMA(100) PRISM_FMA(101) PRISM_FMA(102) PRISM_FMA(103) "s_nop 0\n .endif\n"
+      ".if %c2 == 19\n" PRISM_FMA(100) PRISM_FMA(101) PRISM_FMA(102) PRISM_FMA(103)
+      "v_permlane32_swap_b32 v108, v109\n .endif\n"
+      ".endr\n"
+      "s_waitcnt lgkmcnt(0)\n"
+      "s_sub_u32 s40, s40, 1\n s_cmp_lg_u32 s40, 0\n s_cbranch_scc1 1b\n"
+      "s_nop 7\n s_nop 7\n s_nop 7\n"
+      :
+      : "s"(iters), "v"(lds_off), "n"(PATTERN)
+      : "memory", "scc", "s40", "s41", "v100", "v101", "v102", "v103", "v104", "v105", "v106", "v107", "v108",
+        "v109", "v110", "v111", "v120", "v121", "v122", "v123", "v124", "v125", "v126", "v127", "a0", "a1", "a2",
+        "a3", "a4", "a5", "a6", "a7", "a8", "a9", "a10", "a11", "a12", "a13", "a14", "a15", "a16", "a17", "a18", "a19",
+        "a20", "a21", "a22", "a23", "a24", "a25", "a26", "a27", "a28", "a29", "a30", "a31");
+  const long long c1 = clock64(), w1 = wall_clock64();
+  if (threadIdx.x == 0) {
+    clk[blockIdx.x * 2] = c1 - c0;
+    clk[blockIdx.x * 2 + 1] = w1 - w0;
+  }
+  out[blockIdx.x * 256 + threadIdx.x] = 0.f;
+}
+#undef PRISM_FMA
+#undef PRISM_EXP
+#undef PRISM_SALU
+#undef PRISM_LDS
+#undef PRISM_MFMA
+#undef PRISM_G6
+#undef PRISM_G7
+#undef PRISM_G8
+#undef PRISM_G9
+#undef PRISM_G12
+#undef PRISM_DOT2
+
+template <int PATTERN>
+int run_issue(int cus, double* res) {
+  constexpr int kTrips = 2000;
+  float* out = nullptr;
+  long long* clk = nullptr;
+  if (hipMalloc(&out, (size_t)cus * 256 * sizeof(float)) != hipSuccess) return -1;
+  if (hipMalloc(&clk, (size_t)cus * 2 * sizeof(long long)) != hipSuccess) return -1;
+  hipEvent_t e0, e1;
+  (void)hipEventCreate(&e0);
+  (void)hipEventCreate(&e1);
+  hipLaunchKernelGGL(issue_kernel<PATTERN>, dim3(cus), dim3(256), 0, 0, out, clk, kTrips / 8);   // warm-up
+  (void)hipDeviceSynchronize();
+  (void)hipEventRecord(e0, 0);
+  hipLaunchKernelGGL(issue_kernel<PATTERN>, dim3(cus), dim3(256), 0, 0, out, clk, kTrips);
+  (void)hipEventRecord(e1, 0);
+  int rc = hipEventSynchronize(e1) == hipSuccess && hipGetLastError() == hipSuccess ? 0 : -1;
+  float ms = 0.f;
+  (void)hipEventElapsedTime(&ms, e0, e1);
+  long long h[2] = {0, 1};
+  (void)hipMemcpy(h, clk, sizeof(h), hipMemcpyDeviceToHost);
+  res[0] = ms;
+  res[1] = (double)cus * 4 * kTrips * 64;                 // pattern repetitions of the launch
+  res[2] = (double)h[0] / (double)h[1] * 100.0;
+  res[3] = (double)h[0] / ((double)kTrips * 64);          // cycles per repetition
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  (void)hipFree(out);
+  (void)hipFree(clk);
+  return rc;
+}
+
 template <int PROBE>
 int run_onchip(int wgs_per_cu, int cus, double* res) {
   const int grid = cus * wgs_per_cu;
@@ -231,6 +372,12 @@ extern "C" const char* prism_peaks_name(int probe) {
   return probe >= 0 && probe < kProbeCount ? kNames[probe] : "";
 }
 
+extern "C" int prism_peaks_issue_patterns(void) { return kIssuePatterns; }
+
+extern "C" const char* prism_peaks_issue_pattern_name(int pattern) {
+  return pattern >= 0 && pattern < kIssuePatterns ? kIssueNames[pattern] : "";
+}
+
 extern "C" int prism_peaks_measure(int probe, int arg, double* out) {
   if (out == nullptr) return -1;
   int dev = 0;
@@ -238,6 +385,31 @@ extern "C" int prism_peaks_measure(int probe, int arg, double* out) {
   if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return -1;
   const int cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
   if (probe == kStreamRead) return run_stream(arg, cus, out);
+  if (probe == kIssuePattern) {
+    switch (arg) {
+      case 0: return run_issue<0>(cus, out);
+      case 1: return run_issue<1>(cus, out);
+      case 2: return run_issue<2>(cus, out);
+      case 3: return run_issue<3>(cus, out);
+      case 4: return run_issue<4>(cus, out);
+      case 5: return run_issue<5>(cus, out);
+      case 6: return run_issue<6>(cus, out);
+      case 7: return run_issue<7>(cus, out);
+      case 8: return run_issue<8>(cus, out);
+      case 9: return run_issue<9>(cus, out);
+      case 10: return run_issue<10>(cus, out);
+      case 11: return run_issue<11>(cus, out);
+      case 12: return run_issue<12>(cus, out);
+      case 13: return run_issue<13>(cus, out);
+      case 14: return run_issue<14>(cus, out);
+      case 15: return run_issue<15>(cus, out);
+      case 16: return run_issue<16>(cus, out);
+      case 17: return run_issue<17>(cus, out);
+      case 18: return run_issue<18>(cus, out);
+      case 19: return run_issue<19>(cus, out);
+      default: return -1;
+    }
+  }
   if (arg != 1 && arg != 2) return -1;
   switch (probe) {
     case kMfmaOnly: return run_onchip<kMfmaOnly>(arg, cus, out);
