@@ -211,6 +211,55 @@ def estimate_curve(args) -> int:
     return 0
 
 
+def occupancy_sweep() -> int:
+    """Attention throughput per busy workgroup when only part of the chip works: uniform rows of 2048
+    entries over 16 cache-resident blocks (B = 128, d = 128), from 16 rows (16 workgroups on 16 CUs) to
+    8192 rows (512 persistent workgroups, two per CU), both attention kernels.  Separates what a workgroup
+    can do at the clock of a lightly loaded chip from what the power limit leaves when all 256 CUs run."""
+    import numpy as np
+    import torch
+
+    from paper_2602_08426_amd import binding as pb
+
+    B, n = 128, 2048
+    rows_out = []
+    for h, L in ((1, 2048), (1, 8192), (4, 8192), (8, 8192), (16, 8192), (32, 32768)):
+        hkv = 1 if h < 8 else h // 4
+        N = L // B
+        torch.manual_seed(0)
+        q = torch.randn((h, L, 128), device="cuda").to(torch.bfloat16)
+        k = torch.randn((hkv, L, 128), device="cuda").to(torch.bfloat16)
+        v = torch.randn((hkv, L, 128), device="cuda").to(torch.bfloat16)
+        lst = np.tile(np.arange(16, dtype=np.int32), n // 16)
+        rp = torch.arange(0, (h * N + 1) * n, n, dtype=torch.int32, device="cuda")
+        ci = torch.from_numpy(np.tile(lst, h * N)).cuda()
+        for tag, fl in (("sparse_attn_kernel<128>", pb.PRISM_FLAG_GENERAL_KERNEL), ("sparse_attn_w64_kernel", 0)):
+            params = pb.make_params(h, hkv, L, B, flags=fl | pb.PRISM_FLAG_BIDIRECTIONAL)
+            img = pb.alloc_workspace(pb.prism_sparse_attn_workspace_bytes(params))
+            pb.prism_v_image(params, v, img)
+            out = torch.empty_like(q)
+            pb.prism_sparse_attn_pre(params, q, k, img, rp, ci, ci.numel(), out, None)
+            torch.cuda.synchronize()
+            ts = []
+            for _ in range(3):
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                pb.prism_sparse_attn_pre(params, q, k, img, rp, ci, ci.numel(), out, None)
+                b.record()
+                torch.cuda.synchronize()
+                ts.append(a.elapsed_time(b))
+            rows = h * N
+            wgs = min(rows, 512)
+            tf = 4.0 * B * B * 128 * ci.numel() / (min(ts) * 1e-3) / 1e12
+            rows_out.append({"kernel": tag, "rows": rows, "workgroups": wgs, "ms": round(min(ts), 3),
+                             "tflops": round(tf, 1), "tflops_per_workgroup": round(tf / wgs, 3)})
+            log(f"rows {rows:5d} workgroups {wgs:3d} {tag}: {min(ts):.3f} ms, {tf:.1f} TFLOP/s, "
+                f"{tf / wgs:.3f} per workgroup")
+    print(json.dumps({"metric": "attention throughput vs number of busy workgroups (cache-resident uniform lists)",
+                      "unit": "TFLOP/s", "rows": rows_out}), flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -231,6 +280,9 @@ def main() -> int:
                     help="instead of the step benchmark: run the machine-peak probes (MFMA-only loop, MFMA with "
                          "LDS operand reads, LDS reads, VALU, streaming reads over several footprints), one JSON line")
     ap.add_argument("--no-peaks", action="store_true", help="skip the two peak probes of the default run")
+    ap.add_argument("--occupancy-sweep", action="store_true",
+                    help="instead of the step benchmark: attention throughput per busy workgroup from 16 to 512 "
+                         "workgroups on cache-resident lists (what the power limit costs), one JSON line")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (known HBM traffic) for counter calibration")
     args = ap.parse_args()
@@ -253,6 +305,8 @@ def main() -> int:
         return estimate_curve(args)
     if args.peaks:
         return peaks_main()
+    if args.occupancy_sweep:
+        return occupancy_sweep()
     w = wl.WORKLOADS[args.workload]
     h, hkv, L, B, N, d = w.n_q_heads, w.n_kv_heads, w.seq_len, w.block, w.n_blocks, w.head_dim
 
