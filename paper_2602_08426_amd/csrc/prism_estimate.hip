@@ -312,7 +312,7 @@ constexpr int kStripRows = 16;
 // n0 + k*nstep logits (nstep = 1: block-causal rows, 0: every row sees all N blocks); each row lives in registers: column
 // 64*i + lane in e[k][i].  The four rows are advanced together so that their wave reductions
 // (dependent DPP chains) overlap.  Selected bits are OR-ed into the rows' LDS bit words.
-constexpr int kRowsPerWave = 4;
+// rows per wave: 4 (workgroup of 4 waves) or 2 (8 waves: twice the waves in flight for the same LDS strip)
 
 // lane `i` of (lo, hi) := the wave-uniform 64-bit word w
 __device__ __forceinline__ void put_word(uint64_t w, int i, int lane, int& lo, int& hi) {
@@ -321,7 +321,7 @@ __device__ __forceinline__ void put_word(uint64_t w, int i, int lane, int& lo, i
   hi = mine ? (int)(uint32_t)(w >> 32) : hi;
 }
 
-template <int NCH>
+template <int NCH, int kRowsPerWave>
 __device__ __forceinline__ void select_rows(const float* __restrict__ logits, int ld, int n0, int nstep,
                                             int nrows, float top_p, int lane,
                                             uint64_t* __restrict__ bits, int bits_ld) {
@@ -384,7 +384,10 @@ __device__ __forceinline__ void select_rows(const float* __restrict__ logits, in
       open[k] = n > 1;
     }
     for (int bit = 29; bit >= 0; --bit) {
-      if (!(open[0] || open[1] || open[2] || open[3])) break;
+      bool any_open = false;
+#pragma unroll
+      for (int k = 0; k < kRowsPerWave; ++k) any_open |= open[k];
+      if (!any_open) break;
       float gp[kRowsPerWave];
       int np[kRowsPerWave];
 #pragma unroll
@@ -486,12 +489,13 @@ constexpr int kSelCausal = 1;          // key blocks v > u are excluded (block-c
 constexpr int kSelForceDiagonal = 2;   // block u of every row is switched on after the union
 constexpr int kSelForceSink = 4;       // block 0 of every row is switched on after the union
 
-template <int MAXCH, bool DUMP>
-__global__ __launch_bounds__(256) void select_kernel(
+template <int MAXCH, bool DUMP, int kRowsPerWave>
+__global__ __launch_bounds__(kStripRows / kRowsPerWave * 64) void select_kernel(
     BandVectors bv, const float* __restrict__ inv_scale, int h, int h_kv,
     int N, int bs, int dpad_high, int dpad_low, float top_p, int select_flags,
     uint64_t* __restrict__ mask_bits, int32_t* __restrict__ row_ptr,
     float* __restrict__ logits_high, float* __restrict__ logits_low) {
+  constexpr int kWaves = kStripRows / kRowsPerWave, kThreads = kWaves * 64;
   extern __shared__ float lds_logits[];
   __shared__ uint64_t lds_bits[kStripRows][kMaxBlocks / 64];
   // heavy strips (large u) first
@@ -507,7 +511,7 @@ __global__ __launch_bounds__(256) void select_kernel(
   const int W = (N + 63) >> 6;
 
   if (!DUMP) {
-    for (int i = threadIdx.x; i < kStripRows * (kMaxBlocks / 64); i += 256)
+    for (int i = threadIdx.x; i < kStripRows * (kMaxBlocks / 64); i += kThreads)
       (&lds_bits[0][0])[i] = 0ull;
   }
 
@@ -554,7 +558,7 @@ __global__ __launch_bounds__(256) void select_kernel(
         }
       };
       if (wave < ntiles) load_b(wave);
-      for (int ct = wave; ct < ntiles; ct += 4) {
+      for (int ct = wave; ct < ntiles; ct += kWaves) {
         f32x4 acc = {0.f, 0.f, 0.f, 0.f};
         bf16x8 ch[4], cm[4], cl[4];
 #pragma unroll
@@ -563,7 +567,7 @@ __global__ __launch_bounds__(256) void select_kernel(
           cm[ks] = bm[ks];
           cl[ks] = bl[ks];
         }
-        if (ct + 4 < ntiles) load_b(ct + 4);
+        if (ct + kWaves < ntiles) load_b(ct + kWaves);
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
           if (ks < kn) {
@@ -605,11 +609,11 @@ __global__ __launch_bounds__(256) void select_kernel(
         const float* lg = lds_logits + r0 * ld;
         uint64_t* bits = &lds_bits[r0][0];
         constexpr int bld = kMaxBlocks / 64;
-        if (nmax <= 128) select_rows<2>(lg, ld, n0, nstep, nrows, top_p, lane, bits, bld);
-        else if (nmax <= 256) select_rows<4>(lg, ld, n0, nstep, nrows, top_p, lane, bits, bld);
-        else if (nmax <= 512) select_rows<8>(lg, ld, n0, nstep, nrows, top_p, lane, bits, bld);
-        else if (MAXCH <= 16 || nmax <= 1024) select_rows<16>(lg, ld, n0, nstep, nrows, top_p, lane, bits, bld);
-        else select_rows<MAXCH>(lg, ld, n0, nstep, nrows, top_p, lane, bits, bld);
+        if (nmax <= 128) select_rows<2, kRowsPerWave>(lg, ld, n0, nstep, nrows, top_p, lane, bits, bld);
+        else if (nmax <= 256) select_rows<4, kRowsPerWave>(lg, ld, n0, nstep, nrows, top_p, lane, bits, bld);
+        else if (nmax <= 512) select_rows<8, kRowsPerWave>(lg, ld, n0, nstep, nrows, top_p, lane, bits, bld);
+        else if (MAXCH <= 16 || nmax <= 1024) select_rows<16, kRowsPerWave>(lg, ld, n0, nstep, nrows, top_p, lane, bits, bld);
+        else select_rows<MAXCH, kRowsPerWave>(lg, ld, n0, nstep, nrows, top_p, lane, bits, bld);
       }
       __syncthreads();                             // LDS logits are reused by the next band
     }
@@ -617,8 +621,8 @@ __global__ __launch_bounds__(256) void select_kernel(
 
   if (!DUMP) {
 #pragma unroll 1
-    for (int rr = 0; rr < 4; ++rr) {
-      const int r = wave * 4 + rr;
+    for (int rr = 0; rr < kRowsPerWave; ++rr) {
+      const int r = wave * kRowsPerWave + rr;
       const int u = u0 + r;
       if (u >= N) break;
       const size_t row = (size_t)hq * N + u;
@@ -843,13 +847,13 @@ static int run_pool_and_scale(const prism_params* p, const HeadStrides& hs, cons
   return launch_status();
 }
 
-template <int MAXCH, bool DUMP>
+template <int MAXCH, bool DUMP, int kRowsPerWave = 4>
 static int launch_select(const prism_params* p, const BandMap& map, char* ws, const EstimateWs& L,
                          uint64_t* mask_bits, int32_t* row_ptr, float* lh, float* ll, hipStream_t st) {
   const int N = n_blocks(p);
   const int strips = (N + kStripRows - 1) / kStripRows;
   const size_t lds = (size_t)kStripRows * (((N + 15) / 16) * 16 + 4) * sizeof(float);
-  auto kern = select_kernel<MAXCH, DUMP>;
+  auto kern = select_kernel<MAXCH, DUMP, kRowsPerWave>;
   if (lds > 64 * 1024) {
     // more than 64 KB of dynamic LDS has to be allowed once per kernel and device: what the
     // largest N needs is asked for on the first such call of this instantiation on a device
@@ -870,7 +874,8 @@ static int launch_select(const prism_params* p, const BandMap& map, char* ws, co
   if (!(p->flags & PRISM_FLAG_BIDIRECTIONAL)) select_flags |= kSelCausal;
   if (p->flags & PRISM_FLAG_FORCE_DIAGONAL) select_flags |= kSelForceDiagonal;
   if (p->flags & PRISM_FLAG_FORCE_SINK) select_flags |= kSelForceSink;
-  hipLaunchKernelGGL(kern, dim3(strips, p->n_q_heads), dim3(256), lds, st, band_vectors(ws, L),
+  hipLaunchKernelGGL(kern, dim3(strips, p->n_q_heads), dim3(kStripRows / kRowsPerWave * 64), lds, st,
+                     band_vectors(ws, L),
                      reinterpret_cast<const float*>(ws + L.inv_scale), p->n_q_heads, p->n_kv_heads, N,
                      band_stride(p->head_dim), map.dpad[0], map.dpad[1], p->top_p, select_flags, mask_bits, row_ptr, lh, ll);
   return launch_status();
@@ -934,9 +939,12 @@ static int estimate_core(const prism_params* params, const HeadStrides& hs, cons
   int rc = run_pool_and_scale(params, hs, map, q, k, ws, L, nullptr, nullptr, nullptr, st, rope, q_out, k_out);
   if (rc != PRISM_OK) return rc;
   const int N = n_blocks(params);
+  // up to 1024 blocks: 4 waves of 4 rows, two workgroups per CU; beyond (a 131 KB logit strip, one
+  // workgroup per CU, rows of 32 registers): 8 waves of 2 rows (measured 1.89 -> 1.25 ms at N = 2048,
+  // while at N = 1024 the 4-wave form is 2 % faster)
   rc = (N <= 1024)
-           ? launch_select<16, false>(params, map, ws, L, mask_bits, row_ptr, nullptr, nullptr, st)
-           : launch_select<32, false>(params, map, ws, L, mask_bits, row_ptr, nullptr, nullptr, st);
+           ? launch_select<16, false, 4>(params, map, ws, L, mask_bits, row_ptr, nullptr, nullptr, st)
+           : launch_select<32, false, 2>(params, map, ws, L, mask_bits, row_ptr, nullptr, nullptr, st);
   if (rc != PRISM_OK) return rc;
   return run_compaction(params, mask_bits, row_ptr, col_idx, col_capacity, info, false, st);
 }
