@@ -95,9 +95,6 @@ S_LSE = 74              # 2: lse row base (0 = not requested)
 S_QB = 76               # 2
 S_OB = 78               # 2
 S_VBYTES = 92           # bytes of the V^T image of one kv head (records of the V^T resource)
-S_THR = 93              # SUM_LIMIT as fp32 bits
-S_FLAGP = 94            # 2: address of the plan's flag word (set when a probability overflowed)
-S_INF = 96              # +inf as fp32 bits
 S_MK = 88               # 2: LDS address of this wave's part of Kbuf[0], Kbuf[1]
 S_MV = 90               # 2: ... of Vbuf[0], Vbuf[1]
 
@@ -110,10 +107,6 @@ RESCALE_THRESHOLD = 8.0             # rescale O only when a running max grows by
 # p = 2^(s - m) reaches 2^(M_OFFSET + RESCALE_THRESHOLD) = 4096 at most (fp16 holds 65504) and a
 # probability 2^-36 of the largest one is still a non-zero fp16 value.
 M_OFFSET = 4.0
-# Steady-state softmax: the running max is left alone as long as a lane's 32 probabilities of the
-# half-step sum to SUM_LIMIT at most (then each of them is <= SUM_LIMIT < 65504, the fp16 range);
-# otherwise the slow block moves the max to M_OFFSET below the new true one and rescales.
-SUM_LIMIT = 16384.0
 
 
 # ----------------------------------------------------------------------------------------------
@@ -308,115 +301,6 @@ def softmax_ops(p, qt, tag):
     return ops
 
 
-def softmax_fast(p, uid):
-    """VALU work of softmax(j) on bank p for every half-step but a row's first: no row max on the
-    fast path.  With the running max m (M_OFFSET below the true max when it was last moved)
-        p = 2^(s * scale - m)  in place, summed per lane;
-    a lane whose sum exceeds SUM_LIMIT raises its tile's flag, and only then the slow block runs: row
-    max of the p themselves, delta = max(0, log2(pmax) - M_OFFSET), m += delta, every p, the sums and l
-    scaled by alpha = 2^-delta (O follows at the top of the next iteration, as after any rescale).
-    A probability that overflowed fp32 (a score more than 2^127 above the stale max) cannot be scaled
-    back: the slow block then sets the call's flag word and the general kernel, queued behind this one,
-    recomputes the call.  Returns the instruction list of both query tiles (streams zipped)."""
-    T8 = lambda qt, i: V_T + 8 * qt + i
-    stage_a, stage_b, slow = [[], []], [[], []], []
-    for qt in range(2):
-        ops = stage_a[qt]
-        regs = [SB(p, kt, qt) + r for kt in range(2) for r in range(16)]
-        t_s0, t_s1 = T8(qt, 4), T8(qt, 5)
-        fl = S_FLAG + 2 * qt
-        m, l = V_M + qt, V_L + qt
-        first = [True, True]
-        pend = []
-
-        def flush_one():
-            k = pend.pop(0)
-            ch = k % 2
-            if first[ch]:
-                ops.append(valu(f"v_mov_b32 v{t_s0 + ch}, v{regs[k]}", vr(regs[k]), vr(t_s0 + ch)))
-                first[ch] = False
-            else:
-                ops.append(valu(f"v_add_f32 v{t_s0 + ch}, v{t_s0 + ch}, v{regs[k]}",
-                                vr(t_s0 + ch) + vr(regs[k]), vr(t_s0 + ch)))
-        for k in range(32):
-            ops.append(valu(f"v_fma_f32 v{regs[k]}, v{regs[k]}, s{S_SCALE}, -v{m}", vr(regs[k]) + vr(m), vr(regs[k])))
-            if k >= 1:
-                ops.append(valu(f"v_exp_f32 v{regs[k - 1]}, v{regs[k - 1]}", vr(regs[k - 1]), vr(regs[k - 1]), "trans"))
-                pend.append(k - 1)
-            if len(pend) > 2:
-                flush_one()
-        ops.append(valu(f"v_exp_f32 v{regs[31]}, v{regs[31]}", vr(regs[31]), vr(regs[31]), "trans"))
-        pend.append(31)
-        while pend:
-            flush_one()
-        ops.append(valu(f"v_add_f32 v{t_s0}, v{t_s0}, v{t_s1}", vr(t_s0) + vr(t_s1), vr(t_s0)))
-        ops.append(valu(f"v_cmp_lt_f32 s[{fl}:{fl + 1}], s{S_THR}, v{t_s0}", vr(t_s0), [("s", fl), ("s", fl + 1)]))
-        # ---- slow block of this tile
-        t_mx, t_mc, t_a = T8(qt, 0), T8(qt, 1), T8(qt, 2)
-        al = V_ALPHA + qt
-        sl = []
-        sl.append(valu(f"v_max3_f32 v{t_mx}, v{regs[0]}, v{regs[1]}, v{regs[2]}", vr(regs[0]) + vr(regs[1]) + vr(regs[2]), vr(t_mx)))
-        i = 3
-        while i < 32:
-            if i + 1 < 32:
-                sl.append(valu(f"v_max3_f32 v{t_mx}, v{t_mx}, v{regs[i]}, v{regs[i + 1]}",
-                               vr(t_mx) + vr(regs[i]) + vr(regs[i + 1]), vr(t_mx)))
-                i += 2
-            else:
-                sl.append(valu(f"v_max_f32 v{t_mx}, v{t_mx}, v{regs[i]}", vr(t_mx) + vr(regs[i]), vr(t_mx)))
-                i += 1
-        sl.append(valu(f"v_mov_b32 v{t_mc}, v{t_mx}", vr(t_mx), vr(t_mc)))
-        sl.append(valu(f"v_permlane32_swap_b32 v{t_mx}, v{t_mc}", vr(t_mx) + vr(t_mc), vr(t_mx) + vr(t_mc), "lane"))
-        sl.append(valu(f"v_max_f32 v{t_mx}, v{t_mx}, v{t_mc}", vr(t_mx) + vr(t_mc), vr(t_mx)))
-        # overflow: pmax = +inf (or NaN from inf * 0 further up) -> remember it in s[S_MASK + 2qt]
-        sp = S_MASK + 2 * qt
-        sl.append(valu(f"v_cmp_nlt_f32 s[{sp}:{sp + 1}], v{t_mx}, s{S_INF}", vr(t_mx), [("s", sp), ("s", sp + 1)]))
-        sl.append(valu(f"v_log_f32 v{t_a}, v{t_mx}", vr(t_mx), vr(t_a), "trans"))
-        sl.append(valu(f"v_add_f32 v{t_a}, -{M_OFFSET:.1f}, v{t_a}", vr(t_a), vr(t_a)))
-        sl.append(valu(f"v_max_f32 v{t_a}, 0, v{t_a}", vr(t_a), vr(t_a)))
-        sl.append(valu(f"v_add_f32 v{m}, v{m}, v{t_a}", vr(m) + vr(t_a), vr(m)))
-        sl.append(valu(f"v_exp_f32 v{al}, -v{t_a}", vr(t_a), vr(al), "trans"))
-        for k in range(32):
-            sl.append(valu(f"v_mul_f32 v{regs[k]}, v{regs[k]}, v{al}", vr(regs[k]) + vr(al), vr(regs[k])))
-        sl.append(valu(f"v_mul_f32 v{t_s0}, v{t_s0}, v{al}", vr(t_s0) + vr(al), vr(t_s0)))
-        sl.append(valu(f"v_mul_f32 v{l}, v{l}, v{al}", vr(l) + vr(al), vr(l)))
-        slow += sl
-        # ---- after the check: fp16 pairs in place, l += sum
-        ob = stage_b[qt]
-        for k in range(1, 32, 2):
-            kt, r = divmod(k, 16)
-            dst = SB(p, kt, qt) + (r - 1) // 2
-            ob.append(valu(f"v_cvt_pk_f16_f32 v{dst}, v{regs[k - 1]}, v{regs[k]}", vr(regs[k - 1]) + vr(regs[k]), vr(dst)))
-        ob.append(valu(f"v_add_f32 v{l}, v{l}, v{t_s0}", vr(l) + vr(t_s0), vr(l)))
-    check = [salu(f"s_or_b64 s[{S_TMP}:{S_TMP + 1}], s[{S_FLAG}:{S_FLAG + 1}], s[{S_FLAG + 2}:{S_FLAG + 3}]"),
-             salu(f"s_cbranch_scc0 Lnoslow_{uid}")]
-    # both tiles take the slow block together; a tile that did not need it gets delta = 0, alpha = 1.
-    # The flags stay as the compare left them or are widened to both tiles, so that the O rescale at the
-    # top of the next iteration runs with both alphas valid.
-    tail = [salu(f"s_or_b64 s[{S_TMP}:{S_TMP + 1}], s[{S_MASK}:{S_MASK + 1}], s[{S_MASK + 2}:{S_MASK + 3}]"),
-            salu(f"s_cbranch_scc0 Lnooverflow_{uid}"),
-            valu(f"v_mov_b32 v{T8(0, 0)}, 1", (), vr(T8(0, 0))),
-            valu(f"v_mov_b32 v{T8(0, 1)}, 0", (), vr(T8(0, 1))),
-            Ins(f"global_store_dword v{T8(0, 1)}, v{T8(0, 0)}, s[{S_FLAGP}:{S_FLAGP + 1}]", "vmem",
-                vr(T8(0, 0)) + vr(T8(0, 1))),
-            Ins("s_waitcnt vmcnt(0)", "wait"),
-            Ins(f"Lnooverflow_{uid}:", "label"),
-            Ins(f"Lnoslow_{uid}:", "label")]
-    if EXPERIMENT:
-        # timing experiments: one class of the softmax instructions left out or made cheap
-        def keep(o):
-            op = o.text.split()[0]
-            if "noexp" in EXPERIMENT and op == "v_exp_f32":
-                o.text = o.text.replace("v_exp_f32", "v_mov_b32")
-                o.kind = "valu"
-            return not (("noadd" in EXPERIMENT and op == "v_add_f32") or ("nofma" in EXPERIMENT and op == "v_fma_f32")
-                        or ("nocvt" in EXPERIMENT and op == "v_cvt_pk_f16_f32") or ("dropexp" in EXPERIMENT and op == "v_exp_f32"))
-        for qt in range(2):
-            stage_a[qt] = [o for o in stage_a[qt] if keep(o)]
-            stage_b[qt] = [o for o in stage_b[qt] if keep(o)]
-    return zip_streams(stage_a[0], stage_a[1]), check + slow + tail, zip_streams(stage_b[0], stage_b[1])
-
-
 def f32_bits(x):
     import struct
     return struct.unpack("<I", struct.pack("<f", x))[0]
@@ -548,81 +432,20 @@ def end_of_iteration():
     return [Ins("s_waitcnt vmcnt(0) lgkmcnt(0)", "wait"), Ins("s_barrier", "barrier")]
 
 
-# Issue cost (cycles of a lone wave's issue time) by kind of instruction, measured with the issue-pattern
-# probes of prism_peaks.hip; s_waitcnt and s_nop are free.
-ISSUE_COST = {"mfma": 6.5, "valu": 4.5, "trans": 8.3, "lane": 5.5, "salu": 4.4, "lds": 12.5, "vmem": 17.0}
-
-
-def issue_cost(x):
-    if isinstance(x, list):             # a rarely executed block: the branch round it
-        return 2 * ISSUE_COST["salu"]
-    return ISSUE_COST.get(x.kind, 0.0)
-
-
 def interleave(slots, vops):
-    """MFMA slots with the side instructions spread over them so that every slot carries about the same
-    issue time (program order kept on both sides): a slot that already holds an LDS read or follows a
-    transcendental gets fewer of them.  An element of `vops` that is a list is a block that stays
-    together (a rarely executed block with the branch round it)."""
+    """MFMA slots with the VALU ops spread evenly over them (program order kept on both sides)."""
     out = []
-    v = list(vops)
-    if "evencount" in EXPERIMENT:
-        cost = lambda x: 1.0 if not isinstance(x, list) and x.kind != "mfma" else 0.0
-    else:
-        cost = issue_cost
-    slot_cost = [sum(cost(i) for i in slot) for slot in slots]
-    total = sum(slot_cost) + sum(cost(x) for x in v)
     n = len(slots)
+    v = list(vops)
+    nv = len(v)
     done = 0
-    spent = 0.0
-
-    def put(x):
-        if isinstance(x, list):
-            out.extend(x)
-        else:
-            out.append(x)
     for i, slot in enumerate(slots):
         out += slot
-        spent += slot_cost[i]
-        target = total * (i + 1) / n
-        while done < len(v) and spent + cost(v[done]) / 2 <= target:
-            spent += cost(v[done])
-            put(v[done])
+        want = (nv * (i + 1)) // n if n else nv
+        while done < want:
+            out.append(v[done])
             done += 1
-    for x in v[done:]:
-        put(x)
-    return out
-
-
-def copy_units(ops):
-    """A tile copy as blocks that may be spread over a phase: every load with the scalar set-up in
-    front of it (the M0 write and its wait state stay directly in front of the load they serve)."""
-    units, cur = [], []
-    for o in ops:
-        cur.append(o)
-        if o.kind == "vmem":
-            units.append(cur)
-            cur = []
-    if cur:
-        if units:
-            units[-1] += cur
-        else:
-            units.append(cur)
-    return units
-
-
-def merge_even(a, b):
-    """The elements of `a` placed at even distances among those of `b` (orders kept)."""
-    if not a:
-        return list(b)
-    out, done = [], 0
-    na, nb = len(a), len(b)
-    for i, x in enumerate(b):
-        while done < na and done * nb <= i * na:
-            out.append(a[done])
-            done += 1
-        out.append(x)
-    out += a[done:]
+    out += v[done:]
     return out
 
 
@@ -708,12 +531,7 @@ def iteration(p, hh, do_pv, do_s, incoming, uid, sequential=False):
     Past the end of the list the K / V^T resource is given zero records, so those copies touch no
     memory (the number of loads in flight stays a compile-time fact)."""
     q = p ^ 1
-    if uid == "e0" or "oldsoft" in EXPERIMENT:
-        # a row's first half-step finds the first running max
-        vops = zip_streams(softmax_ops(p, 0, uid), softmax_ops(p, 1, uid))
-    else:
-        before, block, after = softmax_fast(p, uid)
-        vops = before + [block] + after
+    vops = zip_streams(softmax_ops(p, 0, uid), softmax_ops(p, 1, uid))
     if "nosoft" in EXPERIMENT:
         vops = []
     n_a = len(vops) // 2 if (do_pv and do_s) else (len(vops) if do_pv else 0)
@@ -733,25 +551,14 @@ def iteration(p, hh, do_pv, do_s, incoming, uid, sequential=False):
     inc = held_s_mfmas(p) if incoming else []
 
     ops = []
-    spread = "lumpcopy" not in EXPERIMENT
     # ---- first phase
     if do_pv:
         pre, slots, held1 = segment(pv_ops(q), 0, q, q)
         ops += pre
-        if spread:
-            # the copy's loads go out one by one over the whole phase (nothing waits for them before
-            # the middle of the next iteration), the first two beside the held-back MFMAs
-            cu = copy_units(copy_a)
-            n_lead = min(2, len(cu)) if inc else 0
-            ops += interleave([[m] for m in inc], cu[:n_lead]) if inc else []
-            ops += rescale_block(f"Lnoresc_{uid}")
-            ops += mask_block(p, hh, f"Lnomask_{uid}")
-            ops += interleave(slots, merge_even(cu[n_lead:], vops[:n_a]))
-        else:
-            ops += interleave([[m] for m in inc], copy_a) if inc else copy_a
-            ops += rescale_block(f"Lnoresc_{uid}")
-            ops += mask_block(p, hh, f"Lnomask_{uid}")
-            ops += interleave(slots, vops[:n_a])
+        ops += interleave([[m] for m in inc], copy_a) if inc else copy_a
+        ops += rescale_block(f"Lnoresc_{uid}")
+        ops += mask_block(p, hh, f"Lnomask_{uid}")
+        ops += interleave(slots, vops[:n_a])
     else:
         assert not inc
         held1 = []
@@ -762,13 +569,7 @@ def iteration(p, hh, do_pv, do_s, incoming, uid, sequential=False):
     if do_s:
         pre, slots, held2 = segment(s_ops(q), 16 if do_pv else 0, q, q)
         ops += pre
-        if spread:
-            cu = copy_units(copy_b)
-            n_lead = min(2, len(cu)) if held1 else 0
-            if held1:
-                ops += interleave([[m] for m in held1], cu[:n_lead])
-            ops += interleave(slots, merge_even(cu[n_lead:], vops[n_a:]))
-        elif held1:
+        if held1:
             ops += interleave([[m] for m in held1], copy_b)
             ops += interleave(slots, vops[n_a:])
         else:
@@ -827,9 +628,6 @@ def prologue(inp):
     a(salu(f"s_mov_b32 s{S_HAVE_O}, 0"))
     a(salu(f"s_mov_b64 s[{S_FLAG}:{S_FLAG + 1}], 0"))
     a(salu(f"s_mov_b64 s[{S_FLAG + 2}:{S_FLAG + 3}], 0"))
-    a(salu(f"s_mov_b32 s{S_THR}, 0x{f32_bits(SUM_LIMIT):08x}"))
-    a(salu(f"s_mov_b32 s{S_INF}, 0x7f800000"))
-    a(salu(f"s_mov_b64 s[{S_FLAGP}:{S_FLAGP + 1}], {inp['flagp']}"))
     a(salu(f"s_mov_b32 s{S_KBYTES}, {inp['kbytes']}"))
     a(salu(f"s_mov_b32 s{S_VBYTES}, {inp['vbytes']}"))
     for rs, ptr, nbytes in ((S_KRS, inp["k"], inp["kbytes"]), (S_VRS, inp["vt"], inp["vbytes"])):
@@ -1152,7 +950,7 @@ def skipped_view(ops):
         if ins.kind == "salu" and ins.text.startswith("s_cbranch_"):
             target = ins.text.split()[1]
             later = any(o.kind == "label" and o.text == target + ":" for o in ops[i + 1:i + 1200])
-            if later and target.startswith(("Lnomask", "Lnoresc", "Lnok", "Lnolse", "Lnoslow", "Lnooverflow")):
+            if later and target.startswith(("Lnomask", "Lnoresc", "Lnok", "Lnolse")):
                 skip_to = target
     return keep
 
@@ -1186,7 +984,7 @@ def fix_hazards(ops):
 INP = {}          # operand names of the inline-asm inputs, filled by emit()
 
 
-INPUTS = ["t", "q", "o", "lse", "k", "vt", "col", "n", "u", "causal", "lds", "kbytes", "vbytes", "c0", "flagp"]
+INPUTS = ["t", "q", "o", "lse", "k", "vt", "col", "n", "u", "causal", "lds", "kbytes", "vbytes", "c0"]
 
 
 def emit(path, sequential=False):
@@ -1200,7 +998,7 @@ def emit(path, sequential=False):
         raise SystemExit(f"{len(problems)} hazard(s) in the generated schedule")
     clob_v = [f"v{i}" for i in range(32, 256)]
     clob_a = [f"a{i}" for i in range(0, 256)]
-    clob_s = [f"s{i}" for i in range(40, 98)]
+    clob_s = [f"s{i}" for i in range(40, 94)]
     with open(path, "w") as f:
         f.write("// generated by gen_attn_w64.py -- do not edit\n")
         f.write("asm volatile(\n")
@@ -1208,8 +1006,7 @@ def emit(path, sequential=False):
             f.write(f'    "{ins.text}\\n\\t"\n')
         f.write("    :\n")
         f.write('    : "v"(t), "s"(q_row), "s"(o_row), "s"(lse_row), "s"(k_head), "s"(vt_head), "s"(col_row),\n')
-        f.write('      "s"(n_entries), "s"(u), "s"(causal), "s"(lds_base), "s"(k_bytes), "s"(vt_bytes), "s"(c_first),\n')
-        f.write('      "s"(overflow_flag)\n')
+        f.write('      "s"(n_entries), "s"(u), "s"(causal), "s"(lds_base), "s"(k_bytes), "s"(vt_bytes), "s"(c_first)\n')
         clob = ", ".join(f'"{c}"' for c in clob_v + clob_a + clob_s + ["vcc", "scc", "memory"])
         f.write(f"    : {clob});\n")
     n_mfma = sum(1 for i in ops if i.kind == "mfma")

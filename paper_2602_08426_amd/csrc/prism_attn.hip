@@ -225,14 +225,10 @@ enum { kItemEnd = 0, kItemRow = 2 };
 // MI355X: 8 accelerator dies (XCDs), each with its own L2; workgroups are dealt to them round-robin,
 // so the attention kernels keep one work queue per XCD (the plan below has room for exactly kXcds).
 constexpr int kXcds = 8;
-constexpr int kPlanStart = 0, kPlanLen = 8, kPlanCounter = 16, kPlanFlags = 24, kPlanCounter2 = 32, kPlanInts = 40;
+constexpr int kPlanStart = 0, kPlanLen = 8, kPlanCounter = 16, kPlanFlags = 24, kPlanInts = 32;
 // plan[kPlanFlags]: bit 0 = some list holds an entry that must be skipped (negative, beyond the
 // row's last admissible block): such lists go through the general kernel, clean lists through the
 // 64-queries-per-wave kernel; each of the two kernels returns at once when it is not its turn.
-// The 64-queries-per-wave kernel sets the same bit itself when a probability overflowed fp32 in its
-// steady-state softmax (a score more than 2^127 above the running max it had not yet moved): the
-// general kernel queued behind it then recomputes the whole call, pulling from its own set of
-// queue counters (kPlanCounter2), since the first set has been used up by then.
 constexpr int kFlagDirtyLists = 1;
 
 __device__ __forceinline__ int item_kind(int pulled, int seg_start, int seg_len, int* entry) {
@@ -289,7 +285,7 @@ __global__ __launch_bounds__((AttnCfg<BLK, D>::kThreads), (AttnCfg<BLK, D>::kWav
   int my_queue = blockIdx.x % n_queues;
   int seg_start = plan[kPlanStart + my_queue];
   int seg_len = plan[kPlanLen + my_queue];
-  int32_t* counter = plan + (only_dirty ? kPlanCounter2 : kPlanCounter);
+  int32_t* counter = plan + kPlanCounter;
   const int vmax_nc = N - 1;
   const int tail = L - (N - 1) * BLK;              // tokens in the last block (BLK unless ragged)
   const uint32_t head_bytes = (uint32_t)L * D * 2;
@@ -736,7 +732,6 @@ __global__ __launch_bounds__(128) void sparse_attn_w64_kernel(
     const uint16_t* vt_head = vt + (size_t)kvh * N * 128 * kHeadDim;
     const int32_t* col_row = col_idx + it;
     const int n_entries = end - it;
-    int32_t* overflow_flag = plan + kPlanFlags;
 #include "prism_attn_w64_body.inc"
   }
 #endif

@@ -356,13 +356,11 @@ def test_fuzz_random_lists_and_values(seed):
         _compare_rows(params, out, lse, Q, K64, V, mask, None)
 
 
-@pytest.mark.parametrize("jump,expect", [(40.0, "rescale"), (101.0, "overflow")])
-def test_scores_that_jump_far_above_the_running_max(jump, expect):
-    """A key far down the list whose score exceeds everything before it by `jump` nats.  40 nats: the
-    64-queries-per-wave kernel's steady-state softmax (which leaves the running max alone while the
-    probabilities of a half-step stay small) must notice and rescale.  101 nats = 146 in log2 units:
-    the probability overflows fp32 before it can be scaled back, the kernel flags the call and the
-    general kernel queued behind it recomputes it.  Either way the result is the oracle's."""
+@pytest.mark.parametrize("jump", [40.0, 101.0])
+def test_scores_that_jump_far_above_the_running_max(jump):
+    """A key far down the list whose score exceeds everything before it by `jump` nats (58 and 146 in
+    log2 units: beyond the lazy-rescale threshold, and beyond what 2^(s - m) could hold in fp32 if the
+    running max were not moved before the exponentials are taken)."""
     rng = np.random.default_rng(77)
     h, hkv, B, N = 4, 2, 128, 12
     L = N * B
@@ -381,21 +379,13 @@ def test_scores_that_jump_far_above_the_running_max(jump, expect):
     rp_d, ci_d, cnt = gu.csr_to_device(rp, ci)
     qd, kd, vd = _dev(Qb, Kb, Vb)
     Q64, K64, V64 = orc.bf16_to_f64(Qb), orc.bf16_to_f64(Kb), orc.bf16_to_f64(Vb)
-    params = pb.make_params(h, hkv, L, B)
-    out = torch.full((h, L, 128), float("nan"), dtype=torch.bfloat16, device="cuda")
-    lse = torch.full((h, L), float("nan"), dtype=torch.float32, device="cuda")
-    ws = pb.alloc_workspace(pb.prism_sparse_attn_workspace_bytes(params))
-    pb.prism_sparse_attn(params, qd, kd, vd, rp_d, ci_d, cnt, out, lse, ws)
-    torch.cuda.synchronize()
-    _compare_rows(params, out, lse, Q64, K64, V64, mask, None)
-    # the hot queries attend to the hot key alone
-    o = gu.bf16_out_to_f64(out)
-    for hq, tok in hot_q:
-        kv = hq // 2
-        hot_k = 6 * B + 77 if kv == 0 else 5 * B + 3
-        assert np.abs(o[hq, tok] - V64[kv, hot_k]).max() <= OUT_TOL
-    # which kernel produced the result: the flag word of the plan (workspace layout as in test_gpu_queues)
-    from tests.test_gpu_queues import _layout
-    lay = _layout(h, hkv, N, B, L)
-    flag = int(ws.cpu().numpy()[lay["plan"]:lay["plan"] + 160].view(np.int32)[24])
-    assert flag == (1 if expect == "overflow" else 0)
+    for flags in (0, pb.PRISM_FLAG_GENERAL_KERNEL):
+        params = pb.make_params(h, hkv, L, B, flags=flags)
+        out, lse = gu.gpu_sparse_attn(params, qd, kd, vd, rp_d, ci_d, cnt)
+        _compare_rows(params, out, lse, Q64, K64, V64, mask, None)
+        # the hot queries attend to the hot key alone
+        o = gu.bf16_out_to_f64(out)
+        for hq, tok in hot_q:
+            kv = hq // 2
+            hot_k = 6 * B + 77 if kv == 0 else 5 * B + 3
+            assert np.abs(o[hq, tok] - V64[kv, hot_k]).max() <= OUT_TOL

@@ -8,7 +8,7 @@ list and its first valid entry; the segments tile the table; every queue was pul
 inside a queue the (phase, length class) groups come in order; the queues hold about equal work.
 
 The offsets below restate the workspace layout of prism_attn.hip (V^T image, then the int4
-entries, two int32 tables of h*N, class counts, part counts, the 40-int plan, and for whole
+entries, two int32 tables of h*N, class counts, part counts, the 32-int plan, and for whole
 blocks of 128 tokens an fp16 copy of the image with one range flag per kv block; every piece
 aligned to 256 bytes).  They are not part of the C ABI: this file changes with that layout.
 """
@@ -44,7 +44,7 @@ def _layout(h, hkv, N, B, L=None):
     off["parts"] = o
     o = _align(o + hkv * N_CLASSES * 8 * 4)
     off["plan"] = o
-    o = _align(o + 40 * 4)
+    o = _align(o + 32 * 4)
     if B == 128 and (L is None or L % 128 == 0):
         # whole blocks of 128 tokens: a second V^T image in fp16 and one range flag per kv block
         off["image16"] = o
@@ -109,10 +109,8 @@ def test_every_row_is_queued_once_and_the_queues_are_balanced(h, hkv, L, B, bidi
 
     rows = h * N
     items = raw[lay["items"]:lay["items"] + rows * 16].view(np.int32).reshape(rows, 4)
-    plan = raw[lay["plan"]:lay["plan"] + 160].view(np.int32)
-    # two sets of pull counters: the kernel that took the call used one of them (the general kernel
-    # pulls from the second set when it runs behind the 64-queries-per-wave kernel)
-    start, length, pulled = plan[0:8], plan[8:16], np.maximum(plan[16:24], plan[32:40])
+    plan = raw[lay["plan"]:lay["plan"] + 96].view(np.int32)
+    start, length, pulled = plan[0:8], plan[8:16], plan[16:24]
 
     # the segments tile the table, and every queue was pulled past its end
     assert length.sum() == rows
