@@ -59,7 +59,8 @@ typedef enum prism_status {
 #define PRISM_FLAG_STREAM_ONLY 0x40000000u /* measurement aid for prism_sparse_attn(_pre): run the
                                           kernel's K / V^T tile copies, waits and scheduling without
                                           its arithmetic; the outputs are then meaningless.  Shows how
-                                          long the memory side of a call takes on its own. */
+                                          long the memory side of a call takes on its own.  Head dim
+                                          128 only (PRISM_ERR_UNSUPPORTED otherwise). */
 
 /* Problem description shared by all calls (plain data, host memory). */
 typedef struct prism_params {

@@ -89,7 +89,7 @@ __global__ __launch_bounds__(256) void vt_image_kernel(const uint16_t* __restric
 // =====================================================================================
 // Sparse attention kernel.  One workgroup works on one (q-head, q-block) row at a time;
 // BLK/32 waves of 32 queries.
-// LDS: K tile [BLK][128] bf16 and V^T tile [128][BLK] bf16, 16-byte chunks XOR-swizzled by
+// LDS: K tile [BLK][d] bf16 and V^T tile [d][BLK] bf16 (d = 64, 128, 256), 16-byte chunks XOR-swizzled by
 // row so that the 16-lane column reads are conflict-free.  Tiles are copied global -> LDS
 // asynchronously, without passing through registers.
 // Step per listed kv block (each tile buffer is refilled as soon as its last reader is done):
