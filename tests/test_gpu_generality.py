@@ -172,3 +172,66 @@ def test_varlen_batch_matches_per_sequence_oracle(lens, h, hkv, B, d, bands):
     N, W = Ns[s], -(-Ns[s] // 64)
     np.testing.assert_array_equal(one["words"].reshape(-1), words[mo[s]:mo[s + 1]])
     np.testing.assert_array_equal(one["row_ptr"], rp_all[ro[s]:ro[s + 1]])
+
+
+@pytest.mark.parametrize("d,B", [(64, 128), (256, 64)])
+def test_other_head_dims_bidirectional_and_slice_bands(d, B):
+    """Bidirectional selection and attention, bands given as two slices each, at head dims 64 / 256."""
+    L = B * 18
+    base = wl.small_variant(wl.WORKLOADS["c3_llama_32k"], L, 4, 2, B)
+    w = dataclasses.replace(base, head_dim=d, d_high=d // 2, d_low=3 * d // 4)
+    Qb, Kb, Vb = wl.generate(w)
+    qd, kd, vd = (pb.bf16_bits_to_device(x) for x in (Qb, Kb, Vb))
+    Q, K, V = orc.bf16_to_f64(Qb), orc.bf16_to_f64(Kb), orc.bf16_to_f64(Vb)
+    high = [(0, d // 8), (d // 2, d // 8)]                   # two slices: dims [0, d/8) and [d/2, 5d/8)
+    low = [(d // 4, d // 4), (3 * d // 4, d // 4)]
+    p = 0.9
+    sel = orc.prism_select(Q, K, 0, 0, B, p, causal=False, bands={"high": high, "low": low})
+    params = gu.params_for(w, top_p=p, flags=pb.PRISM_FLAG_BIDIRECTIONAL)
+    res = gu.gpu_estimate(params, qd, kd, bands=pb.make_bands(high, low))
+    _check_mask(res["mask"], sel, p)
+    assert np.triu(res["mask"], 1).any()
+    _, rp_d, ci_d, _ = res["dev"]
+    out, lse = gu.gpu_sparse_attn(params, qd, kd, vd, rp_d, ci_d, int(res["info"][0]))
+    o, l = gu.bf16_out_to_f64(out), lse.cpu().numpy().astype(np.float64)
+    ref = orc.block_sparse_attention(Q, K, V, res["mask"], B, None, causal=False)
+    for (hq, u), (ro, rl) in ref.items():
+        sl = slice(u * B, u * B + ro.shape[0])
+        assert np.abs(o[hq, sl] - ro).max() <= OUT_TOL, (hq, u)
+        fin = np.isfinite(rl)
+        assert (np.abs(l[hq, sl][fin] - rl[fin]) <= LSE_TOL).all(), (hq, u)
+
+
+def test_varlen_bidirectional_batch():
+    lens, h, hkv, B, d = [128 * 5, 128 * 3 + 50, 128 * 8], 4, 2, 128, 128
+    parts, Qb, Kb, Vb, cu, w = _packed_batch(lens, h, hkv, B, d, 64, 96)
+    T, p = int(cu[-1]), w.top_p
+    params = pb.make_params(h, hkv, T, B, 64, 96, p, flags=pb.PRISM_FLAG_BIDIRECTIONAL, head_dim=d)
+    mo, ro, co = pb.prism_varlen_layout(params, cu)
+    Ns = [-(-L // B) for L in lens]
+    assert co[-1] == sum(h * N * N for N in Ns)
+    qd, kd, vd = (pb.bf16_bits_to_device(x) for x in (Qb, Kb, Vb))
+    mask_bits = torch.zeros((mo[-1],), dtype=torch.int64, device="cuda")
+    row_ptr = torch.zeros((ro[-1],), dtype=torch.int32, device="cuda")
+    col_idx = torch.zeros((co[-1] + 1,), dtype=torch.int32, device="cuda")
+    info = torch.zeros((4 * len(lens),), dtype=torch.int32, device="cuda")
+    pb.prism_estimate_varlen(params, cu, qd, kd, mask_bits, row_ptr, col_idx, info,
+                             pb.alloc_workspace(pb.prism_estimate_varlen_workspace_bytes(params, cu)))
+    out = torch.full((h, T, d), float("nan"), dtype=torch.bfloat16, device="cuda")
+    lse = torch.full((h, T), float("nan"), dtype=torch.float32, device="cuda")
+    pb.prism_sparse_attn_varlen(params, cu, qd, kd, vd, row_ptr, col_idx, out, lse,
+                                pb.alloc_workspace(pb.prism_sparse_attn_varlen_workspace_bytes(params, cu)))
+    torch.cuda.synchronize()
+    words = mask_bits.cpu().numpy().view(np.uint64)
+    o_all, l_all = gu.bf16_out_to_f64(out), lse.cpu().numpy().astype(np.float64)
+    for s, (L, N) in enumerate(zip(lens, Ns)):
+        Qs, Ks, Vs = (orc.bf16_to_f64(x) for x in parts[s])
+        sel = orc.prism_select(Qs, Ks, 64, 96, B, p, causal=False)
+        mask = gu.unpack_mask(words[mo[s]:mo[s + 1]].reshape(h, N, -(-N // 64)), N)
+        _check_mask(mask, sel, p, max_dont_care=0.05)
+        ref = orc.block_sparse_attention(Qs, Ks, Vs, mask, B, None, causal=False)
+        for (hq, u), (ro_, rl) in ref.items():
+            sl = slice(int(cu[s]) + u * B, int(cu[s]) + u * B + ro_.shape[0])
+            assert np.abs(o_all[hq, sl] - ro_).max() <= OUT_TOL, (s, hq, u)
+            fin = np.isfinite(rl)
+            assert (np.abs(l_all[hq, sl][fin] - rl[fin]) <= LSE_TOL).all(), (s, hq, u)

@@ -84,6 +84,29 @@ def test_fused_rope_matches_oracle_rotation_and_selection(L, h, hkv, B, yarn, of
     assert np.array_equal(plain["col_idx"][:nnz], outs[2].cpu().numpy()[:nnz])
 
 
+@pytest.mark.parametrize("d,d_high,d_low,B,L,offset", [
+    (64, 32, 48, 128, 128 * 11 + 9, 0),
+    (64, 32, 48, 64, 2048, 4000),
+    (256, 128, 192, 128, 128 * 10, 0),
+    (256, 128, 192, 64, 64 * 21 + 5, 120000),       # sixteen rows per thread: the longest fp32 recurrence
+])
+def test_fused_rope_other_head_dims(d, d_high, d_low, B, L, offset):
+    print(f"case d={d} B={B} L={L} offset={offset}", flush=True)
+    base = wl.small_variant(wl.WORKLOADS["c3_llama_32k"], L, 4, 2, B)
+    w = dataclasses.replace(base, head_dim=d, d_high=d_high, d_low=d_low)
+    Qb, Kb, q_out, k_out, params, outs = _run(w, offset)
+    assert params.head_dim == d
+    q_bits = _check_rotation(w, Qb, q_out, offset)
+    k_bits = _check_rotation(w, Kb, k_out, offset)
+    N = params.n_blocks
+    mask = gu.unpack_mask(outs[0].cpu().numpy().view(np.uint64), N)
+    sel = orc.prism_select(orc.bf16_to_f64(q_bits), orc.bf16_to_f64(k_bits), d_high, d_low, B, w.top_p)
+    tol = orc.selection_tolerance(sel, w.top_p)
+    assert not (tol.must & ~mask).any() and not (tol.must_not & mask).any()
+    plain = gu.gpu_estimate(params, q_out, k_out)
+    assert np.array_equal(plain["words"], outs[0].cpu().numpy().view(np.uint64))
+
+
 def test_fused_rope_in_place_equals_out_of_place():
     w = wl.small_variant(wl.WORKLOADS["c2_llama_8k"], 2048, 8, 2)
     _, _, q1, k1, _, o1 = _run(w, 17, in_place=False)
