@@ -383,7 +383,82 @@ __device__ __forceinline__ void select_rows(const float* __restrict__ logits, in
       n_lo[k] = n;
       open[k] = n > 1;
     }
-    for (int bit = 29; bit >= 0; --bit) {
+    // The cut of a row lies within a few octaves of its largest element (= 1): two passes at fixed
+    // keys stand for the first four or five of the search.  The mass above a key does not grow with
+    // the key, so a row that passes at 0x3C000000 (2^-7) has passed at 0x20000000, 0x30000000 and
+    // 0x38000000 as well, and its state is the one after bits 29..26; a row that fails there but
+    // passes at 0x38000000 (2^-15) is in the state after bits 29..27 set and bit 26 refused.  Both go
+    // on at bit 25.  If some row of the wave fails at 2^-15 too, the search starts at bit 29 as usual.
+    int first_bit = 29;
+    {
+      constexpr uint32_t kKeyA = 0x3C000000u, kKeyB = 0x38000000u;
+      float gA[kRowsPerWave], gB[kRowsPerWave];
+      int nA[kRowsPerWave], nB[kRowsPerWave];
+      bool passA[kRowsPerWave];
+      bool anyB = false;
+#pragma unroll
+      for (int k = 0; k < kRowsPerWave; ++k) {
+        float gp = 0.f;
+        nA[k] = 0;
+        if (open[k]) {
+#pragma unroll
+          for (int i = 0; i < NCH; ++i) {
+            const bool above = __float_as_uint(e[k][i]) > kKeyA;
+            gp += above ? e[k][i] : 0.f;
+            nA[k] += __popcll(__builtin_amdgcn_ballot_w64(above));
+          }
+        }
+        gA[k] = gp;
+      }
+#pragma unroll
+      for (int k = 0; k < kRowsPerWave; ++k) {
+        passA[k] = true;
+        if (open[k]) {
+          gA[k] = wave_sum(gA[k]);
+          passA[k] = !(gA[k] < target[k]);
+          anyB = anyB || !passA[k];
+        }
+      }
+      bool all_ok = true;
+      if (anyB) {                                     // uniform
+#pragma unroll
+        for (int k = 0; k < kRowsPerWave; ++k) {
+          float gp = 0.f;
+          nB[k] = 0;
+          if (open[k] && !passA[k]) {
+#pragma unroll
+            for (int i = 0; i < NCH; ++i) {
+              const bool above = __float_as_uint(e[k][i]) > kKeyB;
+              gp += above ? e[k][i] : 0.f;
+              nB[k] += __popcll(__builtin_amdgcn_ballot_w64(above));
+            }
+          }
+          gB[k] = gp;
+        }
+#pragma unroll
+        for (int k = 0; k < kRowsPerWave; ++k)
+          if (open[k] && !passA[k]) all_ok = all_ok && !(wave_sum(gB[k]) < target[k]);
+      }
+      if (all_ok) {
+#pragma unroll
+        for (int k = 0; k < kRowsPerWave; ++k) {
+          if (open[k]) {
+            if (passA[k]) {
+              T[k] = kKeyA;
+              n_lo[k] = nA[k];
+            } else {
+              T[k] = kKeyB;
+              n_lo[k] = nB[k];
+              n_hi[k] = nA[k];
+              g_hi[k] = gA[k];
+            }
+            open[k] = n_lo[k] - n_hi[k] > 1;
+          }
+        }
+        first_bit = 25;
+      }
+    }
+    for (int bit = first_bit; bit >= 0; --bit) {
       bool any_open = false;
 #pragma unroll
       for (int k = 0; k < kRowsPerWave; ++k) any_open |= open[k];
@@ -653,14 +728,24 @@ __global__ __launch_bounds__(256) void row_count_kernel(const uint64_t* __restri
 // 4096 counts (4 consecutive counts per thread, so loads and stores are coalesced).
 __global__ __launch_bounds__(1024) void scan_kernel(int32_t* __restrict__ row_ptr, int R,
                                                     int64_t capacity, int32_t* __restrict__ info) {
-  __shared__ int wave_tot[16];
+  __shared__ int wave_tot[2][16];
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   int carry = 0;
-  for (int base = 0; base < R; base += 4096) {
+  // the counts of the next chunk are requested before the current one is scanned, so a chunk costs
+  // one scan and not one memory round trip
+  int nxt[4];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) nxt[k] = (t * 4 + k < R) ? row_ptr[1 + t * 4 + k] : 0;
+  int buf = 0;
+  for (int base = 0; base < R; base += 4096, buf ^= 1) {
     const int i0 = base + t * 4;
     int v[4];
 #pragma unroll
-    for (int k = 0; k < 4; ++k) v[k] = (i0 + k < R) ? row_ptr[1 + i0 + k] : 0;
+    for (int k = 0; k < 4; ++k) v[k] = nxt[k];
+    if (base + 4096 < R) {
+#pragma unroll
+      for (int k = 0; k < 4; ++k) nxt[k] = (i0 + 4096 + k < R) ? row_ptr[1 + i0 + 4096 + k] : 0;
+    }
     v[1] += v[0];
     v[2] += v[1];
     v[3] += v[2];
@@ -670,13 +755,13 @@ __global__ __launch_bounds__(1024) void scan_kernel(int32_t* __restrict__ row_pt
       const int y = __shfl_up(inc, off, 64);
       if (lane >= off) inc += y;
     }
-    if (lane == 63) wave_tot[wave] = inc;
-    __syncthreads();
+    if (lane == 63) wave_tot[buf][wave] = inc;
+    __syncthreads();                               // the other buffer is free: its readers passed this barrier a chunk ago
     int before = carry + inc - v[3];               // everything ahead of this thread's 4 counts
     int chunk_total = 0;
 #pragma unroll
     for (int w = 0; w < 16; ++w) {
-      const int wt = wave_tot[w];
+      const int wt = wave_tot[buf][w];
       if (w < wave) before += wt;
       chunk_total += wt;
     }
@@ -684,7 +769,6 @@ __global__ __launch_bounds__(1024) void scan_kernel(int32_t* __restrict__ row_pt
     for (int k = 0; k < 4; ++k)
       if (i0 + k < R) row_ptr[1 + i0 + k] = before + v[k];
     carry += chunk_total;
-    __syncthreads();                               // wave_tot is rewritten by the next chunk
   }
   if (t == 0) {
     row_ptr[0] = 0;
@@ -695,7 +779,8 @@ __global__ __launch_bounds__(1024) void scan_kernel(int32_t* __restrict__ row_pt
   }
 }
 
-// One wave per row: ascending columns of the set bits.
+// One wave per row: ascending columns of the set bits.  Lane i fetches word i of the row (one
+// request for the whole row; W <= 32), the words are then taken from registers.
 __global__ __launch_bounds__(256) void fill_kernel(const uint64_t* __restrict__ mask_bits, int R,
                                                    int W, const int32_t* __restrict__ row_ptr,
                                                    int32_t* __restrict__ col_idx, int64_t capacity) {
@@ -703,8 +788,12 @@ __global__ __launch_bounds__(256) void fill_kernel(const uint64_t* __restrict__ 
   const int lane = threadIdx.x & 63;
   if (r >= R) return;
   int64_t base = row_ptr[r];
+  const uint64_t mine = lane < W ? mask_bits[(size_t)r * W + lane] : 0ull;
+  const int lo = (int)(uint32_t)mine, hi = (int)(uint32_t)(mine >> 32);
   for (int i = 0; i < W; ++i) {
-    const uint64_t word = mask_bits[(size_t)r * W + i];
+    const uint64_t word = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane(hi, i) << 32) |
+                          (uint64_t)(uint32_t)__builtin_amdgcn_readlane(lo, i);
+    if (word == 0ull) continue;                      // uniform
     const int rank = __popcll(word & ((1ull << lane) - 1ull));
     if (((word >> lane) & 1ull) && base + rank < capacity) col_idx[base + rank] = i * 64 + lane;
     base += __popcll(word);
