@@ -446,7 +446,9 @@ def main() -> int:
     # measured here.  The no-reuse bytes (K and V^T tile per listed block, Q in, O out) are kept
     # beside it as the algorithmic figure; rows that share tiles are served by the L2s.
     w64 = (B == 128 and L % 128 == 0)
-    attn_kernel = "sparse_attn_w64_kernel" if w64 else f"sparse_attn_kernel<{B}, false>"
+    pair = (B == 64 and N % 2 == 0 and h * N >= 4096)       # two q-blocks per workgroup (pair kernel)
+    attn_kernel = ("sparse_attn_w64_kernel" if w64 else
+                   f"sparse_attn_kernel<{B}, false, {d}, {'true' if pair else 'false'}>")
     attn_key = "sparse_attn_w64_kernel" if w64 else "sparse_attn_kernel"
     attn_traffic, attn_src = profiled_traffic(w.name, attn_key)
     attn_bytes = nnz * 2 * B * d * 2 + 2 * Qb.nbytes

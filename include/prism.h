@@ -54,8 +54,12 @@ typedef enum prism_status {
 #define PRISM_FLAG_FORCE_DIAGONAL 4u   /* extra, not in the paper: block u of row u is always selected */
 #define PRISM_FLAG_FORCE_SINK     8u   /* extra, not in the paper: block 0 is always selected */
 #define PRISM_FLAG_GENERAL_KERNEL 0x20000000u /* measurement aid for prism_sparse_attn(_pre): always
-                                          use the general attention kernel (32 queries per wave), also
-                                          where the 64-queries-per-wave kernel would take the call */
+                                          use the general attention kernel (32 queries per wave, one
+                                          q-block per workgroup), also where the 64-queries-per-wave
+                                          kernel (B = 128) or the pair kernel (B = 64) would take the call */
+#define PRISM_FLAG_PAIR_KERNEL 0x10000000u /* measurement and test aid for prism_sparse_attn(_pre) at B = 64:
+                                          use the pair kernel wherever the shape allows it (an even number
+                                          of blocks), also for problems too small for it to pay */
 #define PRISM_FLAG_STREAM_ONLY 0x40000000u /* measurement aid for prism_sparse_attn(_pre): run the
                                           kernel's K / V^T tile copies, waits and scheduling without
                                           its arithmetic; the outputs are then meaningless.  Shows how

@@ -23,6 +23,7 @@ PRISM_FLAG_NO_CALIBRATION = 1
 PRISM_FLAG_BIDIRECTIONAL = 2
 PRISM_FLAG_FORCE_DIAGONAL = 4
 PRISM_FLAG_FORCE_SINK = 8
+PRISM_FLAG_PAIR_KERNEL = 0x10000000
 PRISM_FLAG_GENERAL_KERNEL = 0x20000000
 PRISM_FLAG_STREAM_ONLY = 0x40000000
 PRISM_MAX_SEGMENTS = 8

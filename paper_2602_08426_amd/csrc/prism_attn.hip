@@ -99,13 +99,16 @@ __global__ __launch_bounds__(256) void vt_image_kernel(const uint16_t* __restric
 // of the last step of the current row and reads that row's queue entry during the last PV, so
 // a row switch exposes only the load of the Q rows and of the first K tile.
 // =====================================================================================
-template <int BLK, int D>
+// PAIR: a workgroup serves two neighbouring q-blocks of one q-head (twice the waves) and walks the
+// union of their two lists, so a tile that both list is copied once.
+template <int BLK, int D, bool PAIR = false>
 struct AttnCfg {
-  static constexpr int kWaves = BLK / 32;
+  static constexpr int kRowWaves = BLK / 32;                // waves of one q-block
+  static constexpr int kWaves = kRowWaves * (PAIR ? 2 : 1);
   static constexpr int kThreads = kWaves * 64;
   static constexpr int kTileBytes = BLK * D * 2;
   static constexpr int kChunks = kTileBytes / 16;          // 16-byte pieces per tile
-  static constexpr int kPerThread = kChunks / kThreads;    // = D / 16
+  static constexpr int kPerThread = kChunks / kThreads;    // = D / 16 (D / 32 with PAIR)
   static constexpr int kKCpr = D / 8;                      // chunks per K row
   static constexpr int kVtCpr = BLK / 8;                   // chunks per V^T row
   static constexpr int kDTiles = D / 32;                   // 32-dim tiles of the output
@@ -149,10 +152,10 @@ __device__ __forceinline__ int vt_piece_offset(int p) {
   return row * (BLK * 2) + (((p % C::kVtCpr) ^ (row & (C::kVtCpr - 1))) << 4);
 }
 
-template <int BLK, int D>
+template <int BLK, int D, bool PAIR>
 __device__ __forceinline__ void async_load_k_tile(__amdgpu_buffer_rsrc_t rs, int tile_off, char* lds,
                                                   int t) {
-  using C = AttnCfg<BLK, D>;
+  using C = AttnCfg<BLK, D, PAIR>;
   // wave-uniform LDS base, re-materialised here so that the per-piece M0 values are formed
   // with scalar adds instead of being kept live (and spilled) across the whole loop
   int wave_base = __builtin_amdgcn_readfirstlane(t & ~63);
@@ -163,10 +166,10 @@ __device__ __forceinline__ void async_load_k_tile(__amdgpu_buffer_rsrc_t rs, int
                                              k_piece_offset<BLK, D>(i * C::kThreads + t), tile_off, 0, 0);
 }
 
-template <int BLK, int D>
+template <int BLK, int D, bool PAIR>
 __device__ __forceinline__ void async_load_vt_tile(__amdgpu_buffer_rsrc_t rs, int tile_off, char* lds,
                                                    int t) {
-  using C = AttnCfg<BLK, D>;
+  using C = AttnCfg<BLK, D, PAIR>;
   int wave_base = __builtin_amdgcn_readfirstlane(t & ~63);
   asm volatile("" : "+s"(wave_base));
 #pragma unroll
@@ -239,17 +242,27 @@ __device__ __forceinline__ int item_kind(int pulled, int seg_start, int seg_len,
 
 // kStreamOnly (PRISM_FLAG_STREAM_ONLY): the same tile copies, waits, barriers and queue traffic
 // with the arithmetic left out; it measures how long the memory side of a call takes alone.
-template <int BLK, bool kStreamOnly, int D>
-__global__ __launch_bounds__((AttnCfg<BLK, D>::kThreads), (AttnCfg<BLK, D>::kWavesPerSimd)) void sparse_attn_kernel(
+// kPair (B = 64, an even number of blocks, every list ascending and clean): items and plan describe PAIR
+// rows (q-blocks 2u' and 2u' + 1 of a head, whose two lists lie one behind the other in col_idx); the
+// workgroup walks the union of the two lists in ascending order, copies every tile of the union once,
+// and the waves of a q-block compute only in the steps whose block their own list names.  `dirty_flag`
+// is the flag word the list check wrote: the pair kernel returns at once when it is set, the plain
+// kernel launched behind it (only_dirty) returns at once when it is not.
+template <int BLK, bool kStreamOnly, int D, bool kPair>
+__global__ __launch_bounds__((AttnCfg<BLK, D, kPair>::kThreads), (AttnCfg<BLK, D, kPair>::kWavesPerSimd)) void sparse_attn_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ vt,
-    const int32_t* __restrict__ col_idx, const int4* __restrict__ items, int32_t* __restrict__ plan,
+    const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx, const int4* __restrict__ items,
+    int32_t* __restrict__ plan, const int32_t* __restrict__ dirty_flag,
     uint16_t* __restrict__ out, float* __restrict__ lse, int h, int h_kv, int L, int N,
     HeadStrides hs, int causal, int only_dirty) {
 #if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the kernel's signature
-  using C = AttnCfg<BLK, D>;
+  using C = AttnCfg<BLK, D, kPair>;
   constexpr int KS = C::kKSteps, DT = C::kDTiles;
-  // launched behind the 64-queries-per-wave kernel: only lists that kernel does not take
-  if (only_dirty && (plan[kPlanFlags] & kFlagDirtyLists) == 0) return;
+  if (kPair) {
+    if ((dirty_flag[0] & kFlagDirtyLists) != 0) return;     // the plain kernel takes this call
+  } else if (only_dirty && (dirty_flag[0] & kFlagDirtyLists) == 0) {
+    return;                                                 // the kernel launched in front of this one took it
+  }
   constexpr int KT = BLK / 32;                       // 32-key tiles per kv block
   __shared__ __attribute__((aligned(16))) char lds_k[C::kTileBytes];
   __shared__ __attribute__((aligned(16))) char lds_v[C::kTileBytes];
@@ -258,6 +271,8 @@ __global__ __launch_bounds__((AttnCfg<BLK, D>::kThreads), (AttnCfg<BLK, D>::kWav
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int l32 = lane & 31, hf = lane >> 5;
   const int g = h / h_kv;
+  // which of the two q-blocks of a pair row this wave belongs to (wave-uniform)
+  const int sub = kPair ? __builtin_amdgcn_readfirstlane(wave / C::kRowWaves) : 0;
   // log2(e) / sqrt(d)
   const float sm_scale = 1.4426950408889634f * (D == 64 ? 0.125f : (D == 128 ? 0.08838834764831845f : 0.0625f));
 
@@ -358,7 +373,9 @@ __global__ __launch_bounds__((AttnCfg<BLK, D>::kThreads), (AttnCfg<BLK, D>::kWav
     const int end = cur_w;
     const bool has_work = kind_cur == kItemRow && it < end;
     const int kvh = hq / g;
-    const int qrow = u * BLK + wave * 32 + l32;       // >= L for the padding rows of a ragged last block
+    // `u` is the index of the row among the head's rows: a q-block, or a pair of them
+    const int qrow = u * (C::kWaves * 32) + wave * 32 + l32;   // >= L for the padding rows of a ragged last block
+    const int u_own = kPair ? 2 * u + sub : u;                 // the q-block this wave's queries belong to
     int kind_nxt = kItemEnd;
 
     if (!has_work) {
@@ -386,7 +403,42 @@ __global__ __launch_bounds__((AttnCfg<BLK, D>::kThreads), (AttnCfg<BLK, D>::kWav
     // read as zeros.  The V^T image is padded to whole blocks.
     const __amdgpu_buffer_rsrc_t krs = make_rsrc(k + (size_t)kvh * hs.kv, head_bytes);
     const __amdgpu_buffer_rsrc_t vrs = make_rsrc(vt + (size_t)kvh * N * BLK * D, image_head_bytes);
-    const int vmax = causal ? u : vmax_nc;
+    const int vmax = causal ? u_own : vmax_nc;
+
+    // Pair rows: the two lists [it, mid) and [mid, end) are walked together, smallest block first;
+    // `act` says whose list names the block (bit 0: q-block 2u, bit 1: q-block 2u + 1).  The heads of
+    // both lists are fetched one step before they are looked at.
+    constexpr int kNoEntry = 0x7fffffff;
+    int mid = 0, ia = 0, ib = 0, act = 0, act_next = 0;
+    int ca_raw = 0, cb_raw = 0;                       // heads of the two lists as loaded (looked at a step later)
+    bool active = true;                               // this wave computes in the current step
+    auto pair_advance = [&](int* vout, int* actout) __attribute__((always_inline)) {
+      // precondition: ia < mid or ib < end
+      const int ca = ia < mid ? __builtin_amdgcn_readfirstlane(ca_raw) : kNoEntry;
+      const int cb = ib < end ? __builtin_amdgcn_readfirstlane(cb_raw) : kNoEntry;
+      const int vv = ca < cb ? ca : cb;
+      const int aa = (ca == vv ? 1 : 0) | (cb == vv ? 2 : 0);
+      if (aa & 1) {
+        ++ia;
+        if (ia < mid) ca_raw = col_idx[ia];
+      }
+      if (aa & 2) {
+        ++ib;
+        if (ib < end) cb_raw = col_idx[ib];
+      }
+      *vout = vv;
+      *actout = aa;
+    };
+    if (kPair) {
+      mid = __builtin_amdgcn_readfirstlane(row_ptr[(size_t)hq * N + 2 * u + 1]);
+      mid = mid < it ? it : (mid > end ? end : mid);
+      ia = it;
+      ib = mid;
+      if (ia < mid) ca_raw = col_idx[ia];
+      if (ib < end) cb_raw = col_idx[ib];
+      pair_advance(&v, &act);                          // has_work: at least one entry
+      active = ((act >> sub) & 1) != 0;
+    }
 
     // Q fragments (B operand of S^T = K Q^T): query row 32*wave + l32, dims 16*ks + 8*hf ..+7
     bf16x8 qf[KS];
@@ -395,7 +447,7 @@ __global__ __launch_bounds__((AttnCfg<BLK, D>::kThreads), (AttnCfg<BLK, D>::kWav
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16);
     }
-    async_load_k_tile<BLK, D>(krs, v * C::kTileBytes, lds_k, t);
+    async_load_k_tile<BLK, D, kPair>(krs, v * C::kTileBytes, lds_k, t);
     wait_async_loads();
     tile_barrier();
 
@@ -415,10 +467,10 @@ __global__ __launch_bounds__((AttnCfg<BLK, D>::kThreads), (AttnCfg<BLK, D>::kWav
       if (kLast && t == 0) pulled_reg = atomicAdd(counter + my_queue, 1);
 
       // ---- V(j) -> LDS, in flight during S^T and the softmax ----
-      async_load_vt_tile<BLK, D>(vrs, v * C::kTileBytes, lds_v, t);
+      async_load_vt_tile<BLK, D, kPair>(vrs, v * C::kTileBytes, lds_v, t);
 
       f32x16 sacc[KT];
-      if (!kStreamOnly) {
+      if (!kStreamOnly && active) {
       // ---- S^T = K Q^T ----
       // Flat software pipeline over the KT*KS (tile, k-step) pairs: the LDS read of step
       // i + kDepth is issued right after the MFMA of step i, in source order.
@@ -448,13 +500,13 @@ __global__ __launch_bounds__((AttnCfg<BLK, D>::kThreads), (AttnCfg<BLK, D>::kWav
 
       // every wave is done reading K(j): K(j+1) can start now and land during softmax + PV
       tile_barrier();
-      if (!kLast) async_load_k_tile<BLK, D>(krs, v_next * C::kTileBytes, lds_k, t);
+      if (!kLast) async_load_k_tile<BLK, D, kPair>(krs, v_next * C::kTileBytes, lds_k, t);
 
       bf16x8 pf[KT][2];
-      if (!kStreamOnly) {
+      if (!kStreamOnly && active) {
       // ---- causal mask inside the diagonal block ----
-      if (causal && v == u) {
-        const int qloc = wave * 32 + l32;
+      if (causal && v == u_own) {
+        const int qloc = (wave % C::kRowWaves) * 32 + l32;
 #pragma unroll
         for (int kt = 0; kt < KT; ++kt)
 #pragma unroll
@@ -534,7 +586,7 @@ __global__ __launch_bounds__((AttnCfg<BLK, D>::kThreads), (AttnCfg<BLK, D>::kWav
         if (kind_nxt == kItemRow) item_nxt = items[e_nxt + lane_zero];
       }
 
-      if (!kStreamOnly) {
+      if (!kStreamOnly && active) {
       // ---- O^T += V^T P^T ----  (same flat pipeline over the DT*KT*2 (d-tile, k-step) pairs)
       {
         constexpr int kPer = KT * 2;                   // k-steps per d-tile
@@ -566,6 +618,17 @@ __global__ __launch_bounds__((AttnCfg<BLK, D>::kThreads), (AttnCfg<BLK, D>::kWav
     // The list is walked one entry ahead of its use: col_idx[it + 1] is requested here and
     // before the MFMA phases of every block, and read only after the waits that end the block,
     // so the latency of the index load is never on the critical path of a block.
+    if (kPair) {
+      for (;;) {
+        if (ia >= mid && ib >= end) break;
+        pair_advance(&v_next, &act_next);
+        step(std::false_type{});
+        v = v_next;
+        act = act_next;
+        active = ((act >> sub) & 1) != 0;
+      }
+      step(std::true_type{});
+    } else {
     int ahead = it + 1 < end ? col_idx[it + 1] : -1;
     for (;;) {
       // next valid entry (v_next <= vmax): normally the entry fetched one block ago; entries
@@ -587,6 +650,7 @@ __global__ __launch_bounds__((AttnCfg<BLK, D>::kThreads), (AttnCfg<BLK, D>::kWav
       v = v_next;
     }
     step(std::true_type{});
+    }
 
     // ---- epilogue: O = O^T / l, bf16, [q][d] ----
     const float l_tot = other_half_sum(l_run);
@@ -738,9 +802,10 @@ __global__ __launch_bounds__(128) void sparse_attn_w64_kernel(
 }
 
 // One wave per row: does the row's list hold an entry the attention kernels must skip?
+// With need_sorted (the pair kernel merges two lists) a list that is not strictly ascending counts too.
 __global__ __launch_bounds__(256) void queue_validate_kernel(const int32_t* __restrict__ row_ptr,
                                                              const int32_t* __restrict__ col_idx, int h,
-                                                             int N, int cap, int causal,
+                                                             int N, int cap, int causal, int need_sorted,
                                                              const int32_t* __restrict__ range_flags,
                                                              int n_range_flags, int32_t* __restrict__ plan) {
   const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -758,6 +823,7 @@ __global__ __launch_bounds__(256) void queue_validate_kernel(const int32_t* __re
   for (int i = b + lane; i < e; i += 64) {
     const int v = col_idx[i];
     bad |= v < 0 || v > vmax;
+    if (need_sorted && i + 1 < e) bad |= col_idx[i + 1] <= v;
   }
   if (__ballot(bad) != 0ull && lane == 0) atomicOr(plan + kPlanFlags, kFlagDirtyLists);
 }
@@ -779,8 +845,10 @@ __global__ __launch_bounds__(256) void queue_validate_kernel(const int32_t* __re
 //       and the number of rows of every (group, part).
 //   queue_fill_kernel   (one thread per row): the row's position in its queue and its entry.
 // =====================================================================================
+// N = rows per head: q-blocks, or pairs of q-blocks (stride = 2: row r of the plan covers the two
+// consecutive lists of q-blocks 2r and 2r + 1 of the index lists).
 struct PlanCfg {
-  int h, g, N, heads_per_phase, n_phases, n_queues, cap, causal;
+  int h, g, N, heads_per_phase, n_phases, n_queues, cap, causal, stride;
 };
 constexpr int kClasses = 11;
 constexpr int kMaxGroups = 512;           // (phase, class) groups held in LDS by queue_fill_kernel
@@ -793,9 +861,9 @@ __device__ __forceinline__ int length_class(int len) {
 }
 
 // list bounds of row r clamped to [0, cap] (and end >= begin)
-__device__ __forceinline__ void row_bounds(const int32_t* __restrict__ row_ptr, int r, int cap, int* beg,
-                                           int* end) {
-  int b = row_ptr[r], e = row_ptr[r + 1];
+__device__ __forceinline__ void row_bounds(const int32_t* __restrict__ row_ptr, int r, int cap, int stride,
+                                           int* beg, int* end) {
+  int b = row_ptr[(size_t)r * stride], e = row_ptr[(size_t)r * stride + stride];
   b = b < 0 ? 0 : (b > cap ? cap : b);
   e = e < b ? b : (e > cap ? cap : e);
   *beg = b;
@@ -818,7 +886,7 @@ __global__ __launch_bounds__(256) void queue_count_kernel(const int32_t* __restr
   __syncthreads();
   for (int u = t; u < c.N; u += 256) {
     int beg, end;
-    row_bounds(row_ptr, hq * c.N + u, c.cap, &beg, &end);
+    row_bounds(row_ptr, hq * c.N + u, c.cap, c.stride, &beg, &end);
     const int cls = length_class(end - beg);
     atomicAdd(&s_rows[cls], 1);
     atomicAdd(&s_work[cls], end - beg + 1);
@@ -874,7 +942,7 @@ __global__ __launch_bounds__(256) void queue_rank_kernel(const int32_t* __restri
     const int i = t * per + j;
     if (i >= c.N) break;
     int beg, end;
-    row_bounds(row_ptr, hq * c.N + (c.N - 1 - i), c.cap, &beg, &end);
+    row_bounds(row_ptr, hq * c.N + (c.N - 1 - i), c.cap, c.stride, &beg, &end);
     const int cls = length_class(end - beg);
     const long long add = ((long long)(end - beg + 1) << 16) + 1;
 #pragma unroll
@@ -902,7 +970,7 @@ __global__ __launch_bounds__(256) void queue_rank_kernel(const int32_t* __restri
     if (i >= c.N) break;
     const int r = hq * c.N + (c.N - 1 - i);
     int beg, end;
-    row_bounds(row_ptr, r, c.cap, &beg, &end);
+    row_bounds(row_ptr, r, c.cap, c.stride, &beg, &end);
     const int cls = length_class(end - beg);
     const long long add = ((long long)(end - beg + 1) << 16) + 1;
     long long upto = 0;                              // this row included
@@ -978,15 +1046,17 @@ __global__ __launch_bounds__(256) void queue_fill_kernel(const int32_t* __restri
   for (int y = 0; y < x; ++y) in_earlier_parts += s_parts[(gp & ~7) + y];
   const int entry = s_start[x] + s_before[gp] + row_rank[r] - in_earlier_parts;
   int beg, end;
-  row_bounds(row_ptr, r, c.cap, &beg, &end);
+  row_bounds(row_ptr, r, c.cap, c.stride, &beg, &end);
   const int vmax = c.causal ? u : c.N - 1;
   int it = beg, v = 0;
-  while (it < end) {
-    v = col_idx[it];
-    if (v >= 0 && v <= vmax) break;
-    ++it;
-  }
-  if (it >= end) v = 0;
+  if (c.stride == 1) {
+    while (it < end) {
+      v = col_idx[it];
+      if (v >= 0 && v <= vmax) break;
+      ++it;
+    }
+    if (it >= end) v = 0;
+  }                                                  // pair rows: clean lists, the kernel finds its first block
   if (entry >= 0 && entry < c.h * c.N) items[entry] = make_int4(hq, u | (v << 16), it, end);
 }
 
@@ -997,12 +1067,15 @@ using namespace prism;
 // ---- workspace layout: [ V image | items[h*N] (queue entries) | row_rank[h*N] | row_part[h*N] |
 //                            bins[2*h*kClasses] | parts[h_kv*kClasses*8] | plan[24] ] ----
 struct AttnWs {
-  size_t image, items, row_rank, row_part, bins, parts, plan, image16, range_flags, total;
+  size_t image, items, row_rank, row_part, bins, parts, plan, image16, range_flags, pair_items, pair_plan, total;
 };
 // the fp16 image exists where the 64-queries-per-wave kernel can take the call
 static bool w64_shape(const prism_params* p) {
   return p->block == 128 && p->head_dim == kHeadDim && p->seq_len % 128 == 0;
 }
+
+// B = 64 with an even number of blocks: a second plan over pairs of q-blocks for the pair kernel
+static bool pair_shape(const prism_params* p) { return p->block == 64 && n_blocks(p) % 2 == 0; }
 
 static AttnWs attn_ws(const prism_params* p) {
   const size_t N = n_blocks(p);
@@ -1023,6 +1096,13 @@ static AttnWs attn_ws(const prism_params* p) {
     off = align_up(off + image_bytes, 256);
     w.range_flags = off;
     off = align_up(off + (size_t)p->n_kv_heads * N * sizeof(int32_t), 256);
+  }
+  w.pair_items = off;
+  w.pair_plan = off;
+  if (pair_shape(p)) {
+    off = align_up(off + rows / 2 * sizeof(int4), 256);
+    w.pair_plan = off;
+    off = align_up(off + kPlanInts * sizeof(int32_t), 256);
   }
   w.total = off;
   return w;
@@ -1113,12 +1193,26 @@ extern "C" int prism_v_image(const prism_params* params, const void* v_bf16, voi
                       static_cast<hipStream_t>(stream));
 }
 
-template <int BLK, bool kStreamOnly, int D>
+template <int BLK, bool kStreamOnly, int D, bool kPair = false>
 static void launch_attn(int grid, hipStream_t st, const uint16_t* q, const uint16_t* k, const uint16_t* vt,
-                        const int32_t* col_idx, const int4* items, int32_t* plan, uint16_t* out, float* lse,
-                        int h, int h_kv, int L, int N, const HeadStrides& hs, int causal, int only_dirty) {
-  hipLaunchKernelGGL((sparse_attn_kernel<BLK, kStreamOnly, D>), dim3(grid), dim3(AttnCfg<BLK, D>::kThreads), 0, st,
-                     q, k, vt, col_idx, items, plan, out, lse, h, h_kv, L, N, hs, causal, only_dirty);
+                        const int32_t* row_ptr, const int32_t* col_idx, const int4* items, int32_t* plan,
+                        const int32_t* dirty_flag, uint16_t* out, float* lse, int h, int h_kv, int L, int N,
+                        const HeadStrides& hs, int causal, int only_dirty) {
+  hipLaunchKernelGGL((sparse_attn_kernel<BLK, kStreamOnly, D, kPair>), dim3(grid),
+                     dim3(AttnCfg<BLK, D, kPair>::kThreads), 0, st, q, k, vt, row_ptr, col_idx, items, plan,
+                     dirty_flag, out, lse, h, h_kv, L, N, hs, causal, only_dirty);
+}
+
+// the three kernels that turn index lists into the queue plan of `pc`
+static void build_plan(const PlanCfg& pc, const int32_t* row_ptr, const int32_t* col_idx, int32_t* bins,
+                       int32_t* parts, int32_t* row_rank, int32_t* row_part, int32_t* plan, int4* items,
+                       hipStream_t st) {
+  const int R = pc.h * pc.N;
+  hipLaunchKernelGGL(queue_count_kernel, dim3(pc.h), dim3(256), 0, st, row_ptr, pc, bins, parts, plan);
+  hipLaunchKernelGGL(queue_rank_kernel, dim3(pc.h), dim3(256), 0, st, row_ptr, pc, bins, parts, row_rank,
+                     row_part);
+  hipLaunchKernelGGL(queue_fill_kernel, dim3((R + 255) / 256), dim3(256), 0, st, row_ptr, col_idx, pc,
+                     parts, row_rank, row_part, plan, items);
 }
 
 // Queue build + attention kernels of one sequence (arguments already validated).
@@ -1161,12 +1255,8 @@ static int attn_core(const prism_params* params, const HeadStrides& hs, const vo
   }
   pc.cap = col_count > 0x7fffffff ? 0x7fffffff : (int)col_count;     // CSR offsets are int32
   pc.causal = (params->flags & PRISM_FLAG_BIDIRECTIONAL) ? 0 : 1;
-
-  hipLaunchKernelGGL(queue_count_kernel, dim3(h), dim3(256), 0, st, row_ptr, pc, bins, parts, plan);
-  hipLaunchKernelGGL(queue_rank_kernel, dim3(h), dim3(256), 0, st, row_ptr, pc, bins, parts, row_rank,
-                     row_part);
-  hipLaunchKernelGGL(queue_fill_kernel, dim3((R + 255) / 256), dim3(256), 0, st, row_ptr, col_idx, pc,
-                     parts, row_rank, row_part, plan, items);
+  pc.stride = 1;
+  build_plan(pc, row_ptr, col_idx, bins, parts, row_rank, row_part, plan, items, st);
   const int causal = pc.causal;
   const bool stream_only = (params->flags & PRISM_FLAG_STREAM_ONLY) != 0;
   const uint16_t* qp = (const uint16_t*)q_bf16;
@@ -1178,18 +1268,48 @@ static int attn_core(const prism_params* params, const HeadStrides& hs, const vo
   // the lists turn out to need it).
   const bool w64 = w64_shape(params) && !stream_only &&
                    !(params->flags & PRISM_FLAG_GENERAL_KERNEL);
-  const int only_dirty = w64 ? 1 : 0;
+  // B = 64 with an even number of blocks: the pair kernel (two q-blocks per workgroup sharing the tiles of
+  // the union of their lists) takes the call when every list is ascending and clean; decided on the
+  // device in the same way.
+  // Below kPairMinRows rows the call is short and launch-bound, and the second plan and the list check
+  // (four more launches) cost more than the shared tiles save (measured: 25 -> 42 us at 32 rows).
+  constexpr int kPairMinRows = 4096;
+  const bool pair = pair_shape(params) && !stream_only && !(params->flags & PRISM_FLAG_GENERAL_KERNEL) &&
+                    (R >= kPairMinRows || (params->flags & PRISM_FLAG_PAIR_KERNEL));
+  const int only_dirty = (w64 || pair) ? 1 : 0;
+  const int32_t* dirty_flag = plan + kPlanFlags;
+  if (pair) {
+    PlanCfg pp = pc;
+    pp.N = N / 2;
+    pp.stride = 2;
+    const int pair_grid = persistent_grid(h * pp.N, d > 128 ? 1 : 2);       // 4 waves and 2 * 64 * d * 2 bytes of LDS each
+    if (pair_grid <= 0) return PRISM_ERR_HIP;
+    pp.n_queues = pair_grid < kXcds ? 1 : kXcds;
+    int4* pair_items = reinterpret_cast<int4*>(ws + W.pair_items);
+    int32_t* pair_plan = reinterpret_cast<int32_t*>(ws + W.pair_plan);
+    build_plan(pp, row_ptr, col_idx, bins, parts, row_rank, row_part, pair_plan, pair_items, st);
+    hipLaunchKernelGGL(queue_validate_kernel, dim3((R + 3) / 4), dim3(256), 0, st, row_ptr, col_idx, h, N,
+                       pc.cap, causal, 1, static_cast<const int32_t*>(nullptr), 0, plan);
+#define PRISM_PAIR(D)                                                                                        \
+  launch_attn<64, false, D, true>(pair_grid, st, qp, kp, vp, row_ptr, col_idx, pair_items, pair_plan, dirty_flag, \
+                                  op, lse, h, h_kv, L, N, hs, causal, 0)
+    if (d == 64) PRISM_PAIR(64);
+    else if (d == 128) PRISM_PAIR(128);
+    else PRISM_PAIR(256);
+#undef PRISM_PAIR
+  }
   if (w64) {
     const int n_range_flags = h_kv * N;
     const int vgrid = ((R + 3) / 4) > ((n_range_flags + 255) / 256) ? (R + 3) / 4 : (n_range_flags + 255) / 256;
     hipLaunchKernelGGL(queue_validate_kernel, dim3(vgrid), dim3(256), 0, st, row_ptr, col_idx, h, N,
-                       pc.cap, causal, reinterpret_cast<const int32_t*>(ws + W.range_flags), n_range_flags, plan);
+                       pc.cap, causal, 0, reinterpret_cast<const int32_t*>(ws + W.range_flags), n_range_flags, plan);
     hipLaunchKernelGGL(sparse_attn_w64_kernel, dim3(grid), dim3(128), 0, st, qp, kp,
                        reinterpret_cast<const uint16_t*>(ws + W.image16), col_idx, items, plan, op, lse, h, h_kv,
                        L, N, hs, causal);
   }
-#define PRISM_ATTN(BLK, SO, D) \
-  launch_attn<BLK, SO, D>(grid, st, qp, kp, vp, col_idx, items, plan, op, lse, h, h_kv, L, N, hs, causal, only_dirty)
+#define PRISM_ATTN(BLK, SO, D)                                                                                \
+  launch_attn<BLK, SO, D>(grid, st, qp, kp, vp, row_ptr, col_idx, items, plan, dirty_flag, op, lse, h, h_kv, L, N, \
+                          hs, causal, only_dirty)
   if (stream_only) {
     // measurement aid of the d = 128 kernels only
     if (d != 128) return PRISM_ERR_UNSUPPORTED;

@@ -184,7 +184,8 @@ def test_attention_is_deterministic_across_runs():
 
 # (workload, rows compared with the oracle: None = every row, flags of the attention call)
 FULL = [("c3_llama_32k", None, 0), ("c3_llama_32k", None, pb.PRISM_FLAG_GENERAL_KERNEL),
-        ("c5_qwen_64k", None, 0), ("c4_llama_128k", 1200, 0), ("c4_llama_128k_b64", 1200, 0)]
+        ("c5_qwen_64k", None, 0), ("c4_llama_128k", 1200, 0), ("c4_llama_128k_b64", 1200, 0),
+        ("c4_llama_128k_b64", 1200, pb.PRISM_FLAG_GENERAL_KERNEL)]
 
 
 def _queue_tables(image, w):
@@ -350,7 +351,9 @@ def test_fuzz_random_lists_and_values(seed):
     rp_d, ci_d, cnt = gu.csr_to_device(rp, ci)
     qd, kd, vd = _dev(Qb, Kb, Vb)
     Q, K64, V = orc.bf16_to_f64(Qb), orc.bf16_to_f64(Kb), orc.bf16_to_f64(Vb)
-    for flags in (0, pb.PRISM_FLAG_GENERAL_KERNEL):
+    # default dispatch, the general kernel, and (B = 64) the pair kernel, which a problem this small would
+    # not get by itself; with entries to skip the pair kernel hands the call to the general one
+    for flags in (0, pb.PRISM_FLAG_GENERAL_KERNEL, pb.PRISM_FLAG_PAIR_KERNEL):
         params = pb.make_params(h, hkv, L, B, flags=flags)
         out, lse = gu.gpu_sparse_attn(params, qd, kd, vd, rp_d, ci_d, cnt)
         _compare_rows(params, out, lse, Q, K64, V, mask, None)
@@ -389,3 +392,57 @@ def test_scores_that_jump_far_above_the_running_max(jump):
             kv = hq // 2
             hot_k = 6 * B + 77 if kv == 0 else 5 * B + 3
             assert np.abs(o[hq, tok] - V64[kv, hot_k]).max() <= OUT_TOL
+
+
+@pytest.mark.parametrize("h,hkv,L,d,bidir,seed", [
+    (4, 2, 64 * 14, 128, False, 21),
+    (2, 1, 64 * 22 - 37, 128, False, 22),      # ragged last block (the second q-block of the last pair)
+    (7, 1, 64 * 10, 128, False, 23),           # group of 7
+    (4, 2, 64 * 12, 64, False, 24),
+    (2, 2, 64 * 10, 256, False, 25),
+    (4, 2, 64 * 16, 128, True, 26),            # bidirectional lists
+])
+def test_pair_kernel_at_block_64(h, hkv, L, d, bidir, seed):
+    """B = 64, even block count, forced through the pair kernel (two q-blocks per workgroup walking the
+    union of their lists): rows whose partner is empty, rows sharing nothing, rows sharing everything,
+    against the oracle and against the plain kernel."""
+    print(f"case h={h}/{hkv} L={L} d={d} bidirectional={bidir}", flush=True)
+    rng = np.random.default_rng(seed)
+    B = 64
+    N = -(-L // B)
+    Qb = wl.f32_to_bf16_bits(rng.standard_normal((h, L, d)).astype(np.float32) * 1.3)
+    Kb = wl.f32_to_bf16_bits(rng.standard_normal((hkv, L, d)).astype(np.float32) * 1.3)
+    Vb = wl.f32_to_bf16_bits(rng.standard_normal((hkv, L, d)).astype(np.float32))
+    dens = rng.choice([0.15, 0.5, 1.0], size=h)
+    mask = rng.random((h, N, N)) < dens[:, None, None]
+    if not bidir:
+        mask = np.tril(mask)
+    mask[:, 4, :] = False                              # q-block 4 empty, its partner 5 is not
+    mask[:, 5, 0] = True
+    mask[0, 6] = mask[0, 7] = False                    # an empty pair
+    mask[1 % h, 8] = False
+    mask[1 % h, 9] = False
+    mask[1 % h, 8, [0, 2]] = True                      # disjoint lists
+    mask[1 % h, 9, [1, 3]] = True
+    rp, ci = orc.mask_to_csr(mask)
+    rp_d, ci_d, cnt = gu.csr_to_device(rp, ci)
+    qd, kd, vd = _dev(Qb, Kb, Vb)
+    Q, K, V = orc.bf16_to_f64(Qb), orc.bf16_to_f64(Kb), orc.bf16_to_f64(Vb)
+    base = pb.PRISM_FLAG_BIDIRECTIONAL if bidir else 0
+    outs = {}
+    for name, fl in (("pair", pb.PRISM_FLAG_PAIR_KERNEL), ("plain", pb.PRISM_FLAG_GENERAL_KERNEL)):
+        params = pb.make_params(h, hkv, L, B, flags=base | fl, head_dim=d)
+        out, lse = gu.gpu_sparse_attn(params, qd, kd, vd, rp_d, ci_d, cnt)
+        o, l = gu.bf16_out_to_f64(out), lse.cpu().numpy().astype(np.float64)
+        assert not np.isnan(o).any() and not np.isnan(l).any()
+        ref = orc.block_sparse_attention(Q, K, V, mask, B, None, causal=not bidir)
+        for (hq, u), (ro, rl) in ref.items():
+            sl = slice(u * B, u * B + ro.shape[0])
+            assert np.abs(o[hq, sl] - ro).max() <= OUT_TOL, (name, hq, u)
+            fin = np.isfinite(rl)
+            assert (np.abs(l[hq, sl][fin] - rl[fin]) <= LSE_TOL).all(), (name, hq, u)
+            assert (l[hq, sl][~fin] == -np.inf).all(), (name, hq, u)
+        outs[name] = (o, l)
+    # same arithmetic per query in both kernels: the results agree to the last bit
+    assert np.array_equal(outs["pair"][0], outs["plain"][0])
+    assert np.array_equal(outs["pair"][1], outs["plain"][1])

@@ -51,6 +51,12 @@ def _layout(h, hkv, N, B, L=None):
         o = _align(o + hkv * N * B * 128 * 2)
         off["range_flags"] = o
         o = _align(o + hkv * N * 4)
+    if B == 64 and N % 2 == 0:
+        # an even number of 64-token blocks: a second plan over pairs of q-blocks (pair kernel)
+        off["pair_items"] = o
+        o = _align(o + rows // 2 * 16)
+        off["pair_plan"] = o
+        o = _align(o + 32 * 4)
     off["total"] = o
     return off
 
@@ -159,3 +165,52 @@ def test_every_row_is_queued_once_and_the_queues_are_balanced(h, hkv, L, B, bidi
         # a part boundary can be off by one row per (phase, class) group
         slack = (lens.max() + 1) * N_CLASSES * max(1, -(-hkv // hpp))
         assert work.max() - work.min() <= slack, (work, slack)
+
+
+@pytest.mark.parametrize("h,hkv,N,dirty", [(4, 2, 40, False), (8, 2, 300, False), (4, 2, 40, True)])
+def test_pair_plan_at_block_64(h, hkv, N, dirty):
+    """B = 64 with an even number of blocks: the pair kernel's plan holds every pair of q-blocks once,
+    its queues are pulled past their ends when the lists are clean, and not at all when a list holds an
+    entry to skip (then the plain kernel takes the call and its plan is the one that is used up)."""
+    rng = np.random.default_rng(5 + N)
+    B, L = 64, 64 * N
+    params = pb.make_params(h, hkv, L, B, flags=pb.PRISM_FLAG_PAIR_KERNEL)
+    lay = _layout(h, hkv, N, B, L)
+    assert pb.prism_sparse_attn_workspace_bytes(params) == lay["total"]
+    lists = []
+    for hq in range(h):
+        for u in range(N):
+            n = rng.binomial(u + 1, [0.05, 0.3, 0.8, 0.15][hq % 4])
+            lists.append(np.sort(rng.choice(u + 1, size=n, replace=False)).astype(np.int32))
+    if dirty:
+        lists[h * N // 2] = np.array([N + 3], np.int32)
+    lens = np.array([len(c) for c in lists])
+    row_ptr = np.zeros(h * N + 1, np.int32)
+    row_ptr[1:] = np.cumsum(lens)
+    col_idx = np.concatenate(lists + [np.zeros(1, np.int32)]).astype(np.int32)
+    q = torch.zeros((h, L, 128), dtype=torch.bfloat16, device="cuda")
+    k = torch.zeros((hkv, L, 128), dtype=torch.bfloat16, device="cuda")
+    v = torch.zeros((hkv, L, 128), dtype=torch.bfloat16, device="cuda")
+    out = torch.empty_like(q)
+    ws = pb.alloc_workspace(lay["total"])
+    pb.prism_sparse_attn(params, q, k, v, torch.from_numpy(row_ptr).cuda(), torch.from_numpy(col_idx).cuda(),
+                         int(row_ptr[-1]), out, None, ws)
+    torch.cuda.synchronize()
+    raw = ws.cpu().numpy()
+    rows = h * N // 2
+    items = raw[lay["pair_items"]:lay["pair_items"] + rows * 16].view(np.int32).reshape(rows, 4)
+    pplan = raw[lay["pair_plan"]:lay["pair_plan"] + 96].view(np.int32)
+    plan = raw[lay["plan"]:lay["plan"] + 128].view(np.int32)
+    start, length, pulled = pplan[0:8], pplan[8:16], pplan[16:24]
+    assert length.sum() == rows
+    np.testing.assert_array_equal(start, np.cumsum(length) - length)
+    hq, up = items[:, 0], items[:, 1] & 0xFFFF
+    assert len(np.unique(hq * (N // 2) + up)) == rows
+    r0 = hq * N + 2 * up
+    np.testing.assert_array_equal(items[:, 2], row_ptr[r0])
+    np.testing.assert_array_equal(items[:, 3], row_ptr[r0 + 2])
+    assert plan[24] == (1 if dirty else 0)
+    if dirty:
+        assert (pulled == 0).all() and (plan[16:24] >= plan[8:16]).all()
+    else:
+        assert (pulled >= length).all() and (plan[16:24] == 0).all()
