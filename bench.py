@@ -449,7 +449,7 @@ def main() -> int:
     pair = (B == 64 and N % 2 == 0 and h * N >= 4096)       # two q-blocks per workgroup (pair kernel)
     attn_kernel = ("sparse_attn_w64_kernel" if w64 else
                    f"sparse_attn_kernel<{B}, false, {d}, {'true' if pair else 'false'}>")
-    attn_key = "sparse_attn_w64_kernel" if w64 else "sparse_attn_kernel"
+    attn_key = "sparse_attn_w64_kernel" if w64 else ("sparse_attn_kernel_pair" if pair else "sparse_attn_kernel")
     attn_traffic, attn_src = profiled_traffic(w.name, attn_key)
     attn_bytes = nnz * 2 * B * d * 2 + 2 * Qb.nbytes
     attn_gbs = None if attn_traffic is None else attn_traffic / (ms_attn * 1e-3) / 1e9
