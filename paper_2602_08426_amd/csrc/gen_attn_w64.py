@@ -237,7 +237,7 @@ def mfma_stream(groups, kbuf, vbuf, depth=6):
 
 def softmax_ops(p, qt, tag):
     """VALU work of softmax(j) for query tile qt on bank p.  Values of the tile live in the two
-    accumulators (kt = 0, 1); P is written in place as bf16 pairs."""
+    accumulators (kt = 0, 1); P is written in place as fp16 pairs."""
     ops = []
     regs = [SB(p, kt, qt) + r for kt in range(2) for r in range(16)]
     t_mx, t_mc, t_a, t_b = V_T + 8 * qt, V_T + 8 * qt + 1, V_T + 8 * qt + 2, V_T + 8 * qt + 3
@@ -267,7 +267,7 @@ def softmax_ops(p, qt, tag):
     ops.append(valu(f"v_exp_f32 v{t_b}, v{t_b}", vr(t_b), vr(t_b), "trans"))
     ops.append(valu(f"v_cndmask_b32 v{m}, v{m}, v{t_mc}, s[{fl}:{fl + 1}]", vr(m) + vr(t_mc) + [("s", fl)], vr(m)))
     ops.append(valu(f"v_cndmask_b32 v{al}, 1.0, v{t_b}, s[{fl}:{fl + 1}]", vr(t_b) + [("s", fl)], vr(al)))
-    # --- p = 2^(s * scale - m), in place; sums in two chains; bf16 pairs in place
+    # --- p = 2^(s * scale - m), in place; sums in two chains; fp16 pairs in place
     first = [True, True]
     pend = []                                   # exps issued, not yet added / packed
     def flush_one():
