@@ -95,6 +95,7 @@ S_LSE = 74              # 2: lse row base (0 = not requested)
 S_QB = 76               # 2
 S_OB = 78               # 2
 S_VBYTES = 92           # bytes of the V^T image of one kv head (records of the V^T resource)
+S_CNT = 94              # 2: address of the pull counter of this workgroup's queue
 S_MK = 88               # 2: LDS address of this wave's part of Kbuf[0], Kbuf[1]
 S_MV = 90               # 2: ... of Vbuf[0], Vbuf[1]
 
@@ -589,10 +590,28 @@ def iteration(p, hh, do_pv, do_s, incoming, uid, sequential=False):
     return ops
 
 
+def pull_next_row():
+    """Lane 0 of wave 0 takes the workgroup's next position in its queue (returning atomic add on the
+    queue's pull counter); the answer travels while the last PV and the epilogue run and is handed
+    to the C++ loop in the asm block's output operand.  Pulling only now, when the row is almost
+    done, keeps the rows that an XCD's workgroups work on at any time neighbours in the queue, i.e.
+    neighbouring q-blocks of one head, whose lists share tiles in the L2."""
+    T = V_T
+    return [salu(f"s_cmp_lg_u32 s{S_WAVE}, 0"),
+            salu("s_cbranch_scc1 Lnopull"),
+            salu(f"s_mov_b64 s[{S_TMP}:{S_TMP + 1}], exec"),
+            salu("s_mov_b64 exec, 1"),
+            valu(f"v_mov_b32 v{T + 29}, 1", (), vr(T + 29)),
+            Ins(f"global_atomic_add v{T + 28}, v{V_ZERO}, v{T + 29}, s[{S_CNT}:{S_CNT + 1}] sc0", "vmem",
+                vr(V_ZERO) + vr(T + 29), vr(T + 28)),
+            salu(f"s_mov_b64 exec, s[{S_TMP}:{S_TMP + 1}]"),
+            Ins("Lnopull:", "label")]
+
+
 def drain(p_bank):
     """PV of the last half-step (its P is in bank p_bank, its V^T half in Vbuf[p_bank])."""
     pre, slots = mfma_stream(pv_ops(p_bank), p_bank, p_bank)
-    ops = rescale_block("Lnoresc_drain") + pre
+    ops = pull_next_row() + rescale_block("Lnoresc_drain") + pre
     for s in slots:
         ops += s
     ops += [nop(7), nop(7), nop(7)]
@@ -628,6 +647,7 @@ def prologue(inp):
     a(salu(f"s_mov_b32 s{S_HAVE_O}, 0"))
     a(salu(f"s_mov_b64 s[{S_FLAG}:{S_FLAG + 1}], 0"))
     a(salu(f"s_mov_b64 s[{S_FLAG + 2}:{S_FLAG + 3}], 0"))
+    a(salu(f"s_mov_b64 s[{S_CNT}:{S_CNT + 1}], {inp['cnt']}"))
     a(salu(f"s_mov_b32 s{S_KBYTES}, {inp['kbytes']}"))
     a(salu(f"s_mov_b32 s{S_VBYTES}, {inp['vbytes']}"))
     for rs, ptr, nbytes in ((S_KRS, inp["k"], inp["kbytes"]), (S_VRS, inp["vt"], inp["vbytes"])):
@@ -950,7 +970,7 @@ def skipped_view(ops):
         if ins.kind == "salu" and ins.text.startswith("s_cbranch_"):
             target = ins.text.split()[1]
             later = any(o.kind == "label" and o.text == target + ":" for o in ops[i + 1:i + 1200])
-            if later and target.startswith(("Lnomask", "Lnoresc", "Lnok", "Lnolse")):
+            if later and target.startswith(("Lnomask", "Lnoresc", "Lnok", "Lnolse", "Lnopull")):
                 skip_to = target
     return keep
 
@@ -984,13 +1004,15 @@ def fix_hazards(ops):
 INP = {}          # operand names of the inline-asm inputs, filled by emit()
 
 
-INPUTS = ["t", "q", "o", "lse", "k", "vt", "col", "n", "u", "causal", "lds", "kbytes", "vbytes", "c0"]
+INPUTS = ["t", "q", "o", "lse", "k", "vt", "col", "n", "u", "causal", "lds", "kbytes", "vbytes", "c0", "cnt"]
 
 
 def emit(path, sequential=False):
-    inp = {name: f"%{i}" for i, name in enumerate(INPUTS)}
+    inp = {name: f"%{i + 1}" for i, name in enumerate(INPUTS)}      # %0 is the output operand
     INP.update(inp)
     ops = fix_hazards(row_program(inp, sequential))
+    # the queue position pulled for the next row (valid in lane 0 of wave 0)
+    ops.append(valu(f"v_mov_b32 %0, v{V_T + 28}", vr(V_T + 28), ()))
     problems = all_hazards(ops)
     if problems:
         for p in problems[:20]:
@@ -998,15 +1020,16 @@ def emit(path, sequential=False):
         raise SystemExit(f"{len(problems)} hazard(s) in the generated schedule")
     clob_v = [f"v{i}" for i in range(32, 256)]
     clob_a = [f"a{i}" for i in range(0, 256)]
-    clob_s = [f"s{i}" for i in range(40, 94)]
+    clob_s = [f"s{i}" for i in range(40, 96)]
     with open(path, "w") as f:
         f.write("// generated by gen_attn_w64.py -- do not edit\n")
         f.write("asm volatile(\n")
         for ins in ops:
             f.write(f'    "{ins.text}\\n\\t"\n')
-        f.write("    :\n")
+        f.write('    : "=&v"(pulled_next)\n')
         f.write('    : "v"(t), "s"(q_row), "s"(o_row), "s"(lse_row), "s"(k_head), "s"(vt_head), "s"(col_row),\n')
-        f.write('      "s"(n_entries), "s"(u), "s"(causal), "s"(lds_base), "s"(k_bytes), "s"(vt_bytes), "s"(c_first)\n')
+        f.write('      "s"(n_entries), "s"(u), "s"(causal), "s"(lds_base), "s"(k_bytes), "s"(vt_bytes), "s"(c_first),\n')
+        f.write('      "s"(pull_counter)\n')
         clob = ", ".join(f'"{c}"' for c in clob_v + clob_a + clob_s + ["vcc", "scc", "memory"])
         f.write(f"    : {clob});\n")
     n_mfma = sum(1 for i in ops if i.kind == "mfma")

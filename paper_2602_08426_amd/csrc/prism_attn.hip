@@ -774,8 +774,9 @@ __global__ __launch_bounds__(128) void sparse_attn_w64_kernel(
     const int c_first = (__builtin_amdgcn_readfirstlane(it0.y) >> 16) & 0xffff;   // first listed block
     const int it = __builtin_amdgcn_readfirstlane(it0.z);
     const int end = __builtin_amdgcn_readfirstlane(it0.w);
-    // the next row's queue position is pulled now and looked at after this row
-    if (t == 0) pulled = atomicAdd(counter + my_queue, 1);
+    // The next row's queue position is pulled when this row is almost done (inside the row loop, at
+    // the start of its last PV phase) and looked at after it: pulling at the start of a row would
+    // reserve a row that its neighbours in the queue have long passed by the time it is started.
 
     const size_t tok0 = (size_t)u * 128 + (size_t)wave * 64;                    // this wave's first query
     const size_t row0 = (size_t)hq * hs.q + tok0 * kHeadDim;                     // its element offset in Q / O
@@ -786,6 +787,7 @@ __global__ __launch_bounds__(128) void sparse_attn_w64_kernel(
 #pragma unroll
       for (int c = 0; c < 16; ++c) *reinterpret_cast<uint4*>(op + c * 8) = make_uint4(0u, 0u, 0u, 0u);
       if (lse != nullptr) lse[(size_t)hq * hs.lse + tok0 + r] = -INFINITY;
+      if (t == 0) pulled = atomicAdd(counter + my_queue, 1);
       continue;
     }
     const uint16_t* q_row = q + row0;
@@ -796,7 +798,10 @@ __global__ __launch_bounds__(128) void sparse_attn_w64_kernel(
     const uint16_t* vt_head = vt + (size_t)kvh * N * 128 * kHeadDim;
     const int32_t* col_row = col_idx + it;
     const int n_entries = end - it;
+    int32_t* pull_counter = counter + my_queue;
+    int pulled_next;
 #include "prism_attn_w64_body.inc"
+    if (t == 0) pulled = pulled_next;
   }
 #endif
 }
