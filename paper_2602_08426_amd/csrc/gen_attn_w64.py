@@ -64,7 +64,8 @@ V_M = 60                # 2 regs: running max (log2 units) per query tile
 V_L = 62                # 2 regs: this lane's share of the running sum
 V_T = 224               # 32 temporaries v[224:255]:
 #   T+0..5 / T+8..13 softmax of query tile 0 / 1;  T+16..25 prologue / epilogue;  T+26,27 mask
-#   thresholds;  T+28,29 debug dump;  T+30 list offset;  T+31 -inf
+#   thresholds;  T+28 pulled queue position, T+29 its increment (drain .. end of row; the debug dump
+#   borrows both);  T+30 list offset;  T+31 -inf
 V_ALPHA = V_T + 6       # 2 regs: rescale factor decided by the last softmax
 V_IDX = V_T + 14        # 1 reg : list entry loaded two blocks ahead
 V_ZERO = V_T + 15       # 1 reg : 0
