@@ -1278,9 +1278,12 @@ static int attn_core(const prism_params* params, const HeadStrides& hs, const vo
   // device in the same way.
   // Below kPairMinRows rows the call is short and launch-bound, and the second plan and the list check
   // (four more launches) cost more than the shared tiles save (measured: 25 -> 42 us at 32 rows).
+  // At d = 64 a tile is 8 KB and the plain kernel is not bound by its copies: the pair form is 5 % slower
+  // even on all-ones lists, where the two lists of a pair coincide (750 -> 712 TFLOP/s at 16K tokens;
+  // d = 128: 948 -> 993, d = 256: 438 -> 753).
   constexpr int kPairMinRows = 4096;
   const bool pair = pair_shape(params) && !stream_only && !(params->flags & PRISM_FLAG_GENERAL_KERNEL) &&
-                    (R >= kPairMinRows || (params->flags & PRISM_FLAG_PAIR_KERNEL));
+                    ((R >= kPairMinRows && d >= 128) || (params->flags & PRISM_FLAG_PAIR_KERNEL));
   const int only_dirty = (w64 || pair) ? 1 : 0;
   const int32_t* dirty_flag = plan + kPlanFlags;
   if (pair) {
