@@ -54,11 +54,17 @@ def build_library(verbose: bool = False, extra_flags: list[str] | None = None) -
     return _compile(SOURCES, LIB_PATH, verbose, extra_flags)
 
 
+SELECT_ABLATION_BITS = {"select_noscores": 1, "select_nosearch": 2, "select_norefetch": 4}
+
+
 def build_ablation(experiment: str, out_path: str, verbose: bool = False) -> str:
-    """A measurement-only variant of libprism.so whose 64-queries-per-wave row loop leaves parts out
-    (PRISM_W64_EXPERIMENT of gen_attn_w64.py: "nosoft", "nocopy", "nowait", "nobar_mid", "nobar_end";
-    results are wrong by construction, control flow and bounds are unchanged).  The generated loop and
-    the library go to the given path; the product library is not touched."""
+    """A measurement-only variant of libprism.so that leaves parts out; results are wrong by construction,
+    control flow and bounds are unchanged.  `experiment` is a space-separated list of
+      nosoft nocopy nowait nobar_mid nobar_end   parts of the 64-queries-per-wave attention row loop
+                                                 (PRISM_W64_EXPERIMENT of gen_attn_w64.py),
+      select_noscores select_nosearch select_norefetch   parts of the selection kernel
+                                                 (PRISM_SELECT_ABLATION of prism_estimate.hip).
+    The generated loop and the library go to the given path; the product library is not touched."""
     import shutil
     import tempfile
     with tempfile.TemporaryDirectory() as tmp:
@@ -71,7 +77,8 @@ def build_ablation(experiment: str, out_path: str, verbose: bool = False) -> str
         if gen.returncode != 0:
             raise RuntimeError(f"gen_attn_w64.py failed:\n{gen.stderr}")
         hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-        cmd = [hipcc, *HIPCC_FLAGS, "-I", os.path.join(ROOT, "include"), "-I", tmp,
+        bits = sum(SELECT_ABLATION_BITS.get(tok, 0) for tok in experiment.split())
+        cmd = [hipcc, *HIPCC_FLAGS, f"-DPRISM_SELECT_ABLATION={bits}", "-I", os.path.join(ROOT, "include"), "-I", tmp,
                *[os.path.join(tmp, s) for s in SOURCES], "-o", out_path]
         if verbose:
             print(" ".join(cmd), flush=True)

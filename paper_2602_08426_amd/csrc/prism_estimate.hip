@@ -559,6 +559,17 @@ __device__ __forceinline__ void select_rows(const float* __restrict__ logits, in
   }
 }
 
+// Measurement builds only (python -m paper_2602_08426_amd.build --ablation "select_..." out.so): parts of
+// select_kernel left out to see what they cost.  Grid, LDS and control flow stay as they are, the masks
+// are wrong by construction.  The conditions are written against a run-time value (top_p is at most 1)
+// so that the code around the part left out is not optimised away with it.
+#ifndef PRISM_SELECT_ABLATION
+#define PRISM_SELECT_ABLATION 0
+#endif
+constexpr bool kAblNoScores = (PRISM_SELECT_ABLATION & 1) != 0;      // no score MFMAs, no LDS strip
+constexpr bool kAblNoSearch = (PRISM_SELECT_ABLATION & 2) != 0;      // no softmax / top-p search
+constexpr bool kAblNoRefetch = (PRISM_SELECT_ABLATION & 4) != 0;     // pooled-K fragments fetched for a wave's first tile only
+
 // select_flags
 constexpr int kSelCausal = 1;          // key blocks v > u are excluded (block-causal estimation)
 constexpr int kSelForceDiagonal = 2;   // block u of every row is switched on after the union
@@ -633,7 +644,7 @@ __global__ __launch_bounds__(kStripRows / kRowsPerWave * 64) void select_kernel(
         }
       };
       if (wave < ntiles) load_b(wave);
-      for (int ct = wave; ct < ntiles; ct += kWaves) {
+      for (int ct = wave; ct < ntiles && (!kAblNoScores || top_p > 5.f); ct += kWaves) {
         f32x4 acc = {0.f, 0.f, 0.f, 0.f};
         bf16x8 ch[4], cm[4], cl[4];
 #pragma unroll
@@ -642,7 +653,7 @@ __global__ __launch_bounds__(kStripRows / kRowsPerWave * 64) void select_kernel(
           cm[ks] = bm[ks];
           cl[ks] = bl[ks];
         }
-        if (ct + kWaves < ntiles) load_b(ct + kWaves);
+        if (ct + kWaves < ntiles && (!kAblNoRefetch || top_p > 5.f)) load_b(ct + kWaves);
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
           if (ks < kn) {
@@ -677,7 +688,7 @@ __global__ __launch_bounds__(kStripRows / kRowsPerWave * 64) void select_kernel(
     if (!DUMP) {
       const int r0 = wave * kRowsPerWave;
       const int nrows = min(kRowsPerWave, N - (u0 + r0));          // uniform per wave, may be <= 0
-      if (nrows > 0) {
+      if (nrows > 0 && (!kAblNoSearch || top_p > 5.f)) {
         const int n0 = causal ? u0 + r0 + 1 : N;                   // columns of the first row
         const int nstep = causal ? 1 : 0;
         const int nmax = n0 + (nrows - 1) * nstep;
