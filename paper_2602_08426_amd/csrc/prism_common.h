@@ -109,18 +109,18 @@ __device__ __forceinline__ double wave_sum(double x) {
   for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off, 64);
   return x;
 }
-__device__ __forceinline__ uint32_t wave_min_u32(uint32_t x) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) {
-    const uint32_t y = (uint32_t)__shfl_xor((int)x, off, 64);
-    x = y < x ? y : x;
-  }
-  return x;
+template <int CTRL, int ROW_MASK = 0xF>
+__device__ __forceinline__ int dpp_i32(int old, int x) {
+  return __builtin_amdgcn_update_dpp(old, x, CTRL, ROW_MASK, 0xF, false);
 }
 __device__ __forceinline__ int wave_sum(int x) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off, 64);
-  return x;
+  x += dpp_i32<kDppQuadSwap1>(0, x);
+  x += dpp_i32<kDppQuadSwap2>(0, x);
+  x += dpp_i32<kDppRowHalfMirror>(0, x);
+  x += dpp_i32<kDppRowMirror>(0, x);
+  x += dpp_i32<kDppRowBcast15, 0xA>(0, x);
+  x += dpp_i32<kDppRowBcast31, 0xC>(0, x);
+  return __builtin_amdgcn_readlane(x, 63);
 }
 
 __device__ __forceinline__ float bf16_bits_to_float(uint32_t b) { return __uint_as_float(b << 16); }

@@ -9,6 +9,7 @@
 #include "prism_common.h"
 
 #include <mutex>
+#include <utility>
 
 namespace prism {
 
@@ -314,11 +315,25 @@ constexpr int kStripRows = 16;
 // (dependent DPP chains) overlap.  Selected bits are OR-ed into the rows' LDS bit words.
 // rows per wave: 4 (workgroup of 4 waves) or 2 (8 waves: twice the waves in flight for the same LDS strip)
 
-// lane `i` of (lo, hi) := the wave-uniform 64-bit word w
-__device__ __forceinline__ void put_word(uint64_t w, int i, int lane, int& lo, int& hi) {
-  const bool mine = lane == i;
-  lo = mine ? (int)(uint32_t)w : lo;
-  hi = mine ? (int)(uint32_t)(w >> 32) : hi;
+// lane I of (lo, hi) := the wave-uniform 64-bit word w.  Two lane writes with the lane number as an
+// immediate: no per-lane predicate has to be formed or kept.  The s_nop gives the compare that wrote w
+// its two wait states before a vector instruction reads the mask as a scalar source.
+template <int I>
+__device__ __forceinline__ void put_word(uint64_t w, int& lo, int& hi) {
+  const int wl = (int)(uint32_t)w, wh = (int)(uint32_t)(w >> 32);
+  asm("s_nop 1\n\tv_writelane_b32 %0, %2, %4\n\tv_writelane_b32 %1, %3, %4"
+      : "+v"(lo), "+v"(hi)
+      : "s"(wl), "s"(wh), "n"(I));
+}
+
+// f(std::integral_constant<int, 0>{}), ..., f(std::integral_constant<int, N - 1>{})
+template <typename F, int... Is>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, Is...>) {
+  (f(std::integral_constant<int, Is>{}), ...);
+}
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  static_for_impl(f, std::make_integer_sequence<int, N>{});
 }
 
 template <int NCH, int kRowsPerWave>
@@ -338,10 +353,11 @@ __device__ __forceinline__ void select_rows(const float* __restrict__ logits, in
       mx = fmaxf(mx, e[k][i]);
     }
     mx = wave_max(mx);
+    mx = mx == -INFINITY ? 0.f : mx;                 // a row without columns
     float part = 0.f;
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
-      e[k][i] = (e[k][i] == -INFINITY) ? 0.f : __expf(e[k][i] - mx);   // softmax numerators, max one = 1
+      e[k][i] = __expf(e[k][i] - mx);                // softmax numerators, max one = 1; columns past the end: exp(-inf) = 0
       part += e[k][i];
     }
     total[k] = wave_sum(part);
@@ -349,7 +365,7 @@ __device__ __forceinline__ void select_rows(const float* __restrict__ logits, in
   }
   const bool all = top_p >= 1.0f;
 
-  uint32_t tstar[kRowsPerWave];
+  uint32_t tstar[kRowsPerWave];                      // T* (rows with equal elements at the cut), else T
   float gstar[kRowsPerWave];
   bool one_tie[kRowsPerWave];                        // exactly one element has the key T*
 #pragma unroll
@@ -377,11 +393,10 @@ __device__ __forceinline__ void select_rows(const float* __restrict__ logits, in
       T[k] = 0;
       n_hi[k] = 0;
       g_hi[k] = 0.f;
-      int n = 0;
-#pragma unroll
-      for (int i = 0; i < NCH; ++i) n += __popcll(__builtin_amdgcn_ballot_w64(__float_as_uint(e[k][i]) > 0u));
-      n_lo[k] = n;
-      open[k] = n > 1;
+      // Elements above key 0: the row's length when it is 0 or 1 (its one element is exp(0) = 1).  Longer
+      // rows get their count from the fixed-key passes below, or are counted when those do not settle it.
+      n_lo[k] = k < nrows ? n0 + k * nstep : 0;
+      open[k] = n_lo[k] > 1;
     }
     // The cut of a row lies within a few octaves of its largest element (= 1): two passes at fixed
     // keys stand for the first four or five of the search.  The mass above a key does not grow with
@@ -456,6 +471,17 @@ __device__ __forceinline__ void select_rows(const float* __restrict__ logits, in
           }
         }
         first_bit = 25;
+      } else {
+#pragma unroll
+        for (int k = 0; k < kRowsPerWave; ++k) {
+          if (open[k]) {
+            int n = 0;
+#pragma unroll
+            for (int i = 0; i < NCH; ++i) n += __popcll(__builtin_amdgcn_ballot_w64(__float_as_uint(e[k][i]) > 0u));
+            n_lo[k] = n;
+            open[k] = n > 1;
+          }
+        }
       }
     }
     for (int bit = first_bit; bit >= 0; --bit) {
@@ -497,15 +523,9 @@ __device__ __forceinline__ void select_rows(const float* __restrict__ logits, in
 #pragma unroll
     for (int k = 0; k < kRowsPerWave; ++k) {
       if (n_lo[k] - n_hi[k] == 1) {
-        // the one element above T and not above the upper bound
-        uint32_t mn = 0xFFFFFFFFu;
-#pragma unroll
-        for (int i = 0; i < NCH; ++i) {
-          const uint32_t key = __float_as_uint(e[k][i]);
-          mn = key > T[k] ? min(mn, key) : mn;
-        }
-        tstar[k] = wave_min_u32(mn);
-        gstar[k] = g_hi[k];
+        // One element lies above T and not above the upper bound: it is T*, the mass above it (g_hi) is
+        // below the target, so it is selected, and with it exactly the elements above T.
+        tstar[k] = T[k];
         one_tie[k] = true;
       } else {
         // the search ran to the last bit (equal elements at the cut), or the row is empty
@@ -526,24 +546,23 @@ __device__ __forceinline__ void select_rows(const float* __restrict__ logits, in
     const int n = n0 + k * nstep;
     int word_lo = 0, word_hi = 0;
     if (all) {
-#pragma unroll
-      for (int i = 0; i < NCH; ++i) {
+      static_for<NCH>([&](auto ic) {
+        constexpr int i = decltype(ic)::value;
         const uint64_t bal = __builtin_amdgcn_ballot_w64(i * 64 + lane < n);
-        put_word(bal, i, lane, word_lo, word_hi);
-      }
+        put_word<i>(bal, word_lo, word_hi);
+      });
     } else if (one_tie[k]) {
-      // the mass above the one element at T* is < target, so it is selected: everything >= T*
-      // (columns past the row's end hold 0 < T*)
-#pragma unroll
-      for (int i = 0; i < NCH; ++i) {
-        const uint64_t bal = __builtin_amdgcn_ballot_w64(__float_as_uint(e[k][i]) >= tstar[k]);
-        put_word(bal, i, lane, word_lo, word_hi);
-      }
+      // everything above T (columns past the row's end hold 0)
+      static_for<NCH>([&](auto ic) {
+        constexpr int i = decltype(ic)::value;
+        const uint64_t bal = __builtin_amdgcn_ballot_w64(__float_as_uint(e[k][i]) > tstar[k]);
+        put_word<i>(bal, word_lo, word_hi);
+      });
     } else {
       const float tie_val = __uint_as_float(tstar[k]);
       int tie_base = 0;
-#pragma unroll
-      for (int i = 0; i < NCH; ++i) {
+      static_for<NCH>([&](auto ic) {
+        constexpr int i = decltype(ic)::value;
         const uint32_t key = __float_as_uint(e[k][i]);
         const bool tie = key == tstar[k];
         const uint64_t tb = __builtin_amdgcn_ballot_w64(tie);
@@ -551,8 +570,8 @@ __device__ __forceinline__ void select_rows(const float* __restrict__ logits, in
         const bool sel = (key > tstar[k]) || (tie && (gstar[k] + (float)rank * tie_val < target[k]));
         tie_base += __popcll(tb);
         const uint64_t bal = __builtin_amdgcn_ballot_w64(sel);
-        put_word(bal, i, lane, word_lo, word_hi);
-      }
+        put_word<i>(bal, word_lo, word_hi);
+      });
     }
     if (lane < NCH)
       bits[k * bits_ld + lane] |= ((uint64_t)(uint32_t)word_hi << 32) | (uint64_t)(uint32_t)word_lo;
@@ -689,7 +708,10 @@ __global__ __launch_bounds__(kStripRows / kRowsPerWave * 64) void select_kernel(
       const int r0 = wave * kRowsPerWave;
       const int nrows = min(kRowsPerWave, N - (u0 + r0));          // uniform per wave, may be <= 0
       if (nrows > 0 && (!kAblNoSearch || top_p > 5.f)) {
-        const int n0 = causal ? u0 + r0 + 1 : N;                   // columns of the first row
+        int n0 = causal ? u0 + r0 + 1 : N;                         // columns of the first row
+        // opaque to the optimiser: the per-column "inside the row" predicates are then formed where they
+        // are used, in each band, instead of being kept as 64 lane masks across both bands
+        asm volatile("" : "+s"(n0));
         const int nstep = causal ? 1 : 0;
         const int nmax = n0 + (nrows - 1) * nstep;
         const float* lg = lds_logits + r0 * ld;
