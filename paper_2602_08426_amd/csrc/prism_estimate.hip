@@ -9,6 +9,7 @@
 #include "prism_common.h"
 
 #include <mutex>
+#include <type_traits>
 #include <utility>
 
 namespace prism {
@@ -640,64 +641,90 @@ __global__ __launch_bounds__(kStripRows / kRowsPerWave * 64) void select_kernel(
       const bool first = k0 == 0, last = k0 + 4 >= ksteps;
       const int arow = min(u0 + (lane & 15), N - 1);
       const size_t aoff = ((size_t)hq * N + arow) * bs + k0 * 32 + (lane >> 4) * 8;
-      bf16x8 ah[4], am[4], al[4];
+      const size_t tile0 = kv_band_offset(h, N, bs, kvh - h, 0, 0) + k0 * 512 + lane * 8;   // this lane's piece of tile 0
+      const size_t tile_stride = (size_t)16 * bs;
+      // The pass with the number of k-steps and "first pass" as compile-time facts: a fixed number of
+      // loads per tile lets the compiler wait for exactly the fragments of the tile whose MFMAs come next
+      // while those of the tile after it stay in flight.  The B fragments alternate between two register
+      // sets; past the wave's last tile the last tile is fetched once more and not used.
+      auto score_pass = [&](auto kn_tag, auto first_tag) __attribute__((always_inline)) {
+        constexpr int KN = decltype(kn_tag)::value;
+        constexpr bool FIRST = decltype(first_tag)::value;
+        struct Frag {
+          bf16x8 h[KN], m[KN], l[KN];
+        };
+        Frag a;
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks) {
-        if (ks < kn) {
-          ah[ks] = *reinterpret_cast<const bf16x8*>(pooled_hi + aoff + ks * 32);
-          am[ks] = *reinterpret_cast<const bf16x8*>(pooled_mid + aoff + ks * 32);
-          al[ks] = *reinterpret_cast<const bf16x8*>(pooled_lo + aoff + ks * 32);
+        for (int ks = 0; ks < KN; ++ks) {
+          a.h[ks] = *reinterpret_cast<const bf16x8*>(pooled_hi + aoff + ks * 32);
+          a.m[ks] = *reinterpret_cast<const bf16x8*>(pooled_mid + aoff + ks * 32);
+          a.l[ks] = *reinterpret_cast<const bf16x8*>(pooled_lo + aoff + ks * 32);
         }
-      }
-      // B fragments of the next tile are fetched while the MFMAs of the current one run
-      bf16x8 bh[4], bm[4], bl[4];
-      auto load_b = [&](int ct) {
-        const size_t boff = kv_band_offset(h, N, bs, kvh - h, ct * 16, 0) + k0 * 512 + lane * 8;
+        auto load_b = [&](Frag& f, int ct) __attribute__((always_inline)) {
+          const size_t boff = tile0 + (size_t)min(ct, ntiles - 1) * tile_stride;
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-          if (ks < kn) {
-            bh[ks] = *reinterpret_cast<const bf16x8*>(pooled_hi + boff + ks * 512);
-            bm[ks] = *reinterpret_cast<const bf16x8*>(pooled_mid + boff + ks * 512);
-            bl[ks] = *reinterpret_cast<const bf16x8*>(pooled_lo + boff + ks * 512);
+          for (int ks = 0; ks < KN; ++ks) {
+            f.h[ks] = *reinterpret_cast<const bf16x8*>(pooled_hi + boff + ks * 512);
+            f.m[ks] = *reinterpret_cast<const bf16x8*>(pooled_mid + boff + ks * 512);
+            f.l[ks] = *reinterpret_cast<const bf16x8*>(pooled_lo + boff + ks * 512);
+          }
+        };
+        auto tile = [&](const Frag& c, int ct) __attribute__((always_inline)) {
+          f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int ks = 0; ks < KN; ++ks) {
+            // all cross terms down to 2^-24 relative, smallest first
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.l[ks], c.h[ks], acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.h[ks], c.l[ks], acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.m[ks], c.m[ks], acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.m[ks], c.h[ks], acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.h[ks], c.m[ks], acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.h[ks], c.h[ks], acc, 0, 0, 0);
+          }
+          const int col = ct * 16 + (lane & 15);
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const int row = (lane >> 4) * 4 + r;
+            float lg = acc[r] * inv;
+            if (!FIRST) lg += lds_logits[row * ld + col];
+            lds_logits[row * ld + col] = lg;
+            if (DUMP && last) {
+              const int u = u0 + row;
+              float* dst = z == 0 ? logits_high : logits_low;
+              if (dst != nullptr && u < N && col < N && (col <= u || !causal))
+                dst[((size_t)hq * N + u) * N + col] = lg;
+            }
+          }
+        };
+        const bool refetch = !kAblNoRefetch || top_p > 5.f;
+        Frag b0, b1;
+        load_b(b0, wave);
+        if (!refetch) load_b(b1, wave);
+        // (the scheduling barriers keep the fetches of the next tile in front of the MFMAs of this one;
+        // left to itself the scheduler sinks them to their first use to save registers)
+        for (int ct = wave; ct < ntiles; ct += 2 * kWaves) {
+          if (refetch) load_b(b1, ct + kWaves);
+          __builtin_amdgcn_sched_barrier(0);
+          tile(b0, ct);
+          __builtin_amdgcn_sched_barrier(0);
+          if (ct + kWaves < ntiles) {
+            if (refetch) load_b(b0, ct + 2 * kWaves);
+            __builtin_amdgcn_sched_barrier(0);
+            tile(b1, ct + kWaves);
+            __builtin_amdgcn_sched_barrier(0);
           }
         }
       };
-      if (wave < ntiles) load_b(wave);
-      for (int ct = wave; ct < ntiles && (!kAblNoScores || top_p > 5.f); ct += kWaves) {
-        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-        bf16x8 ch[4], cm[4], cl[4];
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-          ch[ks] = bh[ks];
-          cm[ks] = bm[ks];
-          cl[ks] = bl[ks];
-        }
-        if (ct + kWaves < ntiles && (!kAblNoRefetch || top_p > 5.f)) load_b(ct + kWaves);
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-          if (ks < kn) {
-            // all cross terms down to 2^-24 relative, smallest first
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al[ks], ch[ks], acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah[ks], cl[ks], acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(am[ks], cm[ks], acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(am[ks], ch[ks], acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah[ks], cm[ks], acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah[ks], ch[ks], acc, 0, 0, 0);
-          }
-        }
-        const int col = ct * 16 + (lane & 15);
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const int row = (lane >> 4) * 4 + r;
-          float lg = acc[r] * inv;
-          if (!first) lg += lds_logits[row * ld + col];
-          lds_logits[row * ld + col] = lg;
-          if (DUMP && last) {
-            const int u = u0 + row;
-            float* dst = z == 0 ? logits_high : logits_low;
-            if (dst != nullptr && u < N && col < N && (col <= u || !causal))
-              dst[((size_t)hq * N + u) * N + col] = lg;
-          }
+      if (wave < ntiles && (!kAblNoScores || top_p > 5.f)) {
+        auto pass = [&](auto kn_tag) __attribute__((always_inline)) {
+          if (first) score_pass(kn_tag, std::true_type{});
+          else score_pass(kn_tag, std::false_type{});
+        };
+        switch (kn) {                                  // uniform
+          case 1: pass(std::integral_constant<int, 1>{}); break;
+          case 2: pass(std::integral_constant<int, 2>{}); break;
+          case 3: pass(std::integral_constant<int, 3>{}); break;
+          default: pass(std::integral_constant<int, 4>{}); break;
         }
       }
     }
