@@ -256,12 +256,17 @@ __global__ __launch_bounds__(64) void scale_kernel(const float* __restrict__ ene
   const int hq = blockIdx.x, lane = threadIdx.x;
   const int kvh = h + hq / (h / h_kv);
   double eq[3] = {0, 0, 0}, ek[3] = {0, 0, 0};
+  // one 16-byte load per (head, block); several blocks in flight (the sums keep their order)
+#pragma unroll 4
   for (int i = lane; i < N; i += 64) {
-#pragma unroll
-    for (int z = 0; z < 3; ++z) {
-      eq[z] += (double)energy[((size_t)hq * N + i) * 4 + z];
-      ek[z] += (double)energy[((size_t)kvh * N + i) * 4 + z];
-    }
+    const float4 a = *reinterpret_cast<const float4*>(energy + ((size_t)hq * N + i) * 4);
+    const float4 b = *reinterpret_cast<const float4*>(energy + ((size_t)kvh * N + i) * 4);
+    eq[0] += (double)a.x;
+    eq[1] += (double)a.y;
+    eq[2] += (double)a.z;
+    ek[0] += (double)b.x;
+    ek[1] += (double)b.y;
+    ek[2] += (double)b.z;
   }
 #pragma unroll
   for (int z = 0; z < 3; ++z) {
