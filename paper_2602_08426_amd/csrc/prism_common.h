@@ -113,6 +113,19 @@ template <int CTRL, int ROW_MASK = 0xF>
 __device__ __forceinline__ int dpp_i32(int old, int x) {
   return __builtin_amdgcn_update_dpp(old, x, CTRL, ROW_MASK, 0xF, false);
 }
+// inclusive prefix sum over the 64 lanes on the DPP paths: shifts by 1, 2, 3 inside a row of 16 lanes
+// (a window of four), then by 4 and 8 for the banks they reach, then the row broadcasts
+__device__ __forceinline__ int wave_scan_inclusive(int x) {
+  int s = x;
+  s += dpp_i32<0x111>(0, x);                         // row_shr:1
+  s += dpp_i32<0x112>(0, x);                         // row_shr:2
+  s += dpp_i32<0x113>(0, x);                         // row_shr:3
+  s += __builtin_amdgcn_update_dpp(0, s, 0x114, 0xF, 0xE, false);   // row_shr:4, banks 1-3
+  s += __builtin_amdgcn_update_dpp(0, s, 0x118, 0xF, 0xC, false);   // row_shr:8, banks 2-3
+  s += dpp_i32<kDppRowBcast15, 0xA>(0, s);
+  s += dpp_i32<kDppRowBcast31, 0xC>(0, s);
+  return s;
+}
 __device__ __forceinline__ int wave_sum(int x) {
   x += dpp_i32<kDppQuadSwap1>(0, x);
   x += dpp_i32<kDppQuadSwap2>(0, x);

@@ -789,11 +789,79 @@ __global__ __launch_bounds__(256) void row_count_kernel(const uint64_t* __restri
 }
 
 // In-place: row_ptr[r+1] holds the count of row r on entry, the inclusive prefix sum on
-// exit; row_ptr[0] = 0.  Single workgroup of 1024 threads sweeping the array in chunks of
-// 4096 counts (4 consecutive counts per thread, so loads and stores are coalesced).
+// exit; row_ptr[0] = 0.  Single workgroup of 1024 threads; a chunk is 4096 counts, 4 consecutive ones
+// per thread, so loads and stores are coalesced.
+// Up to 16 chunks (65536 rows): every count is requested at once and held in registers, each wave scans
+// its part of every chunk, wave 0 scans the 16 x NC wave totals, and every thread adds the base of its
+// (chunk, wave): two barriers and one memory round trip in all.
+template <int NC>
+__device__ __forceinline__ void scan_resident(int32_t* __restrict__ row_ptr, int R, int64_t capacity,
+                                              int32_t* __restrict__ info, int* tot, int* base) {
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  int v[NC][4], inc[NC];
+#pragma unroll
+  for (int c = 0; c < NC; ++c) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int i = c * 4096 + t * 4 + k;
+      v[c][k] = i < R ? row_ptr[1 + i] : 0;
+    }
+  }
+#pragma unroll
+  for (int c = 0; c < NC; ++c) {
+    v[c][1] += v[c][0];
+    v[c][2] += v[c][1];
+    v[c][3] += v[c][2];
+    inc[c] = wave_scan_inclusive(v[c][3]);
+    if (lane == 63) tot[c * 16 + wave] = inc[c];
+  }
+  __syncthreads();
+  if (wave == 0) {
+    // lane l owns the totals 4l .. 4l + 3 of the (chunk, wave) order
+    int a[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) a[j] = lane * 4 + j < NC * 16 ? tot[lane * 4 + j] : 0;
+    a[1] += a[0];
+    a[2] += a[1];
+    a[3] += a[2];
+    const int incl = wave_scan_inclusive(a[3]);
+    const int before = incl - a[3];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      if (lane * 4 + j < NC * 16) base[lane * 4 + j] = before + (j > 0 ? a[j - 1] : 0);
+    if (lane == 63) {
+      row_ptr[0] = 0;
+      info[0] = incl;
+      info[1] = ((int64_t)incl > capacity) ? 1 : 0;
+      info[2] = 0;
+      info[3] = 0;
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int c = 0; c < NC; ++c) {
+    const int before = base[c * 16 + wave] + inc[c] - v[c][3];   // everything ahead of this thread's 4 counts
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int i = c * 4096 + t * 4 + k;
+      if (i < R) row_ptr[1 + i] = before + v[c][k];
+    }
+  }
+}
+
 __global__ __launch_bounds__(1024) void scan_kernel(int32_t* __restrict__ row_ptr, int R,
                                                     int64_t capacity, int32_t* __restrict__ info) {
-  __shared__ int wave_tot[2][16];
+  __shared__ int wave_tot[2][16 * 16];
+  const int chunks = (R + 4095) / 4096;              // uniform
+  if (chunks <= 16) {
+    if (chunks <= 1) scan_resident<1>(row_ptr, R, capacity, info, wave_tot[0], wave_tot[1]);
+    else if (chunks <= 2) scan_resident<2>(row_ptr, R, capacity, info, wave_tot[0], wave_tot[1]);
+    else if (chunks <= 4) scan_resident<4>(row_ptr, R, capacity, info, wave_tot[0], wave_tot[1]);
+    else if (chunks <= 8) scan_resident<8>(row_ptr, R, capacity, info, wave_tot[0], wave_tot[1]);
+    else scan_resident<16>(row_ptr, R, capacity, info, wave_tot[0], wave_tot[1]);
+    return;
+  }
+  // more rows than that: sweep chunk by chunk
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   int carry = 0;
   // the counts of the next chunk are requested before the current one is scanned, so a chunk costs
@@ -814,12 +882,7 @@ __global__ __launch_bounds__(1024) void scan_kernel(int32_t* __restrict__ row_pt
     v[1] += v[0];
     v[2] += v[1];
     v[3] += v[2];
-    int inc = v[3];
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-      const int y = __shfl_up(inc, off, 64);
-      if (lane >= off) inc += y;
-    }
+    const int inc = wave_scan_inclusive(v[3]);
     if (lane == 63) wave_tot[buf][wave] = inc;
     __syncthreads();                               // the other buffer is free: its readers passed this barrier a chunk ago
     int before = carry + inc - v[3];               // everything ahead of this thread's 4 counts

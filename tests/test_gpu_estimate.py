@@ -187,7 +187,11 @@ def test_capacity_overflow_is_flagged_not_written():
     assert (c[cap:] == -7).all()                         # nothing written past the capacity
 
 
-@pytest.mark.parametrize("h,N,B", [(3, 37, 128), (2, 130, 64), (1, 1, 128), (5, 64, 128)])
+@pytest.mark.parametrize("h,N,B", [(3, 37, 128), (2, 130, 64), (1, 1, 128), (5, 64, 128),
+                                   # h * N rows = 2, 4, 8, 16 chunks of the prefix scan held in registers,
+                                   # and more rows than that (chunk-by-chunk sweep)
+                                   (70, 64, 128), (200, 64, 128), (500, 64, 128), (1000, 64, 128),
+                                   (1100, 64, 128)])
 def test_mask_to_csr_and_causal_csr_exact(h, N, B):
     rng = np.random.default_rng(N)
     mask = np.tril(rng.random((h, N, N)) < 0.3)
